@@ -1,0 +1,150 @@
+/*
+ * tidal.h - C ABI of the MI355X (gfx950) decode-step attention library for
+ * TidalDecode (arxiv 2410.05076).
+ *
+ * One decode step of the paper's Alg. 1 runs, per Transformer layer, one of
+ * three attention kinds for the single new query of each sequence:
+ *   - full attention over the whole KV cache (Eq. 1; Alg. 1 "FullAttention"),
+ *   - full attention with token selection: the same, plus the inner products
+ *     <q,K> of every cached token kept on the fly and rho := argTopK(<q,K>, k)
+ *     (Sec. 3.1; Alg. 1 "Token Selection Layer"),
+ *   - position persistent sparse attention over the rows named by the latest
+ *     rho only (Sec. 3.1; Alg. 1 "SparseAttention(q, C[rho])").
+ * The entry points below are those three calls, the argTopK step on its own,
+ * and a driver that applies a layer schedule (Fig. 2: full attention in the
+ * first layers, selection at the next layer and one middle layer, sparse
+ * elsewhere).
+ *
+ * Conventions for every call
+ *   - All data pointers are DEVICE pointers unless a comment says HOST.  The
+ *     caller owns q, K, V, out, positions, seq_lens; the library owns only the
+ *     workspace inside td_ctx, never frees or reallocates caller memory, and
+ *     never synchronises the stream: kernels are enqueued on `hip_stream`
+ *     (a hipStream_t passed as void*, NULL = the null stream) and the call
+ *     returns.  No call other than td_create / td_destroy allocates or frees.
+ *   - q, out : [batch][num_q_heads][head_dim], contiguous, element type `dtype`.
+ *   - K, V   : element type `dtype`; element (b, g, j, c) of either lives at
+ *              b*kv_stride_batch + g*kv_stride_head + j*kv_stride_tok + c
+ *              (strides in elements, multiples of 8; head_dim contiguous).
+ *              Token j of sequence b is valid for 0 <= j < seq_lens[b]; the
+ *              cache already holds the current token (Alg. 1 appends first).
+ *     Pointers must be 16-byte aligned.
+ *   - Query head h reads KV head h / (num_q_heads / num_kv_heads).
+ *   - positions : int32 [batch][num_kv_heads][k], ascending token indices; if
+ *     k > seq_lens[b] only the first seq_lens[b] entries are tokens and the
+ *     rest are -1.  Sparse attention skips entries that are negative or
+ *     >= seq_lens[b]; a (sequence, KV head) with no valid entry yields zeros.
+ *   - Arithmetic: logits, softmax and accumulation in fp32; out is rounded to
+ *     `dtype` (round to nearest even for bf16).
+ *   - Grouped-query selection: the query heads that share a KV head share one
+ *     rho; the top-k is taken over the per-token sum of the group's scaled
+ *     logits (for num_q_heads == num_kv_heads this is the paper's per-head
+ *     argTopK).  Ties at the k-th value go to the smaller token index.
+ *   - Errors: argument errors are found on the host before anything is
+ *     enqueued and returned as TD_ERR_INVALID_ARG / TD_ERR_UNSUPPORTED /
+ *     TD_ERR_WORKSPACE; a failed HIP call gives TD_ERR_HIP.  td_last_error
+ *     returns a text for the most recent failure on that context.
+ *     Supported: head_dim 64 or 128, group size 1, 2, 4 or 8.
+ */
+#ifndef TIDAL_H
+#define TIDAL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TD_OK = 0,
+    TD_ERR_INVALID_ARG = 1,
+    TD_ERR_UNSUPPORTED = 2,
+    TD_ERR_WORKSPACE = 3,
+    TD_ERR_HIP = 4
+} td_status;
+
+typedef enum { TD_BF16 = 0, TD_F32 = 1 } td_dtype;
+
+/* Layer kinds of Alg. 1. */
+typedef enum { TD_LAYER_DENSE = 0, TD_LAYER_SELECT = 1, TD_LAYER_SPARSE = 2 } td_layer_kind;
+
+typedef struct td_shape {
+    int32_t batch;
+    int32_t num_q_heads;
+    int32_t num_kv_heads;      /* divides num_q_heads */
+    int32_t head_dim;          /* 64 or 128 */
+    int32_t dtype;             /* td_dtype of q, K, V, out */
+    float   sm_scale;          /* 0 => 1/sqrt(head_dim), the scaling of Eq. 1 */
+    int64_t kv_stride_batch;   /* elements */
+    int64_t kv_stride_head;
+    int64_t kv_stride_tok;
+    const int32_t *seq_lens;   /* DEVICE int32 [batch]; each in [1, max_seq_len] */
+    int32_t max_seq_len;       /* HOST-known upper bound; sizes grids and workspace */
+} td_shape;
+
+typedef struct td_ctx td_ctx;  /* opaque; owns the workspace (split partials, group scores) */
+
+/* Host-only check of a shape and budget; the same check every call makes first. */
+td_status td_validate(const td_shape *shape, int32_t k);
+
+/* Workspace bytes that any call with this shape and budget k (k <= 0: no
+ * selection or sparse call will be made) needs.  Returns 0 for an invalid shape. */
+size_t td_workspace_bytes(const td_shape *shape, int32_t k);
+
+/* Creates a context on HIP device `device` and allocates `workspace_bytes` of
+ * device memory once.  Synchronises the device. */
+td_status td_create(td_ctx **out, int device, size_t workspace_bytes);
+td_status td_destroy(td_ctx *ctx);
+
+/* FullAttention(q, C[:]) of Alg. 1 (Eq. 1 for one query row per head). */
+td_status td_full_attend(td_ctx *ctx, const td_shape *shape, const void *q, const void *K,
+                         const void *V, void *out, void *hip_stream);
+
+/* Token selection layer of Alg. 1: out as td_full_attend; positions receives
+ * rho.  group_scores (optional, may be NULL) receives the fp32 per-token sums
+ * of scaled logits, [batch][num_kv_heads][max_seq_len], entries at or beyond
+ * seq_lens[b] untouched; when NULL they are kept in the workspace. */
+td_status td_select_tokens(td_ctx *ctx, const td_shape *shape, const void *q, const void *K,
+                           const void *V, int32_t k, void *out, int32_t *positions,
+                           float *group_scores, void *hip_stream);
+
+/* SparseAttention(q, C[rho]) of Alg. 1. */
+td_status td_sparse_attend(td_ctx *ctx, const td_shape *shape, const void *q, const void *K,
+                           const void *V, const int32_t *positions, int32_t k, void *out,
+                           void *hip_stream);
+
+/* argTopK of Alg. 1 on its own: for each of `rows` rows of fp32 scores (row r
+ * at scores + r*row_stride, its length row_lens[r / rows_per_len], row_lens a
+ * DEVICE int32 array) writes the ascending indices of the min(k, len) largest
+ * scores to positions + r*k, -1 padded.  Scores must not be NaN. */
+td_status td_topk(td_ctx *ctx, const float *scores, int64_t row_stride, int32_t rows,
+                  const int32_t *row_lens, int32_t rows_per_len, int32_t max_len, int32_t k,
+                  int32_t *positions, void *hip_stream);
+
+/* The layer loop of Alg. 1, attention part only.  schedule, q_layers,
+ * K_layers, V_layers, out_layers are HOST arrays of num_layers entries (the
+ * pointers inside are device pointers; every layer shares `shape`).  The i-th
+ * selection layer writes rho to positions + i*batch*num_kv_heads*k
+ * (positions: int32 [n_select][batch][num_kv_heads][k]); each sparse layer
+ * reads the most recent one.  A sparse layer before any selection layer is
+ * TD_ERR_INVALID_ARG. */
+td_status td_decode_step(td_ctx *ctx, const td_shape *shape, int32_t num_layers,
+                         const int32_t *schedule, const void *const *q_layers,
+                         const void *const *K_layers, const void *const *V_layers, int32_t k,
+                         void *const *out_layers, int32_t *positions, void *hip_stream);
+
+/* Tuning knobs for measurement sweeps (0 keeps the default): target number of
+ * workgroups per attention launch, and the smallest token chunk per workgroup
+ * for full and for sparse attention.  Affects td_workspace_bytes' answer only
+ * through the process-wide defaults, so size the workspace first. */
+td_status td_set_tuning(td_ctx *ctx, int32_t target_workgroups, int32_t min_chunk_dense,
+                        int32_t min_chunk_sparse);
+
+const char *td_status_string(td_status s);
+const char *td_last_error(const td_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TIDAL_H */

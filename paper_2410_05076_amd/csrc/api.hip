@@ -1,0 +1,297 @@
+// Host side of the C ABI declared in tidal.h: argument checks, workspace layout, launch
+// planning and the layer loop of Alg. 1.
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+
+#include "common.h"
+
+using namespace tidal;
+
+struct td_ctx {
+    int device = 0;
+    char *workspace = nullptr;
+    size_t workspace_bytes = 0;
+    int32_t target_workgroups = 0, min_chunk_dense = 0, min_chunk_sparse = 0;
+    char error[256] = {0};
+};
+
+namespace {
+
+constexpr int32_t kDefaultTargetWorkgroups = 1024;
+constexpr int32_t kDefaultMinChunkDense = 256;
+constexpr int32_t kDefaultMinChunkSparse = 64;
+constexpr int32_t kChunkGranule = 64;
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+int32_t ceil_div(int64_t a, int64_t b) { return (int32_t)((a + b - 1) / b); }
+
+td_status fail(td_ctx *ctx, td_status s, const char *fmt, const char *detail = "") {
+    if (ctx) snprintf(ctx->error, sizeof ctx->error, fmt, detail);
+    return s;
+}
+
+// Why a shape or budget is unusable, or nullptr.  Host only.
+const char *shape_problem(const td_shape *s, int32_t k, td_status *code) {
+    *code = TD_ERR_INVALID_ARG;
+    if (!s) return "shape is NULL";
+    if (s->batch < 1) return "batch < 1";
+    if (s->num_q_heads < 1 || s->num_kv_heads < 1) return "head count < 1";
+    if (s->num_q_heads % s->num_kv_heads) return "num_q_heads is not a multiple of num_kv_heads";
+    if (s->max_seq_len < 1) return "max_seq_len < 1";
+    if (!s->seq_lens) return "seq_lens is NULL";
+    if (s->dtype != TD_BF16 && s->dtype != TD_F32) return "dtype is neither TD_BF16 nor TD_F32";
+    if (!(s->sm_scale >= 0.f)) return "sm_scale is negative or NaN";
+    if (s->kv_stride_tok < s->head_dim || s->kv_stride_head < 1 || s->kv_stride_batch < 0)
+        return "KV strides are too small for head_dim";
+    if (s->kv_stride_tok % 8 || s->kv_stride_head % 8 || s->kv_stride_batch % 8)
+        return "KV strides must be multiples of 8 elements";
+    if (k > kSparseChunkMax * kSplitsMax) return "k is larger than 524288";
+    *code = TD_ERR_UNSUPPORTED;
+    if (s->head_dim != 64 && s->head_dim != 128) return "head_dim must be 64 or 128";
+    const int g = s->num_q_heads / s->num_kv_heads;
+    if (g != 1 && g != 2 && g != 4 && g != 8) return "group size must be 1, 2, 4 or 8";
+    if (s->batch > 65535 || s->num_kv_heads > 65535) return "batch or num_kv_heads above 65535";
+    *code = TD_OK;
+    return nullptr;
+}
+
+bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+struct Workspace {
+    size_t part_acc, part_ml, scores, total;
+    int64_t score_stride;
+};
+
+Workspace workspace_layout(const td_shape *s, int32_t k) {
+    Workspace w;
+    const size_t heads = (size_t)s->batch * s->num_q_heads;
+    w.score_stride = (int64_t)align_up((size_t)s->max_seq_len, 4);
+    w.part_acc = 0;
+    w.part_ml = align_up(w.part_acc + heads * kSplitsMax * s->head_dim * sizeof(float), 256);
+    w.scores = align_up(w.part_ml + heads * kSplitsMax * 2 * sizeof(float), 256);
+    const size_t score_bytes = k > 0 ? (size_t)s->batch * s->num_kv_heads * w.score_stride * sizeof(float) : 0;
+    w.total = align_up(w.scores + score_bytes, 256);
+    return w;
+}
+
+void plan_chunks(const td_ctx *ctx, const td_shape *s, bool sparse, int32_t tokens, int32_t *chunk,
+                 int32_t *splits) {
+    const int32_t target = ctx->target_workgroups > 0 ? ctx->target_workgroups : kDefaultTargetWorkgroups;
+    int32_t floor_chunk = sparse ? (ctx->min_chunk_sparse > 0 ? ctx->min_chunk_sparse : kDefaultMinChunkSparse)
+                                 : (ctx->min_chunk_dense > 0 ? ctx->min_chunk_dense : kDefaultMinChunkDense);
+    const int64_t groups = (int64_t)s->batch * s->num_kv_heads;
+    const int32_t want = (int32_t)std::max<int64_t>(1, target / groups);
+    int32_t c = std::max(ceil_div(tokens, want), floor_chunk);
+    c = std::max(c, ceil_div(tokens, kSplitsMax));
+    c = (int32_t)align_up((size_t)c, kChunkGranule);
+    if (sparse) c = std::min(c, kSparseChunkMax);
+    *chunk = c;
+    *splits = ceil_div(tokens, c);
+}
+
+td_status attend(td_ctx *ctx, const td_shape *s, int mode, const void *q, const void *K, const void *V,
+                 const int32_t *positions, int32_t k, float *scores, int64_t score_stride, void *out,
+                 hipStream_t stream) {
+    const Workspace w = workspace_layout(s, mode == kDense ? 0 : k);
+    AttendParams p;
+    memset(&p, 0, sizeof p);
+    p.q = q; p.K = K; p.V = V; p.out = out;
+    p.seq_lens = s->seq_lens;
+    p.positions = positions;
+    p.scores = scores;
+    p.score_stride = score_stride;
+    p.part_acc = reinterpret_cast<float *>(ctx->workspace + w.part_acc);
+    p.part_ml = reinterpret_cast<float *>(ctx->workspace + w.part_ml);
+    p.stride_batch = s->kv_stride_batch;
+    p.stride_head = s->kv_stride_head;
+    p.stride_tok = s->kv_stride_tok;
+    p.batch = s->batch;
+    p.num_q_heads = s->num_q_heads;
+    p.num_kv_heads = s->num_kv_heads;
+    p.max_seq_len = s->max_seq_len;
+    p.k = k;
+    p.scale = s->sm_scale > 0.f ? s->sm_scale : 1.0f / sqrtf((float)s->head_dim);
+    plan_chunks(ctx, s, mode == kSparse, mode == kSparse ? k : s->max_seq_len, &p.chunk, &p.num_splits);
+    const hipError_t e = launch_attend(s->dtype, s->head_dim, s->num_q_heads / s->num_kv_heads, mode, p, stream);
+    if (e != hipSuccess) return fail(ctx, TD_ERR_HIP, "attention launch failed: %s", hipGetErrorString(e));
+    return TD_OK;
+}
+
+// Checks common to every attention call; `k` <= 0 when the call has no budget.
+td_status check_call(td_ctx *ctx, const td_shape *s, int32_t k, bool needs_k, const void *q, const void *K,
+                     const void *V, const void *out) {
+    if (!ctx) return TD_ERR_INVALID_ARG;
+    td_status code;
+    if (const char *why = shape_problem(s, k, &code)) return fail(ctx, code, "%s", why);
+    if (needs_k && k < 1) return fail(ctx, TD_ERR_INVALID_ARG, "%s", "k < 1");
+    if (!q || !K || !V || !out) return fail(ctx, TD_ERR_INVALID_ARG, "%s", "q, K, V or out is NULL");
+    if (misaligned(q) || misaligned(K) || misaligned(V) || misaligned(out))
+        return fail(ctx, TD_ERR_INVALID_ARG, "%s", "q, K, V and out must be 16-byte aligned");
+    if (workspace_layout(s, needs_k ? k : 0).total > ctx->workspace_bytes)
+        return fail(ctx, TD_ERR_WORKSPACE, "%s", "workspace is smaller than td_workspace_bytes(shape, k)");
+    return TD_OK;
+}
+
+td_status select_tokens(td_ctx *ctx, const td_shape *s, const void *q, const void *K, const void *V,
+                        int32_t k, void *out, int32_t *positions, float *group_scores, hipStream_t stream) {
+    const Workspace w = workspace_layout(s, k);
+    float *scores = group_scores ? group_scores : reinterpret_cast<float *>(ctx->workspace + w.scores);
+    const int64_t stride = group_scores ? (int64_t)s->max_seq_len : w.score_stride;
+    td_status st = attend(ctx, s, kSelect, q, K, V, nullptr, k, scores, stride, out, stream);
+    if (st != TD_OK) return st;
+    const hipError_t e = launch_topk(scores, stride, s->batch * s->num_kv_heads, s->seq_lens, s->num_kv_heads,
+                                     s->max_seq_len, k, positions, stream);
+    if (e != hipSuccess) return fail(ctx, TD_ERR_HIP, "top-k launch failed: %s", hipGetErrorString(e));
+    return TD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+td_status td_validate(const td_shape *shape, int32_t k) {
+    td_status code;
+    shape_problem(shape, k, &code);
+    return code;
+}
+
+size_t td_workspace_bytes(const td_shape *shape, int32_t k) {
+    td_status code;
+    if (shape_problem(shape, k, &code)) return 0;
+    return workspace_layout(shape, k).total;
+}
+
+td_status td_create(td_ctx **out, int device, size_t workspace_bytes) {
+    if (!out) return TD_ERR_INVALID_ARG;
+    *out = nullptr;
+    td_ctx *ctx = new (std::nothrow) td_ctx;
+    if (!ctx) return TD_ERR_HIP;
+    ctx->device = device;
+    hipError_t e = hipSetDevice(device);
+    if (e == hipSuccess && workspace_bytes) e = hipMalloc(reinterpret_cast<void **>(&ctx->workspace), workspace_bytes);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        delete ctx;
+        return TD_ERR_HIP;
+    }
+    ctx->workspace_bytes = workspace_bytes;
+    *out = ctx;
+    return TD_OK;
+}
+
+td_status td_destroy(td_ctx *ctx) {
+    if (!ctx) return TD_ERR_INVALID_ARG;
+    hipError_t e = hipSuccess;
+    if (ctx->workspace) e = hipFree(ctx->workspace);
+    delete ctx;
+    return e == hipSuccess ? TD_OK : TD_ERR_HIP;
+}
+
+td_status td_set_tuning(td_ctx *ctx, int32_t target_workgroups, int32_t min_chunk_dense,
+                        int32_t min_chunk_sparse) {
+    if (!ctx) return TD_ERR_INVALID_ARG;
+    if (target_workgroups < 0 || min_chunk_dense < 0 || min_chunk_sparse < 0)
+        return fail(ctx, TD_ERR_INVALID_ARG, "%s", "tuning values must be >= 0");
+    ctx->target_workgroups = target_workgroups;
+    ctx->min_chunk_dense = min_chunk_dense;
+    ctx->min_chunk_sparse = min_chunk_sparse;
+    return TD_OK;
+}
+
+td_status td_full_attend(td_ctx *ctx, const td_shape *shape, const void *q, const void *K, const void *V,
+                         void *out, void *hip_stream) {
+    td_status st = check_call(ctx, shape, 0, false, q, K, V, out);
+    if (st != TD_OK) return st;
+    return attend(ctx, shape, kDense, q, K, V, nullptr, 0, nullptr, 0, out, static_cast<hipStream_t>(hip_stream));
+}
+
+td_status td_select_tokens(td_ctx *ctx, const td_shape *shape, const void *q, const void *K, const void *V,
+                           int32_t k, void *out, int32_t *positions, float *group_scores, void *hip_stream) {
+    td_status st = check_call(ctx, shape, k, true, q, K, V, out);
+    if (st != TD_OK) return st;
+    if (!positions) return fail(ctx, TD_ERR_INVALID_ARG, "%s", "positions is NULL");
+    if (group_scores && misaligned(group_scores))
+        return fail(ctx, TD_ERR_INVALID_ARG, "%s", "group_scores must be 16-byte aligned");
+    return select_tokens(ctx, shape, q, K, V, k, out, positions, group_scores, static_cast<hipStream_t>(hip_stream));
+}
+
+td_status td_sparse_attend(td_ctx *ctx, const td_shape *shape, const void *q, const void *K, const void *V,
+                           const int32_t *positions, int32_t k, void *out, void *hip_stream) {
+    td_status st = check_call(ctx, shape, k, true, q, K, V, out);
+    if (st != TD_OK) return st;
+    if (!positions) return fail(ctx, TD_ERR_INVALID_ARG, "%s", "positions is NULL");
+    return attend(ctx, shape, kSparse, q, K, V, positions, k, nullptr, 0, out, static_cast<hipStream_t>(hip_stream));
+}
+
+td_status td_topk(td_ctx *ctx, const float *scores, int64_t row_stride, int32_t rows, const int32_t *row_lens,
+                  int32_t rows_per_len, int32_t max_len, int32_t k, int32_t *positions, void *hip_stream) {
+    if (!ctx) return TD_ERR_INVALID_ARG;
+    if (!scores || !row_lens || !positions) return fail(ctx, TD_ERR_INVALID_ARG, "%s", "scores, row_lens or positions is NULL");
+    if (rows < 1 || rows_per_len < 1 || max_len < 1 || k < 1 || row_stride < max_len)
+        return fail(ctx, TD_ERR_INVALID_ARG, "%s", "rows, rows_per_len, max_len, k must be >= 1 and row_stride >= max_len");
+    if (misaligned(scores)) return fail(ctx, TD_ERR_INVALID_ARG, "%s", "scores must be 16-byte aligned");
+    const hipError_t e = launch_topk(scores, row_stride, rows, row_lens, rows_per_len, max_len, k, positions,
+                                     static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail(ctx, TD_ERR_HIP, "top-k launch failed: %s", hipGetErrorString(e));
+    return TD_OK;
+}
+
+td_status td_decode_step(td_ctx *ctx, const td_shape *shape, int32_t num_layers, const int32_t *schedule,
+                         const void *const *q_layers, const void *const *K_layers, const void *const *V_layers,
+                         int32_t k, void *const *out_layers, int32_t *positions, void *hip_stream) {
+    if (!ctx) return TD_ERR_INVALID_ARG;
+    if (num_layers < 1 || !schedule || !q_layers || !K_layers || !V_layers || !out_layers)
+        return fail(ctx, TD_ERR_INVALID_ARG, "%s", "num_layers < 1 or a layer array is NULL");
+    bool any_budget = false, selected = false;
+    for (int i = 0; i < num_layers; ++i) {
+        if (schedule[i] < TD_LAYER_DENSE || schedule[i] > TD_LAYER_SPARSE)
+            return fail(ctx, TD_ERR_INVALID_ARG, "%s", "schedule entry is not a td_layer_kind");
+        if (schedule[i] == TD_LAYER_SELECT) selected = true;
+        if (schedule[i] == TD_LAYER_SPARSE && !selected)
+            return fail(ctx, TD_ERR_INVALID_ARG, "%s", "sparse layer before any selection layer");
+        if (schedule[i] != TD_LAYER_DENSE) any_budget = true;
+    }
+    if (any_budget && !positions) return fail(ctx, TD_ERR_INVALID_ARG, "%s", "positions is NULL");
+    for (int i = 0; i < num_layers; ++i) {
+        td_status st = check_call(ctx, shape, k, any_budget, q_layers[i], K_layers[i], V_layers[i], out_layers[i]);
+        if (st != TD_OK) return st;
+    }
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int64_t slot = (int64_t)shape->batch * shape->num_kv_heads * k;
+    const int32_t *rho = nullptr;
+    int n_sel = 0;
+    for (int i = 0; i < num_layers; ++i) {
+        td_status st;
+        if (schedule[i] == TD_LAYER_DENSE) {
+            st = attend(ctx, shape, kDense, q_layers[i], K_layers[i], V_layers[i], nullptr, 0, nullptr, 0,
+                        out_layers[i], stream);
+        } else if (schedule[i] == TD_LAYER_SELECT) {
+            int32_t *dst = positions + slot * n_sel++;
+            st = select_tokens(ctx, shape, q_layers[i], K_layers[i], V_layers[i], k, out_layers[i], dst, nullptr, stream);
+            rho = dst;
+        } else {
+            st = attend(ctx, shape, kSparse, q_layers[i], K_layers[i], V_layers[i], rho, k, nullptr, 0,
+                        out_layers[i], stream);
+        }
+        if (st != TD_OK) return st;
+    }
+    return TD_OK;
+}
+
+const char *td_status_string(td_status s) {
+    switch (s) {
+    case TD_OK: return "ok";
+    case TD_ERR_INVALID_ARG: return "invalid argument";
+    case TD_ERR_UNSUPPORTED: return "unsupported shape";
+    case TD_ERR_WORKSPACE: return "workspace too small";
+    case TD_ERR_HIP: return "HIP error";
+    }
+    return "unknown status";
+}
+
+const char *td_last_error(const td_ctx *ctx) { return ctx ? ctx->error : "context is NULL"; }
+
+}  // extern "C"

@@ -1,0 +1,321 @@
+// Split-K decode attention for gfx950: Eq. 1 of the paper for one query row per head, over
+// either the whole KV cache (full attention and token selection layers of Alg. 1) or the
+// rows named by rho (position persistent sparse attention).
+//
+// Work decomposition.  grid = (token chunks, KV heads, sequences).  A workgroup of four
+// wave64s streams one chunk of one (sequence, KV head) and serves all G query heads of the
+// group from the same loaded rows, so each K/V byte is fetched once.  A row of head_dim
+// elements is covered by LPR lanes holding 16 bytes each, so one wave-wide 128-bit load
+// fetches 64/LPR whole rows, fully coalesced; a dot product is finished by a DPP reduction
+// over those LPR lanes.  Each lane keeps an online-softmax state (running max, sum, its
+// slice of the output) per query head; states are merged across row groups, waves and
+// finally chunks (second kernel) with the usual rescaling rule.
+//
+// Token selection (Sec. 3.1): the scaled inner products are not turned into probabilities;
+// their sum over the group's query heads is written once per token while the row is in
+// registers, and top-k runs on those sums afterwards.
+#include "common.h"
+
+namespace tidal {
+namespace {
+
+constexpr int kWavesPerGroup = 4;
+constexpr int kThreads = kWavesPerGroup * kWave;
+constexpr int kUnroll = 4;  // row loads in flight per wave, for each of K and V
+constexpr float kEmptyMax = -3.0e38f;
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+    return __builtin_bit_cast(
+        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+
+// Sum over the LPR consecutive lanes that hold one row; every lane gets the same bits.
+template <int LPR>
+__device__ __forceinline__ float row_sum(float v) {
+    v += dpp_move<0xB1>(v);                        // quad_perm [1,0,3,2]
+    v += dpp_move<0x4E>(v);                        // quad_perm [2,3,0,1]
+    if constexpr (LPR >= 8) v += dpp_move<0x141>(v);   // row_half_mirror
+    if constexpr (LPR >= 16) v += dpp_move<0x140>(v);  // row_mirror
+    if constexpr (LPR >= 32) v += __shfl_xor(v, 16);
+    return v;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+template <int DT>
+struct Elems;
+template <>
+struct Elems<TD_BF16> {
+    static constexpr int kPerLane = 8;
+    static constexpr int kBytes = 2;
+    static __device__ __forceinline__ void unpack(const uint4 &r, float (&f)[8]) {
+        f[0] = __uint_as_float(r.x << 16);
+        f[1] = __uint_as_float(r.x & 0xffff0000u);
+        f[2] = __uint_as_float(r.y << 16);
+        f[3] = __uint_as_float(r.y & 0xffff0000u);
+        f[4] = __uint_as_float(r.z << 16);
+        f[5] = __uint_as_float(r.z & 0xffff0000u);
+        f[6] = __uint_as_float(r.w << 16);
+        f[7] = __uint_as_float(r.w & 0xffff0000u);
+    }
+};
+template <>
+struct Elems<TD_F32> {
+    static constexpr int kPerLane = 4;
+    static constexpr int kBytes = 4;
+    static __device__ __forceinline__ void unpack(const uint4 &r, float (&f)[4]) {
+        f[0] = __uint_as_float(r.x);
+        f[1] = __uint_as_float(r.y);
+        f[2] = __uint_as_float(r.z);
+        f[3] = __uint_as_float(r.w);
+    }
+};
+
+__device__ __forceinline__ uint32_t bf16_bits_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;  // NaN stays NaN
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+template <int DT, int D, int G, int MODE>
+__global__ __launch_bounds__(kThreads) void attend_split_kernel(const AttendParams p) {
+    using E = Elems<DT>;
+    constexpr int EPL = E::kPerLane;
+    constexpr int LPR = D / EPL;        // lanes per row
+    constexpr int TPW = kWave / LPR;    // rows per wave-wide load
+    constexpr int STEP = kUnroll * TPW; // rows per wave per iteration
+
+    const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const int r = lane / LPR, c = lane % LPR;
+
+    const int N = min(max(p.seq_lens[b], 0), p.max_seq_len);
+    const int n_tok = MODE == kSparse ? (N > 0 ? p.k : 0) : N;
+    const int t0 = split * p.chunk;
+    if (t0 >= n_tok) return;
+    const int t1 = min(n_tok, t0 + p.chunk);
+
+    __shared__ int s_pos[MODE == kSparse ? kSparseChunkMax : 1];
+    if constexpr (MODE == kSparse) {
+        const int32_t *pos = p.positions + ((int64_t)b * p.num_kv_heads + g) * p.k;
+        for (int i = threadIdx.x; i < t1 - t0; i += kThreads) s_pos[i] = pos[t0 + i];
+        __syncthreads();
+    }
+
+    // this lane's slice of the G queries of the group
+    float qf[G][EPL];
+#pragma unroll
+    for (int i = 0; i < G; ++i) {
+        const char *qp = (const char *)p.q +
+                         (((int64_t)b * p.num_q_heads + g * G + i) * D + c * EPL) * E::kBytes;
+        E::unpack(*(const uint4 *)qp, qf[i]);
+    }
+
+    const int64_t row_bytes = p.stride_tok * E::kBytes;
+    const int64_t head_off = ((int64_t)b * p.stride_batch + (int64_t)g * p.stride_head) * E::kBytes + c * 16;
+    const char *Kb = (const char *)p.K + head_off;
+    const char *Vb = (const char *)p.V + head_off;
+
+    float m[G], l[G], acc[G][EPL];
+#pragma unroll
+    for (int i = 0; i < G; ++i) {
+        m[i] = kEmptyMax;
+        l[i] = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[i][e] = 0.f;
+    }
+    const float scale2 = p.scale * kLog2e;
+
+    for (int base = t0 + wave * STEP; base < t1; base += kWavesPerGroup * STEP) {
+        uint4 kraw[kUnroll], vraw[kUnroll];
+        bool valid[kUnroll];
+        int64_t off[kUnroll];
+        int tok[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int t = base + u * TPW + r;
+            bool ok = t < t1;
+            int row;
+            if constexpr (MODE == kSparse) {
+                const int pj = ok ? s_pos[t - t0] : -1;
+                ok = pj >= 0 && pj < N;
+                row = ok ? pj : 0;
+            } else {
+                row = ok ? t : t1 - 1;
+            }
+            valid[u] = ok;
+            tok[u] = row;
+            off[u] = (int64_t)row * row_bytes;
+            kraw[u] = *(const uint4 *)(Kb + off[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) vraw[u] = *(const uint4 *)(Vb + off[u]);
+
+        float s2[kUnroll][G];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            float kf[EPL];
+            E::unpack(kraw[u], kf);
+            float gsum = 0.f;
+#pragma unroll
+            for (int i = 0; i < G; ++i) {
+                float d = 0.f;
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) d = fmaf(kf[e], qf[i][e], d);
+                d = row_sum<LPR>(d);
+                gsum += d * p.scale;
+                s2[u][i] = valid[u] ? d * scale2 : -INFINITY;
+            }
+            if constexpr (MODE == kSelect) {
+                if (c == 0 && valid[u])
+                    p.scores[((int64_t)b * p.num_kv_heads + g) * p.score_stride + tok[u]] = gsum;
+            }
+        }
+
+        float pr[kUnroll][G];
+#pragma unroll
+        for (int i = 0; i < G; ++i) {
+            float mx = m[i];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) mx = fmaxf(mx, s2[u][i]);
+            const float alpha = fast_exp2(m[i] - mx);
+            m[i] = mx;
+            l[i] *= alpha;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[i][e] *= alpha;
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                pr[u][i] = fast_exp2(s2[u][i] - mx);
+                l[i] += pr[u][i];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            float vf[EPL];
+            E::unpack(vraw[u], vf);
+#pragma unroll
+            for (int i = 0; i < G; ++i)
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) acc[i][e] = fmaf(pr[u][i], vf[e], acc[i][e]);
+        }
+    }
+
+    // merge the row groups of this wave (symmetric, every lane ends with the same state)
+#pragma unroll
+    for (int o = LPR; o < kWave; o <<= 1) {
+#pragma unroll
+        for (int i = 0; i < G; ++i) {
+            const float mo = __shfl_xor(m[i], o), lo = __shfl_xor(l[i], o);
+            const float mx = fmaxf(m[i], mo);
+            const float a = fast_exp2(m[i] - mx), bb = fast_exp2(mo - mx);
+            l[i] = l[i] * a + lo * bb;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[i][e] = acc[i][e] * a + __shfl_xor(acc[i][e], o) * bb;
+            m[i] = mx;
+        }
+    }
+
+    __shared__ float s_ml[kWavesPerGroup][G][2];
+    __shared__ float s_acc[kWavesPerGroup][G][D];
+    if (lane < LPR) {
+#pragma unroll
+        for (int i = 0; i < G; ++i) {
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) s_acc[wave][i][c * EPL + e] = acc[i][e];
+            if (c == 0) {
+                s_ml[wave][i][0] = m[i];
+                s_ml[wave][i][1] = l[i];
+            }
+        }
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {
+        const int i = idx / D, ch = idx % D;
+        float mx = s_ml[0][i][0];
+#pragma unroll
+        for (int w = 1; w < kWavesPerGroup; ++w) mx = fmaxf(mx, s_ml[w][i][0]);
+        float ls = 0.f, as = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWavesPerGroup; ++w) {
+            const float a = fast_exp2(s_ml[w][i][0] - mx);
+            ls += s_ml[w][i][1] * a;
+            as += s_acc[w][i][ch] * a;
+        }
+        const int64_t slot = ((int64_t)b * p.num_q_heads + g * G + i) * p.num_splits + split;
+        p.part_acc[slot * D + ch] = as;
+        if (ch == 0) {
+            p.part_ml[slot * 2] = mx;
+            p.part_ml[slot * 2 + 1] = ls;
+        }
+    }
+}
+
+// Merges the chunk partials of one (sequence, query head) and writes the output row.
+template <int DT, int D>
+__global__ __launch_bounds__(D) void attend_merge_kernel(const AttendParams p, const int sparse) {
+    const int h = blockIdx.x, b = blockIdx.y, ch = threadIdx.x;
+    const int N = min(max(p.seq_lens[b], 0), p.max_seq_len);
+    const int n_tok = sparse ? (N > 0 ? p.k : 0) : N;
+    const int ns = (n_tok + p.chunk - 1) / p.chunk;
+    const int64_t slot0 = ((int64_t)b * p.num_q_heads + h) * p.num_splits;
+    float mx = kEmptyMax;
+    for (int s = 0; s < ns; ++s) mx = fmaxf(mx, p.part_ml[(slot0 + s) * 2]);
+    float ls = 0.f, as = 0.f;
+    for (int s = 0; s < ns; ++s) {
+        const float a = fast_exp2(p.part_ml[(slot0 + s) * 2] - mx);
+        ls += p.part_ml[(slot0 + s) * 2 + 1] * a;
+        as += p.part_acc[(slot0 + s) * D + ch] * a;
+    }
+    const float o = ls > 0.f ? as / ls : 0.f;
+    const int64_t oi = ((int64_t)b * p.num_q_heads + h) * D + ch;
+    if constexpr (DT == TD_BF16)
+        ((uint16_t *)p.out)[oi] = (uint16_t)bf16_bits_rne(o);
+    else
+        ((float *)p.out)[oi] = o;
+}
+
+template <int DT, int D, int G>
+hipError_t launch_mode(int mode, const AttendParams &p, hipStream_t stream) {
+    const dim3 grid(p.num_splits, p.num_kv_heads, p.batch), block(kThreads);
+    switch (mode) {
+    case kDense:
+        hipLaunchKernelGGL((attend_split_kernel<DT, D, G, kDense>), grid, block, 0, stream, p);
+        break;
+    case kSelect:
+        hipLaunchKernelGGL((attend_split_kernel<DT, D, G, kSelect>), grid, block, 0, stream, p);
+        break;
+    default:
+        hipLaunchKernelGGL((attend_split_kernel<DT, D, G, kSparse>), grid, block, 0, stream, p);
+        break;
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((attend_merge_kernel<DT, D>), dim3(p.num_q_heads, p.batch), dim3(D), 0, stream, p,
+                       mode == kSparse ? 1 : 0);
+    return hipGetLastError();
+}
+
+template <int DT, int D>
+hipError_t launch_group(int group, int mode, const AttendParams &p, hipStream_t stream) {
+    switch (group) {
+    case 1: return launch_mode<DT, D, 1>(mode, p, stream);
+    case 2: return launch_mode<DT, D, 2>(mode, p, stream);
+    case 4: return launch_mode<DT, D, 4>(mode, p, stream);
+    case 8: return launch_mode<DT, D, 8>(mode, p, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_attend(int dtype, int head_dim, int group, int mode, const AttendParams &p,
+                         hipStream_t stream) {
+    if (dtype == TD_BF16 && head_dim == 128) return launch_group<TD_BF16, 128>(group, mode, p, stream);
+    if (dtype == TD_BF16 && head_dim == 64) return launch_group<TD_BF16, 64>(group, mode, p, stream);
+    if (dtype == TD_F32 && head_dim == 128) return launch_group<TD_F32, 128>(group, mode, p, stream);
+    if (dtype == TD_F32 && head_dim == 64) return launch_group<TD_F32, 64>(group, mode, p, stream);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace tidal

@@ -1,0 +1,44 @@
+// Internal declarations shared by the host API and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tidal.h"
+
+namespace tidal {
+
+constexpr int kWave = 64;
+constexpr int kSplitsMax = 256;        // upper bound on token chunks per (sequence, KV head)
+constexpr int kSparseChunkMax = 2048;  // positions of one chunk are staged in LDS
+constexpr float kLog2e = 1.4426950408889634f;
+
+enum AttendMode { kDense = 0, kSelect = 1, kSparse = 2 };
+
+struct AttendParams {
+    const void *q, *K, *V;
+    const int32_t *seq_lens;
+    const int32_t *positions;  // sparse: [B][Hkv][k]
+    float *scores;             // select: [B][Hkv][score_stride]
+    float *part_acc;           // [B][Hq][num_splits][D]
+    float *part_ml;            // [B][Hq][num_splits][2]  (running max in log2 units, sum)
+    void *out;                 // [B][Hq][D]
+    int64_t stride_batch, stride_head, stride_tok;  // elements
+    int64_t score_stride;
+    int32_t batch, num_q_heads, num_kv_heads;
+    int32_t max_seq_len;
+    int32_t k;
+    int32_t chunk;       // tokens per workgroup
+    int32_t num_splits;  // grid.x
+    float scale;
+};
+
+// Enqueues the split attention kernel followed by the merge kernel.
+hipError_t launch_attend(int dtype, int head_dim, int group, int mode, const AttendParams &p,
+                         hipStream_t stream);
+
+// argTopK over rows of fp32 scores; one workgroup per row.
+hipError_t launch_topk(const float *scores, int64_t row_stride, int32_t rows, const int32_t *row_lens,
+                       int32_t rows_per_len, int32_t max_len, int32_t k, int32_t *positions,
+                       hipStream_t stream);
+
+}  // namespace tidal

@@ -1,0 +1,155 @@
+"""ctypes binding of libtidal.so (include/tidal.h): argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels; torch is used for
+device memory and the current stream.  If the library has not been built this
+module raises: there is no fallback path.
+"""
+import ctypes
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libtidal.so")
+
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = range(5)
+BF16, F32 = 0, 1
+LAYER_DENSE, LAYER_SELECT, LAYER_SPARSE = 0, 1, 2
+
+EXPORTS = ("td_validate", "td_workspace_bytes", "td_create", "td_destroy", "td_full_attend",
+           "td_select_tokens", "td_sparse_attend", "td_topk", "td_decode_step", "td_set_tuning",
+           "td_status_string", "td_last_error")
+
+
+class Shape(ctypes.Structure):
+    """td_shape of include/tidal.h."""
+    _fields_ = [("batch", ctypes.c_int32), ("num_q_heads", ctypes.c_int32),
+                ("num_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("sm_scale", ctypes.c_float),
+                ("kv_stride_batch", ctypes.c_int64), ("kv_stride_head", ctypes.c_int64),
+                ("kv_stride_tok", ctypes.c_int64),
+                ("seq_lens", ctypes.c_void_p), ("max_seq_len", ctypes.c_int32)]
+
+
+class TidalError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__("td_status %d: %s" % (status, message))
+        self.status = status
+
+
+_lib = None
+
+
+def lib():
+    """Opens libtidal.so (built by paper_2410_05076_amd/build.py) and declares its signatures."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("%s is missing: run `python paper_2410_05076_amd/build.py` "
+                          "(there is no non-HIP fallback)" % LIB_PATH)
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+    shp = ctypes.POINTER(Shape)
+    L.td_validate.argtypes, L.td_validate.restype = [shp, i32], ctypes.c_int
+    L.td_workspace_bytes.argtypes, L.td_workspace_bytes.restype = [shp, i32], sz
+    L.td_create.argtypes, L.td_create.restype = [ctypes.POINTER(vp), ctypes.c_int, sz], ctypes.c_int
+    L.td_destroy.argtypes, L.td_destroy.restype = [vp], ctypes.c_int
+    L.td_full_attend.argtypes, L.td_full_attend.restype = [vp, shp, vp, vp, vp, vp, vp], ctypes.c_int
+    L.td_select_tokens.argtypes = [vp, shp, vp, vp, vp, i32, vp, vp, vp, vp]
+    L.td_select_tokens.restype = ctypes.c_int
+    L.td_sparse_attend.argtypes = [vp, shp, vp, vp, vp, vp, i32, vp, vp]
+    L.td_sparse_attend.restype = ctypes.c_int
+    L.td_topk.argtypes = [vp, vp, i64, i32, vp, i32, i32, i32, vp, vp]
+    L.td_topk.restype = ctypes.c_int
+    L.td_decode_step.argtypes = [vp, shp, i32, ctypes.POINTER(i32), ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                 ctypes.POINTER(vp), i32, ctypes.POINTER(vp), vp, vp]
+    L.td_decode_step.restype = ctypes.c_int
+    L.td_set_tuning.argtypes, L.td_set_tuning.restype = [vp, i32, i32, i32], ctypes.c_int
+    L.td_status_string.argtypes, L.td_status_string.restype = [ctypes.c_int], ctypes.c_char_p
+    L.td_last_error.argtypes, L.td_last_error.restype = [vp], ctypes.c_char_p
+    _lib = L
+    return L
+
+
+def _dtype_code(t):
+    if t == torch.bfloat16:
+        return BF16
+    if t == torch.float32:
+        return F32
+    raise TypeError("q, K, V must be bfloat16 or float32, got %s" % t)
+
+
+def make_shape(q, K, seq_lens, sm_scale=0.0):
+    """td_shape for q [B][Hq][d] and a cache tensor K [B][Hkv][N_max][d] (any strides with d contiguous)."""
+    assert q.dim() == 3 and K.dim() == 4 and q.is_contiguous() and K.stride(3) == 1
+    assert seq_lens.dtype == torch.int32 and seq_lens.is_contiguous() and seq_lens.numel() == q.shape[0]
+    return Shape(q.shape[0], q.shape[1], K.shape[1], q.shape[2], _dtype_code(q.dtype), float(sm_scale),
+                 K.stride(0), K.stride(1), K.stride(2), seq_lens.data_ptr(), K.shape[2])
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+class Tidal:
+    """A td_ctx with a workspace sized for one shape and budget."""
+
+    def __init__(self, shape, k, device=None):
+        L = lib()
+        self.device = torch.cuda.current_device() if device is None else device
+        need = L.td_workspace_bytes(ctypes.byref(shape), k)
+        if need == 0:
+            raise TidalError(L.td_validate(ctypes.byref(shape), k), "invalid or unsupported shape")
+        self.workspace_bytes = need
+        self._ctx = ctypes.c_void_p()
+        st = L.td_create(ctypes.byref(self._ctx), self.device, need)
+        if st != OK:
+            raise TidalError(st, "td_create failed")
+
+    def close(self):
+        if getattr(self, "_ctx", None):
+            lib().td_destroy(self._ctx)
+            self._ctx = None
+
+    __del__ = close
+
+    def _check(self, st):
+        if st != OK:
+            raise TidalError(st, lib().td_last_error(self._ctx).decode())
+
+    def set_tuning(self, target_workgroups=0, min_chunk_dense=0, min_chunk_sparse=0):
+        self._check(lib().td_set_tuning(self._ctx, target_workgroups, min_chunk_dense, min_chunk_sparse))
+
+    def full_attend(self, shape, q, K, V, out):
+        self._check(lib().td_full_attend(self._ctx, ctypes.byref(shape), q.data_ptr(), K.data_ptr(),
+                                         V.data_ptr(), out.data_ptr(), _stream()))
+        return out
+
+    def select_tokens(self, shape, q, K, V, k, out, positions, group_scores=None):
+        self._check(lib().td_select_tokens(self._ctx, ctypes.byref(shape), q.data_ptr(), K.data_ptr(),
+                                           V.data_ptr(), k, out.data_ptr(), positions.data_ptr(),
+                                           group_scores.data_ptr() if group_scores is not None else None,
+                                           _stream()))
+        return out, positions
+
+    def sparse_attend(self, shape, q, K, V, positions, k, out):
+        self._check(lib().td_sparse_attend(self._ctx, ctypes.byref(shape), q.data_ptr(), K.data_ptr(),
+                                           V.data_ptr(), positions.data_ptr(), k, out.data_ptr(), _stream()))
+        return out
+
+    def topk(self, scores, row_lens, rows_per_len, k, positions):
+        rows, stride = scores.shape[0], scores.stride(0)
+        self._check(lib().td_topk(self._ctx, scores.data_ptr(), stride, rows, row_lens.data_ptr(),
+                                  rows_per_len, scores.shape[1], k, positions.data_ptr(), _stream()))
+        return positions
+
+    def decode_step(self, shape, schedule, qs, Ks, Vs, k, outs, positions):
+        n = len(schedule)
+        arr = ctypes.c_void_p * n
+        sched = (ctypes.c_int32 * n)(*[int(x) for x in schedule])
+        self._check(lib().td_decode_step(
+            self._ctx, ctypes.byref(shape), n, sched, arr(*[t.data_ptr() for t in qs]),
+            arr(*[t.data_ptr() for t in Ks]), arr(*[t.data_ptr() for t in Vs]), k,
+            arr(*[t.data_ptr() for t in outs]), positions.data_ptr(), _stream()))
+        return outs, positions

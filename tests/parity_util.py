@@ -1,0 +1,58 @@
+"""Helpers for the GPU parity tests: tolerances and the position-parity rule.
+
+Outputs: max-abs error <= 1e-2 and relative L2 error <= 5e-3 against the fp32
+oracle (bf16 inputs, fp32 accumulation, bf16-rounded output).
+Positions: bit-exact against the oracle except inside a band around the
+oracle's k-th largest score s*: with tau = 1e-4 * max(|s*|, 1), every token
+scoring above s* + tau must be selected, none below s* - tau may be, and the
+list must hold exactly min(k, N) distinct in-range tokens in ascending order
+followed by -1.
+"""
+import torch
+
+MAX_ABS = 1e-2
+REL_L2 = 5e-3
+BAND = 1e-4
+
+
+def check_output(gpu_out, oracle_out, what=""):
+    g = gpu_out.detach().float().cpu()
+    o = oracle_out.float()
+    assert g.shape == o.shape, what
+    assert torch.isfinite(g).all(), "%s: non-finite output" % what
+    max_abs = (g - o).abs().max().item()
+    rel = ((g - o).norm() / o.norm().clamp_min(1e-30)).item()
+    assert max_abs <= MAX_ABS, "%s: max-abs %.3e" % (what, max_abs)
+    assert rel <= REL_L2, "%s: rel-L2 %.3e" % (what, rel)
+    return max_abs, rel
+
+
+def check_positions(gpu_pos, oracle_scores, seq_lens, k, what=""):
+    """gpu_pos [B][Hkv][k] int32, oracle_scores [B][Hkv][N_max] fp32 (oracle's group sums)."""
+    gp = gpu_pos.detach().cpu()
+    B, H, _ = gp.shape
+    exact = 0
+    for b in range(B):
+        n = int(seq_lens[b])
+        ke = min(k, n)
+        for h in range(H):
+            row = gp[b, h]
+            sel = row[:ke].long()
+            assert (row[ke:] == -1).all(), "%s: tail of (%d,%d) is not -1" % (what, b, h)
+            assert sel.min() >= 0 and sel.max() < n, "%s: out of range at (%d,%d)" % (what, b, h)
+            assert (sel[1:] > sel[:-1]).all(), "%s: not strictly ascending at (%d,%d)" % (what, b, h)
+            r = oracle_scores[b, h, :n]
+            kth = torch.topk(r, ke).values[-1]
+            tau = BAND * max(abs(kth.item()), 1.0)
+            chosen = torch.zeros(n, dtype=torch.bool)
+            chosen[sel] = True
+            must = r > kth + tau
+            never = r < kth - tau
+            assert chosen[must].all(), "%s: a token above the band is missing at (%d,%d)" % (what, b, h)
+            assert not chosen[never].any(), "%s: a token below the band was taken at (%d,%d)" % (what, b, h)
+            exact += 1
+    return exact
+
+
+def same_positions(a, b):
+    return torch.equal(a.detach().cpu().int(), b.detach().cpu().int())

@@ -1,0 +1,216 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Tolerances and the position rule are in tests/parity_util.py."""
+import sys
+
+import pytest
+import torch
+
+from oracle import tidal_oracle as O
+from paper_2410_05076_amd import tidal
+from paper_2410_05076_amd import workloads as W
+from parity_util import check_output, check_positions, same_positions
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def device_layers(w, layers):
+    heavy = W.heavy_positions(w)
+    ranks = W.zipf_ranks(w) if w.structure == "zipf" else None
+    return [W.make_layer(w, i, DEV, heavy=heavy, ranks=ranks) for i in layers]
+
+
+def host(t):
+    return t.detach().cpu()
+
+
+class Case:
+    """One workload on the device: context, shape, seq_lens."""
+
+    def __init__(self, w, K_example, q_example):
+        self.w = w
+        self.lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=DEV)
+        self.shape = tidal.make_shape(q_example, K_example, self.lens)
+        self.td = tidal.Tidal(self.shape, w.k)
+
+    def out_like(self, q):
+        return torch.full_like(q, float("nan"))
+
+
+def run_layer_checks(w, layer_kinds, tag):
+    """Runs full / select / sparse on one layer each through the three entry points."""
+    layers = device_layers(w, range(len(layer_kinds)))
+    q0, K0, V0 = layers[0]
+    c = Case(w, K0, q0)
+    stats = {}
+    rho = None
+    for i, kind in enumerate(layer_kinds):
+        q, K, V = layers[i]
+        qh, Kh, Vh = host(q), host(K), host(V)
+        out = c.out_like(q)
+        if kind == W.DENSE:
+            say("%s: layer %d full attention" % (tag, i))
+            c.td.full_attend(c.shape, q, K, V, out)
+            torch.cuda.synchronize()
+            stats[i] = check_output(out, O.full(qh, Kh, Vh, w.seq_lens), "%s L%d full" % (tag, i))
+        elif kind == W.SELECT:
+            say("%s: layer %d selection" % (tag, i))
+            pos = torch.full((w.batch, w.num_kv_heads, w.k), -7, dtype=torch.int32, device=DEV)
+            scores = torch.full((w.batch, w.num_kv_heads, w.max_seq_len), float("nan"), device=DEV)
+            c.td.select_tokens(c.shape, q, K, V, w.k, out, pos, scores)
+            torch.cuda.synchronize()
+            o_out, o_pos, o_scores = O.select(qh, Kh, Vh, w.seq_lens, w.k, return_scores=True)
+            stats[i] = check_output(out, o_out, "%s L%d select" % (tag, i))
+            for b in range(w.batch):   # fused score write against the oracle's group sums
+                n = w.seq_lens[b]
+                d = (host(scores)[b, :, :n] - o_scores[b, :, :n]).abs().max().item()
+                assert d <= 1e-4 * max(1.0, o_scores[b, :, :n].abs().max().item()), "%s scores %g" % (tag, d)
+                assert torch.isnan(host(scores)[b, :, n:]).all(), "scores written beyond the sequence"
+            check_positions(pos, o_scores, w.seq_lens, w.k, "%s L%d" % (tag, i))
+            say("%s: layer %d positions identical to oracle: %s" % (tag, i, same_positions(pos, o_pos)))
+            # same result without the caller's score buffer (workspace path)
+            pos2 = torch.full_like(pos, -7)
+            out2 = c.out_like(q)
+            c.td.select_tokens(c.shape, q, K, V, w.k, out2, pos2)
+            torch.cuda.synchronize()
+            assert torch.equal(pos, pos2) and torch.equal(out, out2)
+            rho = pos
+        else:
+            say("%s: layer %d sparse attention" % (tag, i))
+            c.td.sparse_attend(c.shape, q, K, V, rho, w.k, out)
+            torch.cuda.synchronize()
+            stats[i] = check_output(out, O.sparse(qh, Kh, Vh, w.seq_lens, host(rho)), "%s L%d sparse" % (tag, i))
+    c.td.close()
+    return stats
+
+
+D, S, P = W.DENSE, W.SELECT, W.SPARSE
+
+
+def test_c1_toy_decode_step():
+    w = W.workload("c1")
+    layers = device_layers(w, range(w.num_layers))
+    qs, Ks, Vs = zip(*layers)
+    c = Case(w, Ks[0], qs[0])
+    outs = [c.out_like(q) for q in qs]
+    pos = torch.full((1, w.batch, w.num_kv_heads, w.k), -7, dtype=torch.int32, device=DEV)
+    c.td.decode_step(c.shape, w.schedule, qs, Ks, Vs, w.k, outs, pos)
+    torch.cuda.synchronize()
+    o_outs, o_pos = O.step(w.schedule, [host(t) for t in qs], [host(t) for t in Ks], [host(t) for t in Vs],
+                           w.seq_lens, w.k)
+    assert same_positions(pos, o_pos)            # planted heavy hitters, wide gaps: exact
+    for i in range(w.num_layers):
+        check_output(outs[i], o_outs[i], "c1 L%d" % i)
+    heavy = W.heavy_positions(w)
+    for g in range(w.num_kv_heads):
+        assert set(heavy[0, g].tolist()) <= set(host(pos)[0, 0, g].tolist())
+    c.td.close()
+
+
+@pytest.mark.parametrize("name,over,kinds", [
+    ("c2", dict(context=4099, k=300), (D, S, P)),                       # several chunks + ragged tail
+    ("c3", dict(context=8229, k=512, tau=512.0), (D, S, P)),            # MHA (G = 1)
+    ("c4", dict(seq_lens=(777, 64, 1, 2500, 1300), k=256), (D, S, P)),  # ragged batch, k > N for some
+    ("c5", dict(context=6000, batch=2, k=1024), (S, P)),                # Zipf mass
+    ("c1", dict(context=1000, k=1000), (S, P)),                         # k = N: sparse == full
+    ("c1", dict(context=333, k=64, head_dim=128, num_q_heads=16), (D, S, P)),   # fp32 d128, G = 8
+    ("c2", dict(context=900, k=100, head_dim=64, num_q_heads=16), (D, S, P)),   # bf16 d64, G = 2
+])
+def test_scaled_configs(name, over, kinds):
+    w = W.workload(name, **over)
+    tag = "%s%s" % (name, sorted(over.items()))
+    run_layer_checks(w, kinds, tag)
+
+
+def test_sparse_with_k_equal_n_matches_full_attention():
+    w = W.workload("c2", context=2048, k=2048)
+    (q, K, V), = device_layers(w, [3])
+    c = Case(w, K, q)
+    pos = torch.arange(2048, dtype=torch.int32, device=DEV).repeat(1, w.num_kv_heads, 1).contiguous()
+    a, b = c.out_like(q), c.out_like(q)
+    c.td.full_attend(c.shape, q, K, V, a)
+    c.td.sparse_attend(c.shape, q, K, V, pos, 2048, b)
+    torch.cuda.synchronize()
+    ref = O.full(host(q), host(K), host(V), w.seq_lens)
+    check_output(a, ref, "full")
+    check_output(b, ref, "sparse k=N")
+    c.td.close()
+
+
+def test_sparse_skips_invalid_positions_and_empty_rho_gives_zeros():
+    w = W.workload("c2", context=500, k=8, num_kv_heads=8)
+    (q, K, V), = device_layers(w, [0])
+    c = Case(w, K, q)
+    pos = torch.tensor([3, 17, -1, 499, 500, 100000, -1, 250], dtype=torch.int32, device=DEV)
+    pos = pos.repeat(1, w.num_kv_heads, 1).contiguous()
+    pos[0, 1] = -1                                           # KV head 1: nothing selected
+    out = c.out_like(q)
+    c.td.sparse_attend(c.shape, q, K, V, pos, 8, out)
+    torch.cuda.synchronize()
+    clean = host(pos).clone()
+    clean[clean >= 500] = -1
+    check_output(out, O.sparse(host(q), host(K), host(V), w.seq_lens, clean), "invalid positions")
+    assert (host(out)[0, 4:8] == 0).all()
+    c.td.close()
+
+
+def test_token_major_cache_layout():
+    # K, V stored [B][N][Hkv][d] and passed through the strides
+    w = W.workload("c2", context=1500, k=128)
+    (q, K, V), = device_layers(w, [1])
+    Kt = K.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    Vt = V.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    c = Case(w, Kt, q)
+    assert c.shape.kv_stride_tok == w.num_kv_heads * w.head_dim
+    out = c.out_like(q)
+    pos = torch.zeros((1, w.num_kv_heads, w.k), dtype=torch.int32, device=DEV)
+    c.td.select_tokens(c.shape, q, Kt, Vt, w.k, out, pos)
+    torch.cuda.synchronize()
+    o_out, o_pos, o_scores = O.select(host(q), host(K), host(V), w.seq_lens, w.k, return_scores=True)
+    check_output(out, o_out, "token-major")
+    check_positions(pos, o_scores, w.seq_lens, w.k, "token-major")
+    c.td.close()
+
+
+def test_results_are_deterministic():
+    w = W.workload("c2", context=5000, k=256)
+    (q, K, V), = device_layers(w, [2])
+    c = Case(w, K, q)
+    outs, poss = [], []
+    for _ in range(2):
+        out = c.out_like(q)
+        pos = torch.zeros((1, w.num_kv_heads, w.k), dtype=torch.int32, device=DEV)
+        c.td.select_tokens(c.shape, q, K, V, w.k, out, pos)
+        torch.cuda.synchronize()
+        outs.append(out)
+        poss.append(pos)
+    assert torch.equal(outs[0], outs[1]) and torch.equal(poss[0], poss[1])
+    c.td.close()
+
+
+def test_bad_arguments_are_rejected_on_the_host():
+    w = W.workload("c2", context=256, k=16)
+    (q, K, V), = device_layers(w, [0])
+    c = Case(w, K, q)
+    out = c.out_like(q)
+    pos = torch.zeros((1, w.num_kv_heads, 16), dtype=torch.int32, device=DEV)
+    with pytest.raises(tidal.TidalError) as e:
+        c.td.sparse_attend(c.shape, q, K, V, pos, 0, out)
+    assert e.value.status == tidal.ERR_INVALID_ARG
+    with pytest.raises(tidal.TidalError) as e:
+        c.td.decode_step(c.shape, (D, P), [q, q], [K, K], [V, V], 16, [out, out], pos)
+    assert e.value.status == tidal.ERR_INVALID_ARG and "before any selection" in str(e.value)
+    big = tidal.make_shape(q, K, c.lens)
+    big.max_seq_len = 1 << 20                                 # needs more score workspace than was created
+    with pytest.raises(tidal.TidalError) as e:
+        c.td.select_tokens(big, q, K, V, 16, out, pos)
+    assert e.value.status == tidal.ERR_WORKSPACE
+    with pytest.raises(tidal.TidalError) as e:
+        c.td.full_attend(c.shape, q[:, :, 1:], K, V, out)     # misaligned q
+    assert e.value.status == tidal.ERR_INVALID_ARG
+    c.td.close()
