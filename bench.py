@@ -1,0 +1,227 @@
+"""Decode-step attention benchmark (one MI355X).
+
+A "step" is one pass of the whole hot path - every layer of the schedule: full attention,
+token selection (attention + fused score write + top-k) and position persistent sparse
+attention - over one batch of synthetic, HBM-resident inputs, enqueued through
+td_decode_step.  Timed iterations rotate over independent copies of the inputs so that
+a small working set is not served from the 256 MB Infinity Cache.
+
+Prints ONE JSON line on stdout; progress goes to stderr.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+DESCRIPTIONS = {
+    "c1": "c1 toy: 4 layers (full, selection, 2 sparse), batch 1, 8 q / 2 KV heads, d 64, context 2048, k 128, fp32",
+    "c2": "c2 Llama-3-8B shape: 32 layers (2 full, selection at 2 and 13, 28 sparse), batch 1, 32 q / 8 KV heads, "
+          "d 128, context 32768, k 2048, bf16 KV",
+    "c3": "c3 Llama-2-7B MHA shape: 32 layers, batch 1, 32 q / 32 KV heads, d 128, context 131072, k 4096, bf16 KV",
+    "c4": "c4 batched Llama-3-8B shape: 32 layers, batch 16, ragged contexts 8192..65536, k 2048, bf16 KV",
+    "c5": "c5 Llama-3-8B shape: 32 layers, batch 4, context 131072, k sweep, bf16 KV, Zipf(1.1) mass",
+}
+
+
+def log(msg):
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=60)
+    ap.add_argument("--warmup", type=int, default=6)
+    ap.add_argument("--workload", default="c2", choices=sorted(DESCRIPTIONS))
+    ap.add_argument("--k", type=int, default=0, help="token budget override (c5 sweep)")
+    ap.add_argument("--copies", type=int, default=0, help="independent input copies to rotate over")
+    ap.add_argument("--no-graph", action="store_true", help="enqueue eagerly instead of replaying a HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kernel-reps", type=int, default=40)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus %d is not supported "
+              "(no collectives or sharding are part of it)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2410_05076_amd import tidal, workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    tidal.lib()                      # fail loudly if the HIP library is missing
+    dev = "cuda:0"
+    over = {"k": args.k} if args.k else {}
+    w = W.workload(args.workload, **over)
+    step_bytes = w.algorithmic_bytes_per_step()
+    cache_bytes = w.num_layers * 2 * w.batch * w.num_kv_heads * w.max_seq_len * w.head_dim * w.elem_bytes
+    copies = args.copies or (3 if cache_bytes <= 8 * 2**30 else 1)
+    log("%s: cache %.1f GiB per copy, %d cop%s, %.1f MB algorithmic bytes per step"
+        % (w.name, cache_bytes / 2**30, copies, "y" if copies == 1 else "ies", step_bytes / 1e6))
+
+    lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=dev)
+    n_sel = sum(1 for x in w.schedule if x == W.SELECT)
+    sets = []
+    for c in range(copies):
+        wc = W.workload(args.workload, seed=w.seed + 7919 * c, **over)
+        heavy = W.heavy_positions(wc)
+        ranks = W.zipf_ranks(wc) if wc.structure == "zipf" else None
+        layers = [W.make_layer(wc, i, dev, heavy=heavy, ranks=ranks) for i in range(wc.num_layers)]
+        qs, Ks, Vs = zip(*layers)
+        outs = [torch.zeros_like(q) for q in qs]
+        pos = torch.full((n_sel, w.batch, w.num_kv_heads, w.k), -1, dtype=torch.int32, device=dev)
+        sets.append((qs, Ks, Vs, outs, pos))
+        log("generated copy %d" % c)
+    shape = tidal.make_shape(sets[0][0][0], sets[0][1][0], lens)
+    td = tidal.Tidal(shape, w.k)
+
+    def enqueue(c):
+        qs, Ks, Vs, outs, pos = sets[c]
+        td.decode_step(shape, w.schedule, qs, Ks, Vs, w.k, outs, pos)
+
+    for c in range(copies):
+        enqueue(c)
+    torch.cuda.synchronize()
+
+    use_graph = not args.no_graph
+    graphs = []
+    if use_graph:
+        for c in range(copies):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                enqueue(c)
+            graphs.append(g)
+        torch.cuda.synchronize()
+
+    def step(i):
+        c = i % copies
+        if use_graph:
+            graphs[c].replay()
+        else:
+            enqueue(c)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) / args.steps * 1e3
+    us_per_step = ms_per_step * 1e3
+    log("%.1f us per decode step (%s)" % (us_per_step, "graph replay" if use_graph else "eager"))
+
+    # per-launch duration of each layer kind, HIP events on the launch stream
+    def time_kind(kind, reps):
+        idx = [i for i, x in enumerate(w.schedule) if x == kind]
+        if not idx:
+            return None
+        evs = []
+        for r in range(reps):
+            qs, Ks, Vs, outs, pos = sets[r % copies]
+            i = idx[(r // copies) % len(idx)]
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            if kind == W.DENSE:
+                td.full_attend(shape, qs[i], Ks[i], Vs[i], outs[i])
+            elif kind == W.SELECT:
+                td.select_tokens(shape, qs[i], Ks[i], Vs[i], w.k, outs[i], pos[0])
+            else:
+                td.sparse_attend(shape, qs[i], Ks[i], Vs[i], pos[0], w.k, outs[i])
+            b.record()
+            evs.append((a, b))
+        torch.cuda.synchronize()
+        ts = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
+        return sum(ts) / len(ts), ts[len(ts) // 2]
+
+    per_kind = {}
+    for name, kind in (("full", W.DENSE), ("select", W.SELECT), ("sparse", W.SPARSE)):
+        r = time_kind(kind, args.kernel_reps)
+        if r:
+            per_kind[name] = {"avg_us": round(r[0], 2), "median_us": round(r[1], 2)}
+    dense_bytes = w.kv_bytes_per_layer()
+    dense_us = per_kind["full"]["avg_us"]
+    achieved = dense_bytes / (dense_us * 1e-6) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "attend_dense_%s_traffic.json" % w.name)
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get("hbm_bytes_per_launch")
+    roofline = {"kernel": "attend_split_kernel (full attention layer: K and V of one layer streamed once)",
+                "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                "algorithmic_bytes_per_launch": dense_bytes, "avg_launch_us": dense_us}
+    for name, nbytes in (("select", dense_bytes), ("sparse", w.sparse_bytes_per_layer())):
+        if name in per_kind:
+            per_kind[name]["GBps"] = round(nbytes / (per_kind[name]["avg_us"] * 1e-6) / 1e9, 1)
+    per_kind["full"]["GBps"] = round(achieved, 1)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(w, sets[0], torch)
+
+    out = {
+        "metric": "decode_step_attention_us", "value": round(us_per_step, 2), "unit": "us",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": DESCRIPTIONS[w.name], "k": w.k, "input_copies_rotated": copies,
+                   "launch": "hip graph replay of td_decode_step" if use_graph else "eager td_decode_step"},
+        "step_hbm": {"algorithmic_bytes": step_bytes,
+                     "achieved_GBps": round(step_bytes / (us_per_step * 1e-6) / 1e9, 1),
+                     "frac_of_peak": round(step_bytes / (us_per_step * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)},
+        "per_layer_kind": per_kind,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    td.close()
+    print(json.dumps(out), flush=True)
+
+
+def cpu_baseline(w, inputs, torch):
+    """The CPU oracle on the host cores, one layer at a time (one layer's K, V on the host at once).
+
+    Small caches: every layer of one decode step.  Large caches: one layer of each kind,
+    scaled by the number of layers of that kind (stated in `sample`)."""
+    from oracle import tidal_oracle as O
+    from paper_2410_05076_amd import workloads as W
+    qs, Ks, Vs, _, _ = inputs
+    layer_bytes = 2 * Ks[0].numel() * Ks[0].element_size()
+    whole = layer_bytes * w.num_layers <= 6 * 2**30
+    kinds = list(w.schedule)
+    if whole:
+        todo = list(range(w.num_layers))
+    else:
+        todo = [kinds.index(W.DENSE), kinds.index(W.SELECT), kinds.index(W.SPARSE)]
+    t_kind = {W.DENSE: [], W.SELECT: [], W.SPARSE: []}
+    rho = None
+    for i in sorted(todo):
+        q, K, V = qs[i].cpu(), Ks[i].cpu(), Vs[i].cpu()
+        t0 = time.perf_counter()
+        if kinds[i] == W.DENSE:
+            O.full(q, K, V, w.seq_lens)
+        elif kinds[i] == W.SELECT:
+            _, rho = O.select(q, K, V, w.seq_lens, w.k)
+        else:
+            O.sparse(q, K, V, w.seq_lens, rho)
+        t_kind[kinds[i]].append(time.perf_counter() - t0)
+        log("oracle layer %d: %.3f s" % (i, t_kind[kinds[i]][-1]))
+    total = 0.0
+    for kind, ts in t_kind.items():
+        if ts:
+            total += sum(ts) if whole else sum(ts) / len(ts) * kinds.count(kind)
+    sample = ("all %d layers of one %s decode step, one layer at a time" % (w.num_layers, w.name) if whole else
+              "one full, one selection and one sparse layer of %s, each scaled by its layer count" % w.name)
+    return {"value": round(total * 1e6, 1), "unit": "us", "cores": O.num_threads(), "kind": "oracle",
+            "sample": sample}
+
+
+if __name__ == "__main__":
+    main()
