@@ -45,6 +45,7 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="enqueue eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-reps", type=int, default=40)
+    ap.add_argument("--tune", default="", help="target_workgroups,min_chunk_dense,min_chunk_sparse (0 = default)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus %d is not supported "
@@ -80,6 +81,8 @@ def main():
         log("generated copy %d" % c)
     shape = tidal.make_shape(sets[0][0][0], sets[0][1][0], lens)
     td = tidal.Tidal(shape, w.k)
+    if args.tune:
+        td.set_tuning(*[int(x) for x in args.tune.split(",")])
 
     def enqueue(c):
         qs, Ks, Vs, outs, pos = sets[c]

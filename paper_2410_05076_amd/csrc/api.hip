@@ -61,7 +61,7 @@ const char *shape_problem(const td_shape *s, int32_t k, td_status *code) {
 bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
 struct Workspace {
-    size_t part_acc, part_ml, scores, total;
+    size_t part_acc, part_ml, counters, scores, total;
     int64_t score_stride;
 };
 
@@ -71,7 +71,8 @@ Workspace workspace_layout(const td_shape *s, int32_t k) {
     w.score_stride = (int64_t)align_up((size_t)s->max_seq_len, 4);
     w.part_acc = 0;
     w.part_ml = align_up(w.part_acc + heads * kSplitsMax * s->head_dim * sizeof(float), 256);
-    w.scores = align_up(w.part_ml + heads * kSplitsMax * 2 * sizeof(float), 256);
+    w.counters = align_up(w.part_ml + heads * kSplitsMax * 2 * sizeof(float), 256);
+    w.scores = align_up(w.counters + (size_t)s->batch * s->num_kv_heads * sizeof(int32_t), 256);
     const size_t score_bytes = k > 0 ? (size_t)s->batch * s->num_kv_heads * w.score_stride * sizeof(float) : 0;
     w.total = align_up(w.scores + score_bytes, 256);
     return w;
@@ -105,6 +106,7 @@ td_status attend(td_ctx *ctx, const td_shape *s, int mode, const void *q, const 
     p.score_stride = score_stride;
     p.part_acc = reinterpret_cast<float *>(ctx->workspace + w.part_acc);
     p.part_ml = reinterpret_cast<float *>(ctx->workspace + w.part_ml);
+    p.counters = reinterpret_cast<int32_t *>(ctx->workspace + w.counters);
     p.stride_batch = s->kv_stride_batch;
     p.stride_head = s->kv_stride_head;
     p.stride_tok = s->kv_stride_tok;
@@ -172,6 +174,7 @@ td_status td_create(td_ctx **out, int device, size_t workspace_bytes) {
     ctx->device = device;
     hipError_t e = hipSetDevice(device);
     if (e == hipSuccess && workspace_bytes) e = hipMalloc(reinterpret_cast<void **>(&ctx->workspace), workspace_bytes);
+    if (e == hipSuccess && workspace_bytes) e = hipMemset(ctx->workspace, 0, workspace_bytes);  // chunk counters start at zero
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
         delete ctx;

@@ -9,7 +9,9 @@
 // fetches 64/LPR whole rows, fully coalesced; a dot product is finished by a DPP reduction
 // over those LPR lanes.  Each lane keeps an online-softmax state (running max, sum, its
 // slice of the output) per query head; states are merged across row groups, waves and
-// finally chunks (second kernel) with the usual rescaling rule.
+// finally chunks with the usual rescaling rule.  Chunk partials go to a workspace; the
+// workgroup that finishes last for a (sequence, KV head), found with a device-scope
+// ticket counter, merges them and writes the output, so a layer is one launch.
 //
 // Token selection (Sec. 3.1): the scaled inner products are not turned into probabilities;
 // their sum over the group's query heads is written once per token while the row is in
@@ -76,6 +78,19 @@ __device__ __forceinline__ uint32_t bf16_bits_rne(float f) {
     uint32_t u = __float_as_uint(f);
     if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;  // NaN stays NaN
     return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+template <int DT>
+__device__ __forceinline__ void store_out(void *out, int64_t i, float v) {
+    if constexpr (DT == TD_BF16)
+        static_cast<uint16_t *>(out)[i] = (uint16_t)bf16_bits_rne(v);
+    else
+        static_cast<float *>(out)[i] = v;
+}
+
+// Device-scope store that goes through to memory instead of staying in this XCD's L2.
+__device__ __forceinline__ void publish(float *p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 template <int DT, int D, int G, int MODE>
@@ -201,78 +216,139 @@ __global__ __launch_bounds__(kThreads) void attend_split_kernel(const AttendPara
         }
     }
 
-    // merge the row groups of this wave (symmetric, every lane ends with the same state)
+    // ---- merge the online-softmax states of the workgroup's row groups through LDS,
+    // at most four heads at a time to bound the LDS footprint
+    constexpr int RG = kWavesPerGroup * TPW;  // row groups per workgroup
+    constexpr int GC = G < 4 ? G : 4;         // heads per pass
+    __shared__ float s_m[RG][GC], s_l[RG][GC], s_w[RG][GC], s_max[GC];
+    // row-group accumulators [RG][GC][D]; reused by the final merge as [kThreads] float4 + float2
+    constexpr int kAccFloats = RG * GC * D > kThreads * 6 ? RG * GC * D : kThreads * 6;
+    __shared__ __align__(16) float s_acc[kAccFloats];
+    const int rg = wave * TPW + r;
+    const int ns = (n_tok + p.chunk - 1) / p.chunk;  // chunks of this (sequence, KV head)
 #pragma unroll
-    for (int o = LPR; o < kWave; o <<= 1) {
+    for (int h0 = 0; h0 < G; h0 += GC) {
+        if (h0) __syncthreads();
 #pragma unroll
-        for (int i = 0; i < G; ++i) {
-            const float mo = __shfl_xor(m[i], o), lo = __shfl_xor(l[i], o);
-            const float mx = fmaxf(m[i], mo);
-            const float a = fast_exp2(m[i] - mx), bb = fast_exp2(mo - mx);
-            l[i] = l[i] * a + lo * bb;
+        for (int i = 0; i < GC; ++i) {
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) acc[i][e] = acc[i][e] * a + __shfl_xor(acc[i][e], o) * bb;
-            m[i] = mx;
-        }
-    }
-
-    __shared__ float s_ml[kWavesPerGroup][G][2];
-    __shared__ float s_acc[kWavesPerGroup][G][D];
-    if (lane < LPR) {
-#pragma unroll
-        for (int i = 0; i < G; ++i) {
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) s_acc[wave][i][c * EPL + e] = acc[i][e];
+            for (int e = 0; e < EPL; e += 4)
+                *reinterpret_cast<float4 *>(&s_acc[(rg * GC + i) * D + c * EPL + e]) =
+                    make_float4(acc[h0 + i][e], acc[h0 + i][e + 1], acc[h0 + i][e + 2], acc[h0 + i][e + 3]);
             if (c == 0) {
-                s_ml[wave][i][0] = m[i];
-                s_ml[wave][i][1] = l[i];
+                s_m[rg][i] = m[h0 + i];
+                s_l[rg][i] = l[h0 + i];
+            }
+        }
+        __syncthreads();
+        if (threadIdx.x < RG * GC) {
+            const int i = threadIdx.x % GC, x = threadIdx.x / GC;
+            float mx = s_m[0][i];
+#pragma unroll
+            for (int y = 1; y < RG; ++y) mx = fmaxf(mx, s_m[y][i]);
+            s_w[x][i] = fast_exp2(s_m[x][i] - mx);
+            if (x == 0) s_max[i] = mx;
+        }
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < GC * D; idx += kThreads) {
+            const int i = idx / D, ch = idx % D;
+            float ls = 0.f, as = 0.f;
+#pragma unroll
+            for (int y = 0; y < RG; ++y) {
+                const float w = s_w[y][i];
+                ls = fmaf(s_l[y][i], w, ls);
+                as = fmaf(s_acc[(y * GC + i) * D + ch], w, as);
+            }
+            const int64_t head = (int64_t)b * p.num_q_heads + g * G + h0 + i;
+            if (ns == 1) {  // the only chunk: finish here, no partials
+                store_out<DT>(p.out, head * D + ch, ls > 0.f ? as / ls : 0.f);
+            } else {
+                const int64_t slot = head * p.num_splits + split;
+                publish(&p.part_acc[slot * D + ch], as);
+                if (ch == 0) {
+                    publish(&p.part_ml[slot * 2], s_max[i]);
+                    publish(&p.part_ml[slot * 2 + 1], ls);
+                }
             }
         }
     }
-    __syncthreads();
-    for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {
-        const int i = idx / D, ch = idx % D;
-        float mx = s_ml[0][i][0];
-#pragma unroll
-        for (int w = 1; w < kWavesPerGroup; ++w) mx = fmaxf(mx, s_ml[w][i][0]);
-        float ls = 0.f, as = 0.f;
-#pragma unroll
-        for (int w = 0; w < kWavesPerGroup; ++w) {
-            const float a = fast_exp2(s_ml[w][i][0] - mx);
-            ls += s_ml[w][i][1] * a;
-            as += s_acc[w][i][ch] * a;
-        }
-        const int64_t slot = ((int64_t)b * p.num_q_heads + g * G + i) * p.num_splits + split;
-        p.part_acc[slot * D + ch] = as;
-        if (ch == 0) {
-            p.part_ml[slot * 2] = mx;
-            p.part_ml[slot * 2 + 1] = ls;
-        }
-    }
-}
+    if (ns == 1) return;
 
-// Merges the chunk partials of one (sequence, query head) and writes the output row.
-template <int DT, int D>
-__global__ __launch_bounds__(D) void attend_merge_kernel(const AttendParams p, const int sparse) {
-    const int h = blockIdx.x, b = blockIdx.y, ch = threadIdx.x;
-    const int N = min(max(p.seq_lens[b], 0), p.max_seq_len);
-    const int n_tok = sparse ? (N > 0 ? p.k : 0) : N;
-    const int ns = (n_tok + p.chunk - 1) / p.chunk;
-    const int64_t slot0 = ((int64_t)b * p.num_q_heads + h) * p.num_splits;
-    float mx = kEmptyMax;
-    for (int s = 0; s < ns; ++s) mx = fmaxf(mx, p.part_ml[(slot0 + s) * 2]);
-    float ls = 0.f, as = 0.f;
-    for (int s = 0; s < ns; ++s) {
-        const float a = fast_exp2(p.part_ml[(slot0 + s) * 2] - mx);
-        ls += p.part_ml[(slot0 + s) * 2 + 1] * a;
-        as += p.part_acc[(slot0 + s) * D + ch] * a;
+    // The chunk that finishes last merges all partials of its (sequence, KV head).
+    // Partials are published with device-scope write-through stores and every wave waits
+    // for its stores to complete before the barrier, so they are in memory before this
+    // workgroup's ticket is taken; only the merging workgroup pays for an acquire (cache
+    // invalidate).  A release fence in every workgroup would write back the whole L2 each
+    // time.  The counter returns to zero for the next launch.
+    __shared__ int s_last;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int *counter = p.counters + b * p.num_kv_heads + g;
+        const int done = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_last = done == ns - 1;
+        if (s_last) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    const float o = ls > 0.f ? as / ls : 0.f;
-    const int64_t oi = ((int64_t)b * p.num_q_heads + h) * D + ch;
-    if constexpr (DT == TD_BF16)
-        ((uint16_t *)p.out)[oi] = (uint16_t)bf16_bits_rne(o);
-    else
-        ((float *)p.out)[oi] = o;
+    __syncthreads();
+    if (!s_last) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+
+    // One pass over the partials: thread (sg, col) folds chunks sg, sg + NG, ... of one float4
+    // column of one head with the online rescaling rule, then the NG threads of a column
+    // are folded through LDS.
+    constexpr int COLS = G * D / 4;      // float4 columns over all heads of the group
+    constexpr int NG = kThreads / COLS;  // chunk groups working in parallel
+    static_assert(NG >= 1 && NG * COLS == kThreads, "G * D / 4 must divide the workgroup size");
+    const int col = threadIdx.x % COLS, sg = threadIdx.x / COLS;
+    const int hi = col / (D / 4), c4 = col % (D / 4);
+    const int64_t head = (int64_t)b * p.num_q_heads + g * G + hi;
+    const float2 *ml = reinterpret_cast<const float2 *>(p.part_ml) + head * p.num_splits;
+    const float4 *pa = reinterpret_cast<const float4 *>(p.part_acc) + head * p.num_splits * (D / 4) + c4;
+    float mm = kEmptyMax, ll = 0.f;
+    float4 aa = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 8
+    for (int s = sg; s < ns; s += NG) {
+        const float2 v = ml[s];
+        const float4 x = pa[(int64_t)s * (D / 4)];
+        const float mn = fmaxf(mm, v.x);
+        const float wa = fast_exp2(mm - mn), wb = fast_exp2(v.x - mn);
+        ll = ll * wa + v.y * wb;
+        aa.x = aa.x * wa + x.x * wb;
+        aa.y = aa.y * wa + x.y * wb;
+        aa.z = aa.z * wa + x.z * wb;
+        aa.w = aa.w * wa + x.w * wb;
+        mm = mn;
+    }
+    if constexpr (NG > 1) {
+        float4 *red_a = reinterpret_cast<float4 *>(s_acc);                   // [kThreads], s_acc is free now
+        float2 *red_ml = reinterpret_cast<float2 *>(red_a + kThreads);       // [kThreads]
+        red_a[threadIdx.x] = aa;
+        red_ml[threadIdx.x] = make_float2(mm, ll);
+        __syncthreads();
+        if (sg == 0) {
+#pragma unroll
+            for (int o = 1; o < NG; ++o) {
+                const float2 v = red_ml[o * COLS + col];
+                const float4 x = red_a[o * COLS + col];
+                const float mn = fmaxf(mm, v.x);
+                const float wa = fast_exp2(mm - mn), wb = fast_exp2(v.x - mn);
+                ll = ll * wa + v.y * wb;
+                aa.x = aa.x * wa + x.x * wb;
+                aa.y = aa.y * wa + x.y * wb;
+                aa.z = aa.z * wa + x.z * wb;
+                aa.w = aa.w * wa + x.w * wb;
+                mm = mn;
+            }
+        }
+    }
+    if (sg == 0) {
+        const float inv = ll > 0.f ? 1.f / ll : 0.f;
+        const int64_t oi = head * D + c4 * 4;
+        store_out<DT>(p.out, oi, aa.x * inv);
+        store_out<DT>(p.out, oi + 1, aa.y * inv);
+        store_out<DT>(p.out, oi + 2, aa.z * inv);
+        store_out<DT>(p.out, oi + 3, aa.w * inv);
+    }
 }
 
 template <int DT, int D, int G>
@@ -289,10 +365,6 @@ hipError_t launch_mode(int mode, const AttendParams &p, hipStream_t stream) {
         hipLaunchKernelGGL((attend_split_kernel<DT, D, G, kSparse>), grid, block, 0, stream, p);
         break;
     }
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((attend_merge_kernel<DT, D>), dim3(p.num_q_heads, p.batch), dim3(D), 0, stream, p,
-                       mode == kSparse ? 1 : 0);
     return hipGetLastError();
 }
 

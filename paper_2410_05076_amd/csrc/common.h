@@ -21,6 +21,7 @@ struct AttendParams {
     float *scores;             // select: [B][Hkv][score_stride]
     float *part_acc;           // [B][Hq][num_splits][D]
     float *part_ml;            // [B][Hq][num_splits][2]  (running max in log2 units, sum)
+    int32_t *counters;         // [B][Hkv] chunks finished so far; zero between launches
     void *out;                 // [B][Hq][D]
     int64_t stride_batch, stride_head, stride_tok;  // elements
     int64_t score_stride;
@@ -32,7 +33,7 @@ struct AttendParams {
     float scale;
 };
 
-// Enqueues the split attention kernel followed by the merge kernel.
+// Enqueues the split attention kernel (the last chunk to finish merges the partials).
 hipError_t launch_attend(int dtype, int head_dim, int group, int mode, const AttendParams &p,
                          hipStream_t stream);
 
