@@ -44,7 +44,10 @@
  *     enqueued and returned as TD_ERR_INVALID_ARG / TD_ERR_UNSUPPORTED /
  *     TD_ERR_WORKSPACE; a failed HIP call gives TD_ERR_HIP.  td_last_error
  *     returns a text for the most recent failure on that context.
- *     Supported: head_dim 64 or 128, group size 1, 2, 4 or 8.
+ *     Supported: head_dim 64 or 128, group size 1, 2, 4 or 8,
+ *     batch * num_kv_heads <= 65535.
+ *   - A context serves one stream at a time: calls that use the same context
+ *     must be ordered on one stream (they share its workspace).
  */
 #ifndef TIDAL_H
 #define TIDAL_H
@@ -92,6 +95,9 @@ td_status td_validate(const td_shape *shape, int32_t k);
  * selection or sparse call will be made) needs.  Returns 0 for an invalid shape. */
 size_t td_workspace_bytes(const td_shape *shape, int32_t k);
 
+/* Workspace bytes that td_topk needs for `rows` rows of at most `max_len` scores. */
+size_t td_topk_workspace_bytes(int32_t rows, int32_t max_len);
+
 /* Creates a context on HIP device `device` and allocates `workspace_bytes` of
  * device memory once.  Synchronises the device. */
 td_status td_create(td_ctx **out, int device, size_t workspace_bytes);
@@ -136,8 +142,7 @@ td_status td_decode_step(td_ctx *ctx, const td_shape *shape, int32_t num_layers,
 
 /* Tuning knobs for measurement sweeps (0 keeps the default): target number of
  * workgroups per attention launch, and the smallest token chunk per workgroup
- * for full and for sparse attention.  Affects td_workspace_bytes' answer only
- * through the process-wide defaults, so size the workspace first. */
+ * for full and for sparse attention.  The workspace size does not depend on them. */
 td_status td_set_tuning(td_ctx *ctx, int32_t target_workgroups, int32_t min_chunk_dense,
                         int32_t min_chunk_sparse);
 

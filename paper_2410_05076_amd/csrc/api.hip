@@ -53,27 +53,34 @@ const char *shape_problem(const td_shape *s, int32_t k, td_status *code) {
     if (s->head_dim != 64 && s->head_dim != 128) return "head_dim must be 64 or 128";
     const int g = s->num_q_heads / s->num_kv_heads;
     if (g != 1 && g != 2 && g != 4 && g != 8) return "group size must be 1, 2, 4 or 8";
-    if (s->batch > 65535 || s->num_kv_heads > 65535) return "batch or num_kv_heads above 65535";
+    if (s->batch > 65535 || s->num_kv_heads > 65535 || (int64_t)s->batch * s->num_kv_heads > 65535)
+        return "batch * num_kv_heads above 65535";
     *code = TD_OK;
     return nullptr;
 }
 
 bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
+// Workspace: [ticket counters, fixed size][top-k scratch][chunk partials][group scores].
+// Only the counters carry state from one call to the next (they are zero between launches).
 struct Workspace {
-    size_t part_acc, part_ml, counters, scores, total;
+    size_t counters, topk, part_acc, part_ml, scores, total;
     int64_t score_stride;
 };
+
+constexpr size_t kCountersBytes = (size_t)kCountersMax * sizeof(int32_t);
 
 Workspace workspace_layout(const td_shape *s, int32_t k) {
     Workspace w;
     const size_t heads = (size_t)s->batch * s->num_q_heads;
+    const int32_t rows = s->batch * s->num_kv_heads;
     w.score_stride = (int64_t)align_up((size_t)s->max_seq_len, 4);
-    w.part_acc = 0;
+    w.counters = 0;
+    w.topk = kCountersBytes;
+    w.part_acc = align_up(w.topk + (k > 0 ? topk_scratch_bytes(rows, s->max_seq_len) : 0), 256);
     w.part_ml = align_up(w.part_acc + heads * kSplitsMax * s->head_dim * sizeof(float), 256);
-    w.counters = align_up(w.part_ml + heads * kSplitsMax * 2 * sizeof(float), 256);
-    w.scores = align_up(w.counters + (size_t)s->batch * s->num_kv_heads * sizeof(int32_t), 256);
-    const size_t score_bytes = k > 0 ? (size_t)s->batch * s->num_kv_heads * w.score_stride * sizeof(float) : 0;
+    w.scores = align_up(w.part_ml + heads * kSplitsMax * 2 * sizeof(float), 256);
+    const size_t score_bytes = k > 0 ? (size_t)rows * w.score_stride * sizeof(float) : 0;
     w.total = align_up(w.scores + score_bytes, 256);
     return w;
 }
@@ -107,6 +114,7 @@ td_status attend(td_ctx *ctx, const td_shape *s, int mode, const void *q, const 
     p.part_acc = reinterpret_cast<float *>(ctx->workspace + w.part_acc);
     p.part_ml = reinterpret_cast<float *>(ctx->workspace + w.part_ml);
     p.counters = reinterpret_cast<int32_t *>(ctx->workspace + w.counters);
+    p.topk_scratch = ctx->workspace + w.topk;
     p.stride_batch = s->kv_stride_batch;
     p.stride_head = s->kv_stride_head;
     p.stride_tok = s->kv_stride_tok;
@@ -145,7 +153,7 @@ td_status select_tokens(td_ctx *ctx, const td_shape *s, const void *q, const voi
     td_status st = attend(ctx, s, kSelect, q, K, V, nullptr, k, scores, stride, out, stream);
     if (st != TD_OK) return st;
     const hipError_t e = launch_topk(scores, stride, s->batch * s->num_kv_heads, s->seq_lens, s->num_kv_heads,
-                                     s->max_seq_len, k, positions, stream);
+                                     s->max_seq_len, k, positions, ctx->workspace + w.topk, false, stream);
     if (e != hipSuccess) return fail(ctx, TD_ERR_HIP, "top-k launch failed: %s", hipGetErrorString(e));
     return TD_OK;
 }
@@ -164,6 +172,11 @@ size_t td_workspace_bytes(const td_shape *shape, int32_t k) {
     td_status code;
     if (shape_problem(shape, k, &code)) return 0;
     return workspace_layout(shape, k).total;
+}
+
+size_t td_topk_workspace_bytes(int32_t rows, int32_t max_len) {
+    if (rows < 1 || max_len < 1) return 0;
+    return align_up(kCountersBytes + topk_scratch_bytes(rows, max_len), 256);
 }
 
 td_status td_create(td_ctx **out, int device, size_t workspace_bytes) {
@@ -236,8 +249,11 @@ td_status td_topk(td_ctx *ctx, const float *scores, int64_t row_stride, int32_t 
     if (rows < 1 || rows_per_len < 1 || max_len < 1 || k < 1 || row_stride < max_len)
         return fail(ctx, TD_ERR_INVALID_ARG, "%s", "rows, rows_per_len, max_len, k must be >= 1 and row_stride >= max_len");
     if (misaligned(scores)) return fail(ctx, TD_ERR_INVALID_ARG, "%s", "scores must be 16-byte aligned");
+    if (rows > 65535) return fail(ctx, TD_ERR_UNSUPPORTED, "%s", "more than 65535 rows");
+    if (kCountersBytes + topk_scratch_bytes(rows, max_len) > ctx->workspace_bytes)
+        return fail(ctx, TD_ERR_WORKSPACE, "%s", "workspace is smaller than td_topk_workspace_bytes(rows, max_len)");
     const hipError_t e = launch_topk(scores, row_stride, rows, row_lens, rows_per_len, max_len, k, positions,
-                                     static_cast<hipStream_t>(hip_stream));
+                                     ctx->workspace + kCountersBytes, true, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return fail(ctx, TD_ERR_HIP, "top-k launch failed: %s", hipGetErrorString(e));
     return TD_OK;
 }

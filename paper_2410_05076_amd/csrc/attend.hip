@@ -105,6 +105,11 @@ __global__ __launch_bounds__(kThreads) void attend_split_kernel(const AttendPara
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
     const int r = lane / LPR, c = lane % LPR;
 
+    if constexpr (MODE == kSelect) {  // leave the row's top-k state clear for the kernels that follow
+        TopkRow *row = static_cast<TopkRow *>(p.topk_scratch) + (b * p.num_kv_heads + g);
+        for (int i = split * kThreads + threadIdx.x; i < kTopkBins; i += p.num_splits * kThreads) row->hist[i] = 0;
+        if (split == 0 && threadIdx.x == 0) row->ncand = 0;
+    }
     const int N = min(max(p.seq_lens[b], 0), p.max_seq_len);
     const int n_tok = MODE == kSparse ? (N > 0 ? p.k : 0) : N;
     const int t0 = split * p.chunk;

@@ -11,6 +11,23 @@ constexpr int kWave = 64;
 constexpr int kSplitsMax = 256;        // upper bound on token chunks per (sequence, KV head)
 constexpr int kSparseChunkMax = 2048;  // positions of one chunk are staged in LDS
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr int kCountersMax = 65536;    // ticket counters, one per (sequence, KV head)
+constexpr int kTopkBins = 2048;        // linear histogram bins per row
+constexpr int kTopkCandMax = 4096;     // scores of the k-th bin kept per row
+constexpr int kTopkSliceScores = 4096; // scores per top-k workgroup
+
+// Per-row state of the top-k kernels (global memory).
+struct TopkRow {
+    uint32_t hist[kTopkBins];  // zero when the histogram kernel starts
+    uint32_t ncand;            // zero when the pick kernel starts
+    uint32_t remaining;        // rank of the k-th largest inside its bin
+    int32_t kth_bin;
+    float lo, inv;             // bin(x) = clamp((x - lo) * inv)
+    uint32_t pad[3];
+};
+
+inline int topk_slices(int32_t max_len) { return (int)(((int64_t)max_len + 3 + kTopkSliceScores - 1) / kTopkSliceScores); }
+size_t topk_scratch_bytes(int32_t rows, int32_t max_len);
 
 enum AttendMode { kDense = 0, kSelect = 1, kSparse = 2 };
 
@@ -22,6 +39,7 @@ struct AttendParams {
     float *part_acc;           // [B][Hq][num_splits][D]
     float *part_ml;            // [B][Hq][num_splits][2]  (running max in log2 units, sum)
     int32_t *counters;         // [B][Hkv] chunks finished so far; zero between launches
+    void *topk_scratch;        // select: TopkRow [B][Hkv], histogram and candidate count cleared here
     void *out;                 // [B][Hq][D]
     int64_t stride_batch, stride_head, stride_tok;  // elements
     int64_t score_stride;
@@ -37,9 +55,10 @@ struct AttendParams {
 hipError_t launch_attend(int dtype, int head_dim, int group, int mode, const AttendParams &p,
                          hipStream_t stream);
 
-// argTopK over rows of fp32 scores; one workgroup per row.
+// argTopK over rows of fp32 scores.  scratch: topk_scratch_bytes(rows, max_len) bytes; reset
+// clears the per-row state first (not needed right after a selection attention launch).
 hipError_t launch_topk(const float *scores, int64_t row_stride, int32_t rows, const int32_t *row_lens,
-                       int32_t rows_per_len, int32_t max_len, int32_t k, int32_t *positions,
-                       hipStream_t stream);
+                       int32_t rows_per_len, int32_t max_len, int32_t k, int32_t *positions, void *scratch,
+                       bool reset, hipStream_t stream);
 
 }  // namespace tidal

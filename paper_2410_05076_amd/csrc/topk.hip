@@ -2,31 +2,37 @@
 // then an order-preserving compaction, so positions come out in ascending token order and
 // ties at the k-th value go to the smaller index.
 //
-// One workgroup of 1024 threads per row; the row is streamed three times (it was just
-// written by the selection layer and sits in L2 / Infinity Cache).
-//   1. 1024 samples give a value range [lo, hi]; every score is binned by the monotone map
-//      bin(x) = clamp(floor((x - lo) * 2048 / (hi - lo))) into a 2048-bin LDS histogram.
-//      Linear bins spread the atomics (the top bits of a float key would pile most scores
-//      into a handful of bins).  A block-wide scan from the top finds the bin holding the
-//      k-th largest score and how many scores above that bin are already taken.
-//   2. The keys of that one bin (a few dozen for smooth distributions) are gathered into
-//      LDS and an exact radix select (4 passes of 8 bits on the order-preserving uint32
-//      image of the float) finds the k-th key and the number of ties to take.  If the bin
-//      holds more keys than the LDS list (all-equal rows, say) the radix select runs over
-//      the whole row instead.
-//   3. Compaction in index order, 4096 scores per tile, eight tiles per round, with a
-//      block-wide prefix sum of (greater, equal) counts.
-// Every streaming loop issues eight independent 16-byte loads per thread before it uses
-// any of them, and rows of up to 32768 scores are read once and kept in registers.
+// A row (up to 128K scores per KV head, few rows) is cut into slices of 4096 scores, one
+// workgroup of 256 threads each, so that a handful of rows still fills the chip.  Slices of
+// a row meet through global memory at kernel boundaries (three short kernels):
+//   hist  256 samples of the row give a value range [lo, hi]; every score is binned by the
+//         monotone map bin(x) = clamp(floor((x - lo) * 2048 / (hi - lo))).  Linear bins spread
+//         the counts (the top bits of a float key would pile most scores into a handful of
+//         bins).  Each slice builds its histogram in LDS and adds the non-empty bins to the
+//         row's histogram.
+//   pick  every slice scans the row histogram from the top for the bin b* holding the k-th
+//         largest score, counts its own scores above b* and appends its scores inside b*
+//         (a few dozen per row for smooth distributions) to the row's candidate list.
+//   emit  every slice selects the k-th key exactly among the candidates (order-preserving
+//         uint32 image of the float), derives its output offset from the counts of the
+//         slices before it, and compacts its scores in index order (each thread owns 16
+//         consecutive scores, one prefix sum over the workgroup orders the slice).
+// If a row has more candidates than the list holds (many equal scores), emit falls back to
+// an exact radix select over the row's scores inside b*: slow, but never wrong.
+// The row histogram and candidate count must be zero when hist starts: the selection
+// attention kernel clears them on its way, a stand-alone call runs a reset kernel first.
 #include "common.h"
 
 namespace tidal {
 namespace {
 
-constexpr int kTopkThreads = 1024;
+constexpr int kTopkThreads = 256;
 constexpr int kTopkWaves = kTopkThreads / kWave;
-constexpr int kBins = 2048;
-constexpr int kCandMax = 8192;
+constexpr int kPerThread = 4;                              // 16-byte granules per thread
+constexpr int kSliceGranules = kTopkThreads * kPerThread;  // 1024 granules = 4096 scores
+constexpr int kBins = kTopkBins;
+constexpr int kCandMax = kTopkCandMax;
+static_assert(kSliceGranules * 4 == kTopkSliceScores, "slice size");
 
 __device__ __forceinline__ uint32_t order_key(float f) {
     uint32_t u = __float_as_uint(f);
@@ -47,16 +53,22 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v, int lane) {
     return v;
 }
 
-// Inclusive prefix sum over the 1024 threads; *total receives the block sum.
-__device__ __forceinline__ uint32_t block_inclusive_scan(uint32_t v, int lane, int wave, uint32_t *s_wave_tot,
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// Inclusive prefix sum over the workgroup; *total receives the block sum.  s_tot: [kTopkWaves].
+__device__ __forceinline__ uint32_t block_inclusive_scan(uint32_t v, int lane, int wave, uint32_t *s_tot,
                                                         uint32_t *total) {
     const uint32_t incl = wave_inclusive_scan(v, lane);
-    if (lane == kWave - 1) s_wave_tot[wave] = incl;
+    if (lane == kWave - 1) s_tot[wave] = incl;
     __syncthreads();
     uint32_t before = 0, tot = 0;
 #pragma unroll
     for (int w = 0; w < kTopkWaves; ++w) {
-        const uint32_t t = s_wave_tot[w];
+        const uint32_t t = s_tot[w];
         if (w < wave) before += t;
         tot += t;
     }
@@ -65,86 +77,208 @@ __device__ __forceinline__ uint32_t block_inclusive_scan(uint32_t v, int lane, i
     return incl + before;
 }
 
-// The scores of one row as 16-byte granules; the row may start up to 3 floats into one.
-struct RowView {
+// One row as 16-byte granules (it may start up to 3 floats into one; the buffer itself is
+// 16-byte aligned, so the granule of a valid score never leaves the allocation), and the
+// slice of it this workgroup owns.
+struct Slice {
+    const float *src;
     const float4 *src4;
-    int mis, n, n4;
+    int mis, n, n4, first;  // first: index of the slice's first granule
+    TopkRow *state;
+    bool active;
 };
 
-constexpr int kBatch = 8;  // 16-byte loads in flight per thread
+__device__ __forceinline__ Slice open_slice(const float *scores, int64_t row_stride, const int32_t *row_lens,
+                                            int rows_per_len, int max_len, int k, void *scratch) {
+    Slice s;
+    const int row = blockIdx.y;
+    s.n = min(max(row_lens[row / rows_per_len], 0), max_len);
+    s.src = scores + (int64_t)row * row_stride;
+    s.mis = (int)((reinterpret_cast<uintptr_t>(s.src) >> 2) & 3);
+    s.src4 = reinterpret_cast<const float4 *>(s.src - s.mis);
+    s.n4 = (s.mis + s.n + 3) >> 2;
+    s.first = blockIdx.x * kSliceGranules;
+    s.state = static_cast<TopkRow *>(scratch) + row;
+    s.active = k < s.n && s.first < s.n4;  // k >= n needs no selection at all
+    return s;
+}
 
-// The scores of a row, streamed in rounds of kBatch granules per thread.  With RESIDENT the
-// row fits one round: it is loaded once and later walks reuse the registers.
-template <bool RESIDENT>
-struct RowReader {
-    const RowView &row;
-    int tid;
-    float4 regs[kBatch];
-
-    __device__ __forceinline__ RowReader(const RowView &r, int t) : row(r), tid(t) {
-        if constexpr (RESIDENT) load(0, regs);
-    }
-    __device__ __forceinline__ void load(int base, float4 (&v)[kBatch]) const {
+// The slice's scores: granule u of thread t is first + u*256 + t.
+__device__ __forceinline__ void load_slice(const Slice &s, int tid, float4 (&v)[kPerThread]) {
 #pragma unroll
-        for (int u = 0; u < kBatch; ++u) {
-            const int i = base + u * kTopkThreads + tid;
-            v[u] = i < row.n4 ? row.src4[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int u = 0; u < kPerThread; ++u) {
+        const int i = s.first + u * kTopkThreads + tid;
+        v[u] = i < s.n4 ? s.src4[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+}
+
+template <class Fn>
+__device__ __forceinline__ void for_each_score(const Slice &s, int tid, const float4 (&v)[kPerThread], Fn fn) {
+#pragma unroll
+    for (int u = 0; u < kPerThread; ++u) {
+        const int i = s.first + u * kTopkThreads + tid;
+        const float f[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int j = 4 * i - s.mis + e;
+            if (i < s.n4 && j >= 0 && j < s.n) fn(f[e], j);
         }
     }
-    // Calls fn(score, j) for every score of the row.
-    template <class Fn>
-    __device__ __forceinline__ void for_each(Fn fn) const {
-        for (int base = 0; base < row.n4; base += kBatch * kTopkThreads) {
-            float4 tmp[kBatch];
-            if constexpr (!RESIDENT) load(base, tmp);
-            const float4(&v)[kBatch] = RESIDENT ? regs : tmp;
+}
+
+__global__ __launch_bounds__(kTopkThreads) void topk_reset_kernel(void *scratch) {
+    TopkRow *state = static_cast<TopkRow *>(scratch) + blockIdx.x;
+    for (int i = threadIdx.x; i < kBins; i += kTopkThreads) state->hist[i] = 0;
+    if (threadIdx.x == 0) state->ncand = 0;
+}
+
+__global__ __launch_bounds__(kTopkThreads) void topk_hist_kernel(const float *scores, int64_t row_stride,
+                                                                const int32_t *row_lens, int rows_per_len,
+                                                                int max_len, int k, void *scratch) {
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+    const Slice s = open_slice(scores, row_stride, row_lens, rows_per_len, max_len, k, scratch);
+    if (!s.active) return;
+    __shared__ uint32_t s_hist[kBins];
+    __shared__ float s_lo[kTopkWaves], s_hi[kTopkWaves];
+    float4 v[kPerThread];
+    load_slice(s, tid, v);
+    // value range from 256 samples of the whole row: the same in every slice of the row
+    const float x = s.src[(int64_t)tid * s.n / kTopkThreads];
+    float lo = x, hi = x;
 #pragma unroll
-            for (int u = 0; u < kBatch; ++u) {
-                const int i = base + u * kTopkThreads + tid;
-                const float f[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+    for (int o = 1; o < kWave; o <<= 1) {
+        lo = fminf(lo, __shfl_xor(lo, o));
+        hi = fmaxf(hi, __shfl_xor(hi, o));
+    }
+    if (lane == 0) {
+        s_lo[wave] = lo;
+        s_hi[wave] = hi;
+    }
+    for (int i = tid; i < kBins; i += kTopkThreads) s_hist[i] = 0;
+    __syncthreads();
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int j = 4 * i - row.mis + e;
-                    if (i < row.n4 && j >= 0 && j < row.n) fn(f[e], j);
-                }
+    for (int w = 0; w < kTopkWaves; ++w) {
+        lo = fminf(lo, s_lo[w]);
+        hi = fmaxf(hi, s_hi[w]);
+    }
+    const float inv = hi > lo ? (float)kBins / (hi - lo) : 0.f;
+    if (blockIdx.x == 0 && tid == 0) {
+        s.state->lo = lo;
+        s.state->inv = inv;
+    }
+    for_each_score(s, tid, v, [&](float f, int) { atomicAdd(&s_hist[linear_bin(f, lo, inv)], 1u); });
+    __syncthreads();
+    for (int i = tid; i < kBins; i += kTopkThreads) {
+        const uint32_t c = s_hist[i];
+        if (c) atomicAdd(&s.state->hist[i], c);
+    }
+}
+
+__global__ __launch_bounds__(kTopkThreads) void topk_pick_kernel(const float *scores, int64_t row_stride,
+                                                                const int32_t *row_lens, int rows_per_len,
+                                                                int max_len, int k, void *scratch, uint32_t *cand_key,
+                                                                int32_t *cand_idx, uint32_t *slice_above,
+                                                                int slices_per_row) {
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+    const Slice s = open_slice(scores, row_stride, row_lens, rows_per_len, max_len, k, scratch);
+    if (!s.active) return;
+    __shared__ uint32_t s_tot[kTopkWaves];
+    __shared__ uint32_t s_bin, s_remaining;
+    float4 v[kPerThread];
+    load_slice(s, tid, v);
+    // bin of the k-th largest: thread t owns bins 2047-8t .. 2040-8t, the scan walks downwards
+    constexpr int PER = kBins / kTopkThreads;
+    uint32_t cnt[PER], mine = 0;
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+        cnt[e] = s.state->hist[kBins - 1 - PER * tid - e];
+        mine += cnt[e];
+    }
+    uint32_t total;
+    const uint32_t incl = block_inclusive_scan(mine, lane, wave, s_tot, &total);
+    const uint32_t want = (uint32_t)k;
+    uint32_t run = incl - mine;
+    if (run < want && want <= incl) {
+#pragma unroll
+        for (int e = 0; e < PER; ++e) {
+            if (run < want && want <= run + cnt[e]) {
+                s_bin = kBins - 1 - PER * tid - e;
+                s_remaining = want - run;
+            }
+            run += cnt[e];
+        }
+    }
+    __syncthreads();
+    const int kth_bin = (int)s_bin;
+    if (blockIdx.x == 0 && tid == 0) {
+        s.state->kth_bin = kth_bin;
+        s.state->remaining = s_remaining;
+    }
+    const float lo = s.state->lo, inv = s.state->inv;
+    const int row = blockIdx.y;
+    uint32_t above = 0;
+    for_each_score(s, tid, v, [&](float f, int j) {
+        const int bin = linear_bin(f, lo, inv);
+        above += bin > kth_bin ? 1u : 0u;
+        if (bin == kth_bin) {
+            const uint32_t at = atomicAdd(&s.state->ncand, 1u);
+            if (at < (uint32_t)kCandMax) {
+                cand_key[(int64_t)row * kCandMax + at] = order_key(f);
+                cand_idx[(int64_t)row * kCandMax + at] = j;
             }
         }
+    });
+    above = wave_sum(above);
+    __syncthreads();
+    if (lane == 0) s_tot[wave] = above;
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t t = 0;
+#pragma unroll
+        for (int w = 0; w < kTopkWaves; ++w) t += s_tot[w];
+        slice_above[(int64_t)row * slices_per_row + blockIdx.x] = t;
     }
+}
+
+struct EmitShared {
+    uint32_t key[kCandMax];
+    int32_t idx[kCandMax];
+    uint32_t hist[256];
+    uint32_t tot[kTopkWaves];
+    uint32_t bin, remaining, kth, need;
 };
 
-struct Shared {
-    uint32_t hist[kBins];
-    uint32_t cand[kCandMax];
-    uint32_t wave_tot[kTopkWaves];
-    uint32_t tile_tot[kBatch][kTopkWaves];  // compaction: per (tile, wave) counts, then exclusive offsets
-    float wave_lo[kTopkWaves], wave_hi[kTopkWaves];
-    uint32_t bin, remaining, ncand;
-};
-
-// Exact radix select over keys: either the gathered list in LDS or every score of the row.
-// On return *kth is the `remaining`-th largest key and *need how many keys equal to it
-// still have to be taken.
-template <bool FROM_ROW, class Reader>
-__device__ __forceinline__ void radix_select(const Reader &reader, Shared &sm, uint32_t count, uint32_t remaining,
-                                             int tid, int lane, int wave, uint32_t *kth, uint32_t *need) {
+// Exact radix select (4 passes of 8 bits, most significant first) of the `remaining`-th
+// largest key among either the candidate list in LDS or, with FROM_ROW, all scores of the
+// row whose linear bin is kth_bin.  Leaves the key in sm.kth and the tie count in sm.need.
+template <bool FROM_ROW>
+__device__ __forceinline__ void radix_select(const Slice &s, EmitShared &sm, uint32_t count, uint32_t remaining,
+                                             int kth_bin, float lo, float inv, int tid, int lane, int wave) {
     uint32_t prefix = 0, mask = 0;
     for (int pass = 0; pass < 4; ++pass) {
         const int shift = 24 - 8 * pass;
-        if (tid < 256) sm.hist[tid] = 0;
+        sm.hist[tid] = 0;
         __syncthreads();
         auto add = [&](uint32_t key) {
             if ((key & mask) == prefix) atomicAdd(&sm.hist[(key >> shift) & 255u], 1u);
         };
         if constexpr (FROM_ROW) {
-            reader.for_each([&](float f, int) { add(order_key(f)); });
+            for (int i = tid; i < s.n4; i += kTopkThreads) {
+                const float4 v = s.src4[i];
+                const float f[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int j = 4 * i - s.mis + e;
+                    if (j >= 0 && j < s.n && linear_bin(f[e], lo, inv) == kth_bin) add(order_key(f[e]));
+                }
+            }
         } else {
-            for (uint32_t i = tid; i < count; i += kTopkThreads) add(sm.cand[i]);
+            for (uint32_t i = tid; i < count; i += kTopkThreads) add(sm.key[i]);
         }
         __syncthreads();
-        // thread t < 256 owns bin 255 - t, so the scan walks the bins downwards
-        const uint32_t cnt = tid < 256 ? sm.hist[255 - tid] : 0u;
+        const uint32_t cnt = sm.hist[255 - tid];  // thread t owns bin 255 - t: the scan walks downwards
         uint32_t total;
-        const uint32_t incl = block_inclusive_scan(cnt, lane, wave, sm.wave_tot, &total);
+        const uint32_t incl = block_inclusive_scan(cnt, lane, wave, sm.tot, &total);
         const uint32_t excl = incl - cnt;
         if (excl < remaining && remaining <= incl) {
             sm.bin = 255 - tid;
@@ -156,174 +290,150 @@ __device__ __forceinline__ void radix_select(const Reader &reader, Shared &sm, u
         remaining = sm.remaining;
         __syncthreads();
     }
-    *kth = prefix;
-    *need = remaining;
+    if (tid == 0) {
+        sm.kth = prefix;
+        sm.need = remaining;
+    }
+    __syncthreads();
 }
 
-template <bool RESIDENT>
-__device__ __forceinline__ void topk_row(const RowView &row, const float *src, int k, int32_t *dst, Shared &sm,
-                                         int tid, int lane, int wave) {
-    const int n = row.n;
-    // 1. value range from 1024 samples, linear histogram, bin of the k-th largest
-    {
-        const float x = src[(int64_t)tid * n / kTopkThreads];
-        float lo = x, hi = x;
-#pragma unroll
-        for (int o = 1; o < kWave; o <<= 1) {
-            lo = fminf(lo, __shfl_xor(lo, o));
-            hi = fmaxf(hi, __shfl_xor(hi, o));
-        }
-        if (lane == 0) {
-            sm.wave_lo[wave] = lo;
-            sm.wave_hi[wave] = hi;
-        }
-        for (int i = tid; i < kBins; i += kTopkThreads) sm.hist[i] = 0;
-        if (tid == 0) sm.ncand = 0;
-    }
-    const RowReader<RESIDENT> reader(row, tid);
-    __syncthreads();
-    float lo = sm.wave_lo[0], hi = sm.wave_hi[0];
-#pragma unroll
-    for (int w = 1; w < kTopkWaves; ++w) {
-        lo = fminf(lo, sm.wave_lo[w]);
-        hi = fmaxf(hi, sm.wave_hi[w]);
-    }
-    const float inv = hi > lo ? (float)kBins / (hi - lo) : 0.f;
-    reader.for_each([&](float f, int) { atomicAdd(&sm.hist[linear_bin(f, lo, inv)], 1u); });
-    __syncthreads();
-    uint32_t remaining = (uint32_t)k;
-    {
-        // thread t owns bins 2047 - 2t and 2046 - 2t: the scan walks the bins downwards
-        const uint32_t c1 = sm.hist[kBins - 1 - 2 * tid], c2 = sm.hist[kBins - 2 - 2 * tid];
-        uint32_t total;
-        const uint32_t incl = block_inclusive_scan(c1 + c2, lane, wave, sm.wave_tot, &total);
-        const uint32_t excl = incl - (c1 + c2);
-        if (excl < remaining && remaining <= incl) {
-            const bool first = remaining <= excl + c1;
-            sm.bin = kBins - 1 - 2 * tid - (first ? 0 : 1);
-            sm.remaining = remaining - excl - (first ? 0u : c1);
-        }
-    }
-    __syncthreads();
-    const int kth_bin = (int)sm.bin;
-    remaining = sm.remaining;
-
-    // 2. gather that bin's keys and select exactly among them
-    reader.for_each([&](float f, int) {
-        if (linear_bin(f, lo, inv) == kth_bin) {
-            const uint32_t at = atomicAdd(&sm.ncand, 1u);
-            if (at < kCandMax) sm.cand[at] = order_key(f);
-        }
-    });
-    __syncthreads();
-    const uint32_t ncand = sm.ncand;
-    uint32_t kth, need;
-    if (ncand <= kCandMax)
-        radix_select<false>(reader, sm, ncand, remaining, tid, lane, wave, &kth, &need);
-    else
-        radix_select<true>(reader, sm, 0, (uint32_t)k, tid, lane, wave, &kth, &need);
-
-    // 3. compaction in index order: tile u of a round holds granules base + u*1024 + tid
-    uint32_t gt_base = 0, eq_base = 0;
-    for (int base = 0; base < row.n4; base += kBatch * kTopkThreads) {
-        float4 tmp[kBatch];
-        if constexpr (!RESIDENT) reader.load(base, tmp);
-        const float4(&v)[kBatch] = RESIDENT ? reader.regs : tmp;
-        uint32_t flags[kBatch], packed[kBatch];  // flags: bit e = greater, bit 4+e = equal
-#pragma unroll
-        for (int u = 0; u < kBatch; ++u) {
-            const int i = base + u * kTopkThreads + tid;
-            const float f[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
-            flags[u] = 0;
-            packed[u] = 0;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int j = 4 * i - row.mis + e;
-                if (i < row.n4 && j >= 0 && j < n) {
-                    const uint32_t key = order_key(f[e]);
-                    if (key > kth) {
-                        flags[u] |= 1u << e;
-                        packed[u] += 1u;
-                    } else if (key == kth) {
-                        flags[u] |= 16u << e;
-                        packed[u] += 0x10000u;
-                    }
-                }
-            }
-        }
-        uint32_t incl[kBatch];
-#pragma unroll
-        for (int u = 0; u < kBatch; ++u) {
-            incl[u] = wave_inclusive_scan(packed[u], lane);
-            if (lane == kWave - 1) sm.tile_tot[u][wave] = incl[u];
-        }
-        __syncthreads();
-        // exclusive offsets over the (tile, wave) pairs in tile-major order: 128 values, one wave
-        static_assert(kBatch * kTopkWaves == 2 * kWave, "two values per lane");
-        if (wave == 0) {
-            uint32_t *flat = &sm.tile_tot[0][0];
-            const uint32_t c0 = flat[2 * lane], c1 = flat[2 * lane + 1];
-            const uint32_t inc = wave_inclusive_scan(c0 + c1, lane);
-            flat[2 * lane] = inc - c0 - c1;
-            flat[2 * lane + 1] = inc - c1;
-            if (lane == kWave - 1) sm.wave_tot[0] = inc;  // round total
-        }
-        __syncthreads();
-        const uint32_t round_total = sm.wave_tot[0];
-#pragma unroll
-        for (int u = 0; u < kBatch; ++u) {
-            const int i = base + u * kTopkThreads + tid;
-            const uint32_t excl = sm.tile_tot[u][wave] + incl[u] - packed[u];
-            uint32_t gtb = gt_base + (excl & 0xffffu), eqb = eq_base + (excl >> 16);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int j = 4 * i - row.mis + e;
-                if (flags[u] & (1u << e)) {
-                    dst[gtb + min(eqb, need)] = j;
-                    ++gtb;
-                } else if (flags[u] & (16u << e)) {
-                    if (eqb < need) dst[gtb + eqb] = j;
-                    ++eqb;
-                }
-            }
-        }
-        gt_base += round_total & 0xffffu;
-        eq_base += round_total >> 16;
-        __syncthreads();
-    }
-}
-
-__global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float *scores, int64_t row_stride,
-                                                           const int32_t *row_lens, int rows_per_len,
-                                                           int max_len, int k, int32_t *positions) {
-    const int r = blockIdx.x, tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
-    const int n = min(max(row_lens[r / rows_per_len], 0), max_len);
-    const float *src = scores + (int64_t)r * row_stride;
-    int32_t *dst = positions + (int64_t)r * k;
-    if (k >= n) {
-        for (int i = tid; i < k; i += kTopkThreads) dst[i] = i < n ? i : -1;
+__global__ __launch_bounds__(kTopkThreads) void topk_emit_kernel(const float *scores, int64_t row_stride,
+                                                                const int32_t *row_lens, int rows_per_len,
+                                                                int max_len, int k, void *scratch,
+                                                                const uint32_t *cand_key, const int32_t *cand_idx,
+                                                                const uint32_t *slice_above, int slices_per_row,
+                                                                int32_t *positions) {
+    static_assert(kTopkThreads == 256, "one radix bin per thread");
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+    const int row = blockIdx.y;
+    const Slice s = open_slice(scores, row_stride, row_lens, rows_per_len, max_len, k, scratch);
+    int32_t *dst = positions + (int64_t)row * k;
+    if (k >= s.n) {  // every token is selected: slice x writes entries x*4096 .. and the last one the -1 tail
+        const int lo_i = blockIdx.x * kTopkSliceScores;
+        const int hi_i = blockIdx.x == gridDim.x - 1 ? k : min(k, lo_i + kTopkSliceScores);
+        for (int i = lo_i + tid; i < hi_i; i += kTopkThreads) dst[i] = i < s.n ? i : -1;
         return;
     }
-    // the buffer is 16-byte aligned, so the granule of a valid score never leaves the allocation
-    RowView row;
-    row.mis = (int)((reinterpret_cast<uintptr_t>(src) >> 2) & 3);
-    row.src4 = reinterpret_cast<const float4 *>(src - row.mis);
-    row.n = n;
-    row.n4 = (row.mis + n + 3) >> 2;
-    __shared__ Shared sm;
-    if (row.n4 <= kBatch * kTopkThreads)
-        topk_row<true>(row, src, k, dst, sm, tid, lane, wave);
-    else
-        topk_row<false>(row, src, k, dst, sm, tid, lane, wave);
+    if (!s.active) return;
+
+    __shared__ EmitShared sm;
+    const uint32_t ncand = s.state->ncand, remaining = s.state->remaining;
+    const int kth_bin = s.state->kth_bin;
+    const float lo = s.state->lo, inv = s.state->inv;
+    const int slice_start = 4 * s.first - s.mis;  // first token index of this slice
+
+    // scores of earlier slices above the bin
+    uint32_t gt_before = 0, eq_before = 0;
+    for (int i = tid; i < (int)blockIdx.x; i += kTopkThreads) gt_before += slice_above[(int64_t)row * slices_per_row + i];
+
+    if (ncand <= (uint32_t)kCandMax) {
+        for (uint32_t i = tid; i < ncand; i += kTopkThreads) {
+            sm.key[i] = cand_key[(int64_t)row * kCandMax + i];
+            sm.idx[i] = cand_idx[(int64_t)row * kCandMax + i];
+        }
+        __syncthreads();
+        radix_select<false>(s, sm, ncand, remaining, kth_bin, lo, inv, tid, lane, wave);
+        const uint32_t kth = sm.kth;
+        for (uint32_t i = tid; i < ncand; i += kTopkThreads) {
+            if (sm.idx[i] < slice_start) {
+                gt_before += sm.key[i] > kth ? 1u : 0u;
+                eq_before += sm.key[i] == kth ? 1u : 0u;
+            }
+        }
+    } else {
+        radix_select<true>(s, sm, 0, remaining, kth_bin, lo, inv, tid, lane, wave);
+        const uint32_t kth = sm.kth;
+        for (int i = tid; i < min(s.first, s.n4); i += kTopkThreads) {
+            const float4 q = s.src4[i];
+            const float f[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int j = 4 * i - s.mis + e;
+                if (j >= 0 && j < s.n && linear_bin(f[e], lo, inv) == kth_bin) {
+                    const uint32_t key = order_key(f[e]);
+                    gt_before += key > kth ? 1u : 0u;
+                    eq_before += key == kth ? 1u : 0u;
+                }
+            }
+        }
+    }
+    const uint32_t kth = sm.kth, need = sm.need;
+    gt_before = wave_sum(gt_before);
+    eq_before = wave_sum(eq_before);
+    __syncthreads();
+    if (lane == 0) {
+        sm.tot[wave] = gt_before;
+        sm.hist[wave] = eq_before;
+    }
+    __syncthreads();
+    uint32_t gt_base = 0, eq_base = 0;
+#pragma unroll
+    for (int w = 0; w < kTopkWaves; ++w) {
+        gt_base += sm.tot[w];
+        eq_base += sm.hist[w];
+    }
+    __syncthreads();
+
+    // compaction in index order: this thread owns the 16 consecutive scores of granules
+    // first + 4*tid .. first + 4*tid + 3, so one prefix sum over the threads orders the slice
+    uint32_t gt_mask = 0, eq_mask = 0;  // bit 4*u + e
+#pragma unroll
+    for (int u = 0; u < kPerThread; ++u) {
+        const int i = s.first + kPerThread * tid + u;
+        const float4 q = i < s.n4 ? s.src4[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+        const float f[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int j = 4 * i - s.mis + e;
+            const bool inside = i < s.n4 && j >= 0 && j < s.n;
+            const int bin = linear_bin(f[e], lo, inv);
+            const uint32_t key = order_key(f[e]);
+            const bool gt = inside && (bin > kth_bin || (bin == kth_bin && key > kth));
+            const bool eq = inside && bin == kth_bin && key == kth;
+            gt_mask |= (gt ? 1u : 0u) << (4 * u + e);
+            eq_mask |= (eq ? 1u : 0u) << (4 * u + e);
+        }
+    }
+    const uint32_t packed = (uint32_t)__popc(gt_mask) | ((uint32_t)__popc(eq_mask) << 16);
+    uint32_t total;
+    const uint32_t excl = block_inclusive_scan(packed, lane, wave, sm.tot, &total) - packed;
+    uint32_t gtb = gt_base + (excl & 0xffffu), eqb = eq_base + (excl >> 16);
+    const int j0 = 4 * (s.first + kPerThread * tid) - s.mis;
+#pragma unroll
+    for (int t = 0; t < 4 * kPerThread; ++t) {
+        if ((gt_mask >> t) & 1u) {
+            dst[gtb + min(eqb, need)] = j0 + t;
+            ++gtb;
+        } else if ((eq_mask >> t) & 1u) {
+            if (eqb < need) dst[gtb + eqb] = j0 + t;
+            ++eqb;
+        }
+    }
 }
 
 }  // namespace
 
+size_t topk_scratch_bytes(int32_t rows, int32_t max_len) {
+    const size_t slices = (size_t)topk_slices(max_len);
+    return (size_t)rows * (sizeof(TopkRow) + (size_t)kCandMax * 8 + slices * 4);
+}
+
 hipError_t launch_topk(const float *scores, int64_t row_stride, int32_t rows, const int32_t *row_lens,
-                       int32_t rows_per_len, int32_t max_len, int32_t k, int32_t *positions,
-                       hipStream_t stream) {
-    hipLaunchKernelGGL(topk_kernel, dim3(rows), dim3(kTopkThreads), 0, stream, scores, row_stride,
-                       row_lens, rows_per_len, max_len, k, positions);
+                       int32_t rows_per_len, int32_t max_len, int32_t k, int32_t *positions, void *scratch,
+                       bool reset, hipStream_t stream) {
+    const int slices = topk_slices(max_len);
+    char *base = static_cast<char *>(scratch);
+    uint32_t *cand_key = reinterpret_cast<uint32_t *>(base + (size_t)rows * sizeof(TopkRow));
+    int32_t *cand_idx = reinterpret_cast<int32_t *>(cand_key + (size_t)rows * kCandMax);
+    uint32_t *slice_above = reinterpret_cast<uint32_t *>(cand_idx + (size_t)rows * kCandMax);
+    const dim3 grid(slices, rows), block(kTopkThreads);
+    if (reset) hipLaunchKernelGGL(topk_reset_kernel, dim3(rows), block, 0, stream, scratch);
+    hipLaunchKernelGGL(topk_hist_kernel, grid, block, 0, stream, scores, row_stride, row_lens, rows_per_len, max_len,
+                       k, scratch);
+    hipLaunchKernelGGL(topk_pick_kernel, grid, block, 0, stream, scores, row_stride, row_lens, rows_per_len, max_len,
+                       k, scratch, cand_key, cand_idx, slice_above, slices);
+    hipLaunchKernelGGL(topk_emit_kernel, grid, block, 0, stream, scores, row_stride, row_lens, rows_per_len, max_len,
+                       k, scratch, cand_key, cand_idx, slice_above, slices, positions);
     return hipGetLastError();
 }
 

@@ -16,7 +16,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = range(5)
 BF16, F32 = 0, 1
 LAYER_DENSE, LAYER_SELECT, LAYER_SPARSE = 0, 1, 2
 
-EXPORTS = ("td_validate", "td_workspace_bytes", "td_create", "td_destroy", "td_full_attend",
+EXPORTS = ("td_validate", "td_workspace_bytes", "td_topk_workspace_bytes", "td_create", "td_destroy", "td_full_attend",
            "td_select_tokens", "td_sparse_attend", "td_topk", "td_decode_step", "td_set_tuning",
            "td_status_string", "td_last_error")
 
@@ -53,6 +53,7 @@ def lib():
     shp = ctypes.POINTER(Shape)
     L.td_validate.argtypes, L.td_validate.restype = [shp, i32], ctypes.c_int
     L.td_workspace_bytes.argtypes, L.td_workspace_bytes.restype = [shp, i32], sz
+    L.td_topk_workspace_bytes.argtypes, L.td_topk_workspace_bytes.restype = [i32, i32], sz
     L.td_create.argtypes, L.td_create.restype = [ctypes.POINTER(vp), ctypes.c_int, sz], ctypes.c_int
     L.td_destroy.argtypes, L.td_destroy.restype = [vp], ctypes.c_int
     L.td_full_attend.argtypes, L.td_full_attend.restype = [vp, shp, vp, vp, vp, vp, vp], ctypes.c_int
@@ -95,12 +96,14 @@ def _stream():
 class Tidal:
     """A td_ctx with a workspace sized for one shape and budget."""
 
-    def __init__(self, shape, k, device=None):
+    def __init__(self, shape, k, device=None, topk_rows=0, topk_max_len=0):
         L = lib()
         self.device = torch.cuda.current_device() if device is None else device
         need = L.td_workspace_bytes(ctypes.byref(shape), k)
         if need == 0:
             raise TidalError(L.td_validate(ctypes.byref(shape), k), "invalid or unsupported shape")
+        if topk_rows:       # also room for stand-alone td_topk calls of this size
+            need = max(need, L.td_topk_workspace_bytes(topk_rows, topk_max_len))
         self.workspace_bytes = need
         self._ctx = ctypes.c_void_p()
         st = L.td_create(ctypes.byref(self._ctx), self.device, need)

@@ -15,7 +15,7 @@ def td():
     lens = torch.ones(1, dtype=torch.int32, device=DEV)
     q = torch.zeros((1, 1, 64), dtype=torch.float32, device=DEV)
     K = torch.zeros((1, 1, 8, 64), dtype=torch.float32, device=DEV)
-    t = tidal.Tidal(tidal.make_shape(q, K, lens), 1)
+    t = tidal.Tidal(tidal.make_shape(q, K, lens), 1, topk_rows=16, topk_max_len=131072)
     yield t
     t.close()
 
