@@ -44,8 +44,10 @@ def main():
     ap.add_argument("--copies", type=int, default=0, help="independent input copies to rotate over")
     ap.add_argument("--no-graph", action="store_true", help="enqueue eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--kernel-reps", type=int, default=40)
-    ap.add_argument("--tune", default="", help="target_workgroups,min_chunk_dense,min_chunk_sparse (0 = default)")
+    ap.add_argument("--kernel-reps", type=int, default=24)
+    ap.add_argument("--probe-only", action="store_true",
+                    help="run only the plain streaming kernels (1 GiB read, 1 GiB copy): counter calibration")
+    ap.add_argument("--tune", default="", help="target_workgroups,min_chunk_dense,min_chunk_sparse,max_splits (0 = default)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus %d is not supported "
@@ -58,6 +60,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     tidal.lib()                      # fail loudly if the HIP library is missing
     dev = "cuda:0"
+    if args.probe_only:
+        print(json.dumps({"hbm_probe": hbm_probe(torch, tidal, dev)}), flush=True)
+        return
     over = {"k": args.k} if args.k else {}
     w = W.workload(args.workload, **over)
     step_bytes = w.algorithmic_bytes_per_step()
@@ -121,27 +126,44 @@ def main():
     us_per_step = ms_per_step * 1e3
     log("%.1f us per decode step (%s)" % (us_per_step, "graph replay" if use_graph else "eager"))
 
-    # per-launch duration of each layer kind, HIP events on the launch stream
+    # Per-launch duration of each layer kind: `reps` launches of that kind (rotating over input
+    # copies and layers, so each launch streams data that is not in cache) are captured into one
+    # HIP graph; HIP events on the launch stream bracket each replay.  Back-to-back kernels in a
+    # graph leave gaps well under a microsecond, so time / reps is the kernel's own duration.
     def time_kind(kind, reps):
         idx = [i for i, x in enumerate(w.schedule) if x == kind]
         if not idx:
             return None
+
+        def launches():
+            for r in range(reps):
+                qs, Ks, Vs, outs, pos = sets[r % copies]
+                i = idx[(r // copies) % len(idx)]
+                if kind == W.DENSE:
+                    td.full_attend(shape, qs[i], Ks[i], Vs[i], outs[i])
+                elif kind == W.SELECT:
+                    td.select_tokens(shape, qs[i], Ks[i], Vs[i], w.k, outs[i], pos[0])
+                else:
+                    td.sparse_attend(shape, qs[i], Ks[i], Vs[i], pos[0], w.k, outs[i])
+
+        if use_graph:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                launches()
+            run = g.replay
+        else:
+            run = launches
+        run()
+        torch.cuda.synchronize()
         evs = []
-        for r in range(reps):
-            qs, Ks, Vs, outs, pos = sets[r % copies]
-            i = idx[(r // copies) % len(idx)]
+        for _ in range(5):
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             a.record()
-            if kind == W.DENSE:
-                td.full_attend(shape, qs[i], Ks[i], Vs[i], outs[i])
-            elif kind == W.SELECT:
-                td.select_tokens(shape, qs[i], Ks[i], Vs[i], w.k, outs[i], pos[0])
-            else:
-                td.sparse_attend(shape, qs[i], Ks[i], Vs[i], pos[0], w.k, outs[i])
+            run()
             b.record()
             evs.append((a, b))
         torch.cuda.synchronize()
-        ts = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
+        ts = sorted(a.elapsed_time(b) * 1e3 / reps for a, b in evs)
         return sum(ts) / len(ts), ts[len(ts) // 2]
 
     per_kind = {}
@@ -166,6 +188,9 @@ def main():
             per_kind[name]["GBps"] = round(nbytes / (per_kind[name]["avg_us"] * 1e-6) / 1e9, 1)
     per_kind["full"]["GBps"] = round(achieved, 1)
 
+    probe = hbm_probe(torch, tidal, dev, td)
+    log("plain streaming kernels: read %.0f GB/s, copy %.0f GB/s (read + write bytes)"
+        % (probe["read_GBps"], probe["copy_GBps"]))
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(w, sets[0], torch)
@@ -181,11 +206,39 @@ def main():
                      "achieved_GBps": round(step_bytes / (us_per_step * 1e-6) / 1e9, 1),
                      "frac_of_peak": round(step_bytes / (us_per_step * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)},
         "per_layer_kind": per_kind,
+        "hbm_probe": probe,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
     td.close()
     print(json.dumps(out), flush=True)
+
+
+def hbm_probe(torch, tidal, dev, td=None, nbytes=2**30, reps=6):
+    """Measured rate of a plain streaming read and a plain copy of 1 GiB (cold: larger than every cache)."""
+    src = torch.empty(nbytes, dtype=torch.uint8, device=dev).fill_(3)
+    dst = torch.empty_like(src)
+    own = td is None
+    if own:
+        lens = torch.ones(1, dtype=torch.int32, device=dev)
+        q = torch.zeros((1, 1, 64), dtype=torch.float32, device=dev)
+        K = torch.zeros((1, 1, 8, 64), dtype=torch.float32, device=dev)
+        td = tidal.Tidal(tidal.make_shape(q, K, lens), 1)
+    out = {"bytes": nbytes}
+    for name, d, moved in (("read_GBps", None, nbytes), ("copy_GBps", dst, 2 * nbytes)):
+        evs = []
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            td.probe_stream(src, d)
+            b.record()
+            evs.append((a, b))
+        torch.cuda.synchronize()
+        ts = sorted(a.elapsed_time(b) for a, b in evs[1:])
+        out[name] = round(moved / (ts[len(ts) // 2] * 1e-3) / 1e9, 1)
+    if own:
+        td.close()
+    return out
 
 
 def cpu_baseline(w, inputs, torch):

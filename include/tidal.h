@@ -141,10 +141,17 @@ td_status td_decode_step(td_ctx *ctx, const td_shape *shape, int32_t num_layers,
                          void *const *out_layers, int32_t *positions, void *hip_stream);
 
 /* Tuning knobs for measurement sweeps (0 keeps the default): target number of
- * workgroups per attention launch, and the smallest token chunk per workgroup
- * for full and for sparse attention.  The workspace size does not depend on them. */
+ * workgroups per attention launch, the smallest token chunk per workgroup for
+ * full and for sparse attention, and the largest number of chunks per
+ * (sequence, KV head).  The workspace size does not depend on them. */
 td_status td_set_tuning(td_ctx *ctx, int32_t target_workgroups, int32_t min_chunk_dense,
-                        int32_t min_chunk_sparse);
+                        int32_t min_chunk_sparse, int32_t max_splits);
+
+/* Measurement helper, not part of the attention path: a plain streaming kernel
+ * of known size.  Copies `bytes` (rounded down to 16) from src to dst, or only
+ * reads src when dst is NULL.  Used to calibrate hardware counters and to
+ * report a measured streaming rate next to the published HBM peak. */
+td_status td_probe_stream(td_ctx *ctx, void *dst, const void *src, size_t bytes, void *hip_stream);
 
 const char *td_status_string(td_status s);
 const char *td_last_error(const td_ctx *ctx);

@@ -14,7 +14,7 @@ struct td_ctx {
     int device = 0;
     char *workspace = nullptr;
     size_t workspace_bytes = 0;
-    int32_t target_workgroups = 0, min_chunk_dense = 0, min_chunk_sparse = 0;
+    int32_t target_workgroups = 0, min_chunk_dense = 0, min_chunk_sparse = 0, max_splits = 0;
     char error[256] = {0};
 };
 
@@ -22,8 +22,11 @@ namespace {
 
 constexpr int32_t kDefaultTargetWorkgroups = 1024;
 constexpr int32_t kDefaultMinChunkDense = 256;
-constexpr int32_t kDefaultMinChunkSparse = 64;
-constexpr int32_t kChunkGranule = 64;
+constexpr int32_t kDefaultMinChunkSparse = 128;
+constexpr int32_t kChunkGranule = 128;
+// chunks per (sequence, KV head): every chunk takes a ticket on one counter and the last one
+// merges all partials alone, so the tail grows with the count
+constexpr int32_t kDefaultMaxSplits = 64;
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 int32_t ceil_div(int64_t a, int64_t b) { return (int32_t)((a + b - 1) / b); }
@@ -87,13 +90,16 @@ Workspace workspace_layout(const td_shape *s, int32_t k) {
 
 void plan_chunks(const td_ctx *ctx, const td_shape *s, bool sparse, int32_t tokens, int32_t *chunk,
                  int32_t *splits) {
-    const int32_t target = ctx->target_workgroups > 0 ? ctx->target_workgroups : kDefaultTargetWorkgroups;
+    // sparse launches are latency-bound: fewer, fatter workgroups shorten the ticket and merge tail
+    const int32_t target = (ctx->target_workgroups > 0 ? ctx->target_workgroups : kDefaultTargetWorkgroups) /
+                           (sparse ? 2 : 1);
     int32_t floor_chunk = sparse ? (ctx->min_chunk_sparse > 0 ? ctx->min_chunk_sparse : kDefaultMinChunkSparse)
                                  : (ctx->min_chunk_dense > 0 ? ctx->min_chunk_dense : kDefaultMinChunkDense);
     const int64_t groups = (int64_t)s->batch * s->num_kv_heads;
-    const int32_t want = (int32_t)std::max<int64_t>(1, target / groups);
+    const int32_t cap = std::min(kSplitsMax, ctx->max_splits > 0 ? ctx->max_splits : kDefaultMaxSplits);
+    const int32_t want = (int32_t)std::min<int64_t>(cap, std::max<int64_t>(1, target / groups));
     int32_t c = std::max(ceil_div(tokens, want), floor_chunk);
-    c = std::max(c, ceil_div(tokens, kSplitsMax));
+    c = std::max(c, ceil_div(tokens, cap));
     c = (int32_t)align_up((size_t)c, kChunkGranule);
     if (sparse) c = std::min(c, kSparseChunkMax);
     *chunk = c;
@@ -207,13 +213,14 @@ td_status td_destroy(td_ctx *ctx) {
 }
 
 td_status td_set_tuning(td_ctx *ctx, int32_t target_workgroups, int32_t min_chunk_dense,
-                        int32_t min_chunk_sparse) {
+                        int32_t min_chunk_sparse, int32_t max_splits) {
     if (!ctx) return TD_ERR_INVALID_ARG;
-    if (target_workgroups < 0 || min_chunk_dense < 0 || min_chunk_sparse < 0)
+    if (target_workgroups < 0 || min_chunk_dense < 0 || min_chunk_sparse < 0 || max_splits < 0)
         return fail(ctx, TD_ERR_INVALID_ARG, "%s", "tuning values must be >= 0");
     ctx->target_workgroups = target_workgroups;
     ctx->min_chunk_dense = min_chunk_dense;
     ctx->min_chunk_sparse = min_chunk_sparse;
+    ctx->max_splits = max_splits;
     return TD_OK;
 }
 
@@ -297,6 +304,16 @@ td_status td_decode_step(td_ctx *ctx, const td_shape *shape, int32_t num_layers,
         }
         if (st != TD_OK) return st;
     }
+    return TD_OK;
+}
+
+td_status td_probe_stream(td_ctx *ctx, void *dst, const void *src, size_t bytes, void *hip_stream) {
+    if (!ctx) return TD_ERR_INVALID_ARG;
+    if (!src || bytes < 16 || misaligned(src) || (dst && misaligned(dst)))
+        return fail(ctx, TD_ERR_INVALID_ARG, "%s", "src (and dst) must be 16-byte aligned and bytes >= 16");
+    const hipError_t e = launch_probe(dst, src, bytes, reinterpret_cast<uint32_t *>(ctx->workspace),
+                                      static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail(ctx, TD_ERR_HIP, "probe launch failed: %s", hipGetErrorString(e));
     return TD_OK;
 }
 

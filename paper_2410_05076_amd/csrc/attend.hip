@@ -3,8 +3,8 @@
 // rows named by rho (position persistent sparse attention).
 //
 // Work decomposition.  grid = (token chunks, KV heads, sequences).  A workgroup of four
-// wave64s streams one chunk of one (sequence, KV head) and serves all G query heads of the
-// group from the same loaded rows, so each K/V byte is fetched once.  A row of head_dim
+// wave64s streams one chunk of consecutive tokens of one (sequence, KV head) and serves all
+// G query heads of the group from the same loaded rows, so each K/V byte is fetched once.  A row of head_dim
 // elements is covered by LPR lanes holding 16 bytes each, so one wave-wide 128-bit load
 // fetches 64/LPR whole rows, fully coalesced; a dot product is finished by a DPP reduction
 // over those LPR lanes.  Each lane keeps an online-softmax state (running max, sum, its
@@ -88,9 +88,13 @@ __device__ __forceinline__ void store_out(void *out, int64_t i, float v) {
         static_cast<float *>(out)[i] = v;
 }
 
-// Device-scope store that goes through to memory instead of staying in this XCD's L2.
+// Device-scope store that goes through to memory instead of staying in this XCD's L2, and
+// the matching load that does not trust this XCD's caches.
 __device__ __forceinline__ void publish(float *p, float v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint64_t coherent_load(const uint64_t *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 template <int DT, int D, int G, int MODE>
@@ -112,9 +116,13 @@ __global__ __launch_bounds__(kThreads) void attend_split_kernel(const AttendPara
     }
     const int N = min(max(p.seq_lens[b], 0), p.max_seq_len);
     const int n_tok = MODE == kSparse ? (N > 0 ? p.k : 0) : N;
+    // A workgroup owns p.chunk consecutive tokens (a multiple of the 128-token granule): a
+    // contiguous stream per workgroup keeps TLB and DRAM-page locality.
+    constexpr int TILE = kWavesPerGroup * STEP;
     const int t0 = split * p.chunk;
     if (t0 >= n_tok) return;
     const int t1 = min(n_tok, t0 + p.chunk);
+    const int ns = (n_tok + p.chunk - 1) / p.chunk;  // workgroups of this (sequence, KV head) with work
 
     __shared__ int s_pos[MODE == kSparse ? kSparseChunkMax : 1];
     if constexpr (MODE == kSparse) {
@@ -147,7 +155,7 @@ __global__ __launch_bounds__(kThreads) void attend_split_kernel(const AttendPara
     }
     const float scale2 = p.scale * kLog2e;
 
-    for (int base = t0 + wave * STEP; base < t1; base += kWavesPerGroup * STEP) {
+    for (int base = t0 + wave * STEP; base < t1; base += TILE) {
         uint4 kraw[kUnroll], vraw[kUnroll];
         bool valid[kUnroll];
         int64_t off[kUnroll];
@@ -230,7 +238,6 @@ __global__ __launch_bounds__(kThreads) void attend_split_kernel(const AttendPara
     constexpr int kAccFloats = RG * GC * D > kThreads * 6 ? RG * GC * D : kThreads * 6;
     __shared__ __align__(16) float s_acc[kAccFloats];
     const int rg = wave * TPW + r;
-    const int ns = (n_tok + p.chunk - 1) / p.chunk;  // chunks of this (sequence, KV head)
 #pragma unroll
     for (int h0 = 0; h0 < G; h0 += GC) {
         if (h0) __syncthreads();
@@ -282,9 +289,8 @@ __global__ __launch_bounds__(kThreads) void attend_split_kernel(const AttendPara
     // The chunk that finishes last merges all partials of its (sequence, KV head).
     // Partials are published with device-scope write-through stores and every wave waits
     // for its stores to complete before the barrier, so they are in memory before this
-    // workgroup's ticket is taken; only the merging workgroup pays for an acquire (cache
-    // invalidate).  A release fence in every workgroup would write back the whole L2 each
-    // time.  The counter returns to zero for the next launch.
+    // workgroup's ticket is taken.  (A release fence in every workgroup would write back the
+    // whole L2 each time.)  The counter returns to zero for the next launch.
     __shared__ int s_last;
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
@@ -296,25 +302,29 @@ __global__ __launch_bounds__(kThreads) void attend_split_kernel(const AttendPara
     }
     __syncthreads();
     if (!s_last) return;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
 
     // One pass over the partials: thread (sg, col) folds chunks sg, sg + NG, ... of one float4
     // column of one head with the online rescaling rule, then the NG threads of a column
-    // are folded through LDS.
+    // are folded through LDS.  The partials are read with device-scope loads (they come
+    // from other workgroups' write-through stores), which needs no cache invalidate.
     constexpr int COLS = G * D / 4;      // float4 columns over all heads of the group
     constexpr int NG = kThreads / COLS;  // chunk groups working in parallel
     static_assert(NG >= 1 && NG * COLS == kThreads, "G * D / 4 must divide the workgroup size");
     const int col = threadIdx.x % COLS, sg = threadIdx.x / COLS;
     const int hi = col / (D / 4), c4 = col % (D / 4);
     const int64_t head = (int64_t)b * p.num_q_heads + g * G + hi;
-    const float2 *ml = reinterpret_cast<const float2 *>(p.part_ml) + head * p.num_splits;
-    const float4 *pa = reinterpret_cast<const float4 *>(p.part_acc) + head * p.num_splits * (D / 4) + c4;
+    const uint64_t *ml = reinterpret_cast<const uint64_t *>(p.part_ml) + head * p.num_splits;
+    const uint64_t *pa = reinterpret_cast<const uint64_t *>(p.part_acc) + (head * p.num_splits * (D / 4) + c4) * 2;
     float mm = kEmptyMax, ll = 0.f;
     float4 aa = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll 8
     for (int s = sg; s < ns; s += NG) {
-        const float2 v = ml[s];
-        const float4 x = pa[(int64_t)s * (D / 4)];
+        const uint64_t vml = coherent_load(ml + s);
+        const uint64_t lo = coherent_load(pa + (int64_t)s * (D / 2));
+        const uint64_t hi2 = coherent_load(pa + (int64_t)s * (D / 2) + 1);
+        const float2 v = make_float2(__uint_as_float((uint32_t)vml), __uint_as_float((uint32_t)(vml >> 32)));
+        const float4 x = make_float4(__uint_as_float((uint32_t)lo), __uint_as_float((uint32_t)(lo >> 32)),
+                                     __uint_as_float((uint32_t)hi2), __uint_as_float((uint32_t)(hi2 >> 32)));
         const float mn = fmaxf(mm, v.x);
         const float wa = fast_exp2(mm - mn), wb = fast_exp2(v.x - mn);
         ll = ll * wa + v.y * wb;

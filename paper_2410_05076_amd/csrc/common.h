@@ -61,4 +61,7 @@ hipError_t launch_topk(const float *scores, int64_t row_stride, int32_t rows, co
                        int32_t rows_per_len, int32_t max_len, int32_t k, int32_t *positions, void *scratch,
                        bool reset, hipStream_t stream);
 
+// Streaming probe: copies `bytes` from src to dst, or (dst == nullptr) only reads src.
+hipError_t launch_probe(void *dst, const void *src, size_t bytes, uint32_t *sink, hipStream_t stream);
+
 }  // namespace tidal

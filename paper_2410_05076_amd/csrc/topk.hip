@@ -317,6 +317,13 @@ __global__ __launch_bounds__(kTopkThreads) void topk_emit_kernel(const float *sc
     if (!s.active) return;
 
     __shared__ EmitShared sm;
+    // this thread owns the 16 consecutive scores of granules first + 4*tid .. first + 4*tid + 3
+    float4 own[kPerThread];
+#pragma unroll
+    for (int u = 0; u < kPerThread; ++u) {
+        const int i = s.first + kPerThread * tid + u;
+        own[u] = i < s.n4 ? s.src4[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
     const uint32_t ncand = s.state->ncand, remaining = s.state->remaining;
     const int kth_bin = s.state->kth_bin;
     const float lo = s.state->lo, inv = s.state->inv;
@@ -332,7 +339,23 @@ __global__ __launch_bounds__(kTopkThreads) void topk_emit_kernel(const float *sc
             sm.idx[i] = cand_idx[(int64_t)row * kCandMax + i];
         }
         __syncthreads();
-        radix_select<false>(s, sm, ncand, remaining, kth_bin, lo, inv, tid, lane, wave);
+        if (ncand <= (uint32_t)kTopkThreads) {
+            // one candidate per thread: its rank by counting; equal keys agree on the answer
+            const uint32_t mine = tid < (int)ncand ? sm.key[tid] : 0u;
+            uint32_t above = 0, same = 0;
+            for (uint32_t i = 0; i < ncand; ++i) {
+                const uint32_t other = sm.key[i];
+                above += other > mine ? 1u : 0u;
+                same += other == mine ? 1u : 0u;
+            }
+            if (tid < (int)ncand && above < remaining && remaining <= above + same) {
+                sm.kth = mine;
+                sm.need = remaining - above;
+            }
+            __syncthreads();
+        } else {
+            radix_select<false>(s, sm, ncand, remaining, kth_bin, lo, inv, tid, lane, wave);
+        }
         const uint32_t kth = sm.kth;
         for (uint32_t i = tid; i < ncand; i += kTopkThreads) {
             if (sm.idx[i] < slice_start) {
@@ -374,14 +397,13 @@ __global__ __launch_bounds__(kTopkThreads) void topk_emit_kernel(const float *sc
     }
     __syncthreads();
 
-    // compaction in index order: this thread owns the 16 consecutive scores of granules
-    // first + 4*tid .. first + 4*tid + 3, so one prefix sum over the threads orders the slice
+    // compaction in index order: each thread owns 16 consecutive scores, so one prefix sum
+    // over the threads orders the slice
     uint32_t gt_mask = 0, eq_mask = 0;  // bit 4*u + e
 #pragma unroll
     for (int u = 0; u < kPerThread; ++u) {
         const int i = s.first + kPerThread * tid + u;
-        const float4 q = i < s.n4 ? s.src4[i] : make_float4(0.f, 0.f, 0.f, 0.f);
-        const float f[4] = {q.x, q.y, q.z, q.w};
+        const float f[4] = {own[u].x, own[u].y, own[u].z, own[u].w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int j = 4 * i - s.mis + e;

@@ -17,7 +17,7 @@ BF16, F32 = 0, 1
 LAYER_DENSE, LAYER_SELECT, LAYER_SPARSE = 0, 1, 2
 
 EXPORTS = ("td_validate", "td_workspace_bytes", "td_topk_workspace_bytes", "td_create", "td_destroy", "td_full_attend",
-           "td_select_tokens", "td_sparse_attend", "td_topk", "td_decode_step", "td_set_tuning",
+           "td_select_tokens", "td_sparse_attend", "td_topk", "td_decode_step", "td_set_tuning", "td_probe_stream",
            "td_status_string", "td_last_error")
 
 
@@ -66,7 +66,8 @@ def lib():
     L.td_decode_step.argtypes = [vp, shp, i32, ctypes.POINTER(i32), ctypes.POINTER(vp), ctypes.POINTER(vp),
                                  ctypes.POINTER(vp), i32, ctypes.POINTER(vp), vp, vp]
     L.td_decode_step.restype = ctypes.c_int
-    L.td_set_tuning.argtypes, L.td_set_tuning.restype = [vp, i32, i32, i32], ctypes.c_int
+    L.td_set_tuning.argtypes, L.td_set_tuning.restype = [vp, i32, i32, i32, i32], ctypes.c_int
+    L.td_probe_stream.argtypes, L.td_probe_stream.restype = [vp, vp, vp, sz, vp], ctypes.c_int
     L.td_status_string.argtypes, L.td_status_string.restype = [ctypes.c_int], ctypes.c_char_p
     L.td_last_error.argtypes, L.td_last_error.restype = [vp], ctypes.c_char_p
     _lib = L
@@ -121,8 +122,9 @@ class Tidal:
         if st != OK:
             raise TidalError(st, lib().td_last_error(self._ctx).decode())
 
-    def set_tuning(self, target_workgroups=0, min_chunk_dense=0, min_chunk_sparse=0):
-        self._check(lib().td_set_tuning(self._ctx, target_workgroups, min_chunk_dense, min_chunk_sparse))
+    def set_tuning(self, target_workgroups=0, min_chunk_dense=0, min_chunk_sparse=0, max_splits=0):
+        self._check(lib().td_set_tuning(self._ctx, target_workgroups, min_chunk_dense, min_chunk_sparse,
+                                        max_splits))
 
     def full_attend(self, shape, q, K, V, out):
         self._check(lib().td_full_attend(self._ctx, ctypes.byref(shape), q.data_ptr(), K.data_ptr(),
@@ -146,6 +148,12 @@ class Tidal:
         self._check(lib().td_topk(self._ctx, scores.data_ptr(), stride, rows, row_lens.data_ptr(),
                                   rows_per_len, scores.shape[1], k, positions.data_ptr(), _stream()))
         return positions
+
+    def probe_stream(self, src, dst=None):
+        """Streams the bytes of `src` (copying them to `dst` when given) with a plain kernel."""
+        nbytes = src.numel() * src.element_size()
+        self._check(lib().td_probe_stream(self._ctx, dst.data_ptr() if dst is not None else None,
+                                          src.data_ptr(), nbytes, _stream()))
 
     def decode_step(self, shape, schedule, qs, Ks, Vs, k, outs, positions):
         n = len(schedule)
