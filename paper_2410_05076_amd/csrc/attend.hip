@@ -23,7 +23,6 @@ namespace {
 
 constexpr int kWavesPerGroup = 4;
 constexpr int kThreads = kWavesPerGroup * kWave;
-constexpr int kUnroll = 4;  // row loads in flight per wave, for each of K and V
 constexpr float kEmptyMax = -3.0e38f;
 
 template <int CTRL>
@@ -103,6 +102,9 @@ __global__ __launch_bounds__(kThreads) void attend_split_kernel(const AttendPara
     constexpr int EPL = E::kPerLane;
     constexpr int LPR = D / EPL;        // lanes per row
     constexpr int TPW = kWave / LPR;    // rows per wave-wide load
+    // row loads in flight per wave for each of K and V: the gather of a sparse layer is one
+    // short burst, so it issues twice as many at once
+    constexpr int kUnroll = MODE == kSparse && G <= 4 ? 8 : 4;
     constexpr int STEP = kUnroll * TPW; // rows per wave per iteration
 
     const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
