@@ -47,7 +47,7 @@ def main():
     ap.add_argument("--kernel-reps", type=int, default=24)
     ap.add_argument("--probe-only", action="store_true",
                     help="run only the plain streaming kernels (1 GiB read, 1 GiB copy): counter calibration")
-    ap.add_argument("--tune", default="", help="target_workgroups,min_chunk_dense,min_chunk_sparse,max_splits (0 = default)")
+    ap.add_argument("--tune", default="", help="target_workgroups,min_chunk_dense,min_chunk_sparse,max_splits,kernel_variant (0 = default)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus %d is not supported "

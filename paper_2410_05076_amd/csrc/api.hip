@@ -14,7 +14,7 @@ struct td_ctx {
     int device = 0;
     char *workspace = nullptr;
     size_t workspace_bytes = 0;
-    int32_t target_workgroups = 0, min_chunk_dense = 0, min_chunk_sparse = 0, max_splits = 0;
+    int32_t target_workgroups = 0, min_chunk_dense = 0, min_chunk_sparse = 0, max_splits = 0, kernel_variant = 0;
     char error[256] = {0};
 };
 
@@ -131,7 +131,10 @@ td_status attend(td_ctx *ctx, const td_shape *s, int mode, const void *q, const 
     p.k = k;
     p.scale = s->sm_scale > 0.f ? s->sm_scale : 1.0f / sqrtf((float)s->head_dim);
     plan_chunks(ctx, s, mode == kSparse, mode == kSparse ? k : s->max_seq_len, &p.chunk, &p.num_splits);
-    const hipError_t e = launch_attend(s->dtype, s->head_dim, s->num_q_heads / s->num_kv_heads, mode, p, stream);
+    const int group = s->num_q_heads / s->num_kv_heads;
+    const bool mfma = s->dtype == TD_BF16 && s->head_dim == 128 && ctx->kernel_variant == 1;
+    const hipError_t e = mfma ? launch_attend_mfma(group, mode, p, stream)
+                              : launch_attend(s->dtype, s->head_dim, group, mode, p, stream);
     if (e != hipSuccess) return fail(ctx, TD_ERR_HIP, "attention launch failed: %s", hipGetErrorString(e));
     return TD_OK;
 }
@@ -213,14 +216,16 @@ td_status td_destroy(td_ctx *ctx) {
 }
 
 td_status td_set_tuning(td_ctx *ctx, int32_t target_workgroups, int32_t min_chunk_dense,
-                        int32_t min_chunk_sparse, int32_t max_splits) {
+                        int32_t min_chunk_sparse, int32_t max_splits, int32_t kernel_variant) {
     if (!ctx) return TD_ERR_INVALID_ARG;
-    if (target_workgroups < 0 || min_chunk_dense < 0 || min_chunk_sparse < 0 || max_splits < 0)
+    if (target_workgroups < 0 || min_chunk_dense < 0 || min_chunk_sparse < 0 || max_splits < 0 ||
+        kernel_variant < 0 || kernel_variant > 1)
         return fail(ctx, TD_ERR_INVALID_ARG, "%s", "tuning values must be >= 0");
     ctx->target_workgroups = target_workgroups;
     ctx->min_chunk_dense = min_chunk_dense;
     ctx->min_chunk_sparse = min_chunk_sparse;
     ctx->max_splits = max_splits;
+    ctx->kernel_variant = kernel_variant;
     return TD_OK;
 }
 

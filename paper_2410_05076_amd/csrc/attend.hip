@@ -16,14 +16,10 @@
 // Token selection (Sec. 3.1): the scaled inner products are not turned into probabilities;
 // their sum over the group's query heads is written once per token while the row is in
 // registers, and top-k runs on those sums afterwards.
-#include "common.h"
+#include "attend_tail.h"
 
 namespace tidal {
 namespace {
-
-constexpr int kWavesPerGroup = 4;
-constexpr int kThreads = kWavesPerGroup * kWave;
-constexpr float kEmptyMax = -3.0e38f;
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_move(float v) {
@@ -41,8 +37,6 @@ __device__ __forceinline__ float row_sum(float v) {
     if constexpr (LPR >= 32) v += __shfl_xor(v, 16);
     return v;
 }
-
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 template <int DT>
 struct Elems;
@@ -72,29 +66,6 @@ struct Elems<TD_F32> {
         f[3] = __uint_as_float(r.w);
     }
 };
-
-__device__ __forceinline__ uint32_t bf16_bits_rne(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;  // NaN stays NaN
-    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-}
-
-template <int DT>
-__device__ __forceinline__ void store_out(void *out, int64_t i, float v) {
-    if constexpr (DT == TD_BF16)
-        static_cast<uint16_t *>(out)[i] = (uint16_t)bf16_bits_rne(v);
-    else
-        static_cast<float *>(out)[i] = v;
-}
-
-// Device-scope store that goes through to memory instead of staying in this XCD's L2, and
-// the matching load that does not trust this XCD's caches.
-__device__ __forceinline__ void publish(float *p, float v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ uint64_t coherent_load(const uint64_t *p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
 
 template <int DT, int D, int G, int MODE>
 __global__ __launch_bounds__(kThreads) void attend_split_kernel(const AttendParams p) {
@@ -161,7 +132,6 @@ __global__ __launch_bounds__(kThreads) void attend_split_kernel(const AttendPara
         uint4 kraw[kUnroll], vraw[kUnroll];
         bool valid[kUnroll];
         int64_t off[kUnroll];
-        int tok[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const int t = base + u * TPW + r;
@@ -175,32 +145,38 @@ __global__ __launch_bounds__(kThreads) void attend_split_kernel(const AttendPara
                 row = ok ? t : t1 - 1;
             }
             valid[u] = ok;
-            tok[u] = row;
             off[u] = (int64_t)row * row_bytes;
-            kraw[u] = *(const uint4 *)(Kb + off[u]);
+            kraw[u] = stream_load16(Kb + off[u]);
         }
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) vraw[u] = *(const uint4 *)(Vb + off[u]);
+        for (int u = 0; u < kUnroll; ++u) vraw[u] = stream_load16(Vb + off[u]);
 
-        float s2[kUnroll][G];
+        float s2[kUnroll][G], gsum[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             float kf[EPL];
             E::unpack(kraw[u], kf);
-            float gsum = 0.f;
+            gsum[u] = 0.f;
 #pragma unroll
             for (int i = 0; i < G; ++i) {
                 float d = 0.f;
 #pragma unroll
                 for (int e = 0; e < EPL; ++e) d = fmaf(kf[e], qf[i][e], d);
                 d = row_sum<LPR>(d);
-                gsum += d * p.scale;
+                gsum[u] += d * p.scale;
                 s2[u][i] = valid[u] ? d * scale2 : -INFINITY;
             }
-            if constexpr (MODE == kSelect) {
-                if (c == 0 && valid[u])
-                    p.scores[((int64_t)b * p.num_kv_heads + g) * p.score_stride + tok[u]] = gsum;
-            }
+        }
+        if constexpr (MODE == kSelect) {
+            // every lane of a row holds the row's sums; lane c < kUnroll writes the one of load c,
+            // so the wave stores its kUnroll * TPW consecutive scores with one instruction
+            static_assert(kUnroll <= LPR, "one writing lane per load");
+            float mine = gsum[0];
+#pragma unroll
+            for (int u = 1; u < kUnroll; ++u) mine = c == u ? gsum[u] : mine;
+            const int t = base + c * TPW + r;
+            if (c < kUnroll && t < t1)
+                p.scores[((int64_t)b * p.num_kv_heads + g) * p.score_stride + t] = mine;
         }
 
         float pr[kUnroll][G];
@@ -235,10 +211,7 @@ __global__ __launch_bounds__(kThreads) void attend_split_kernel(const AttendPara
     // at most four heads at a time to bound the LDS footprint
     constexpr int RG = kWavesPerGroup * TPW;  // row groups per workgroup
     constexpr int GC = G < 4 ? G : 4;         // heads per pass
-    __shared__ float s_m[RG][GC], s_l[RG][GC], s_w[RG][GC], s_max[GC];
-    // row-group accumulators [RG][GC][D]; reused by the final merge as [kThreads] float4 + float2
-    constexpr int kAccFloats = RG * GC * D > kThreads * 6 ? RG * GC * D : kThreads * 6;
-    __shared__ __align__(16) float s_acc[kAccFloats];
+    __shared__ TailShared<D, GC, RG> sm;
     const int rg = wave * TPW + r;
 #pragma unroll
     for (int h0 = 0; h0 < G; h0 += GC) {
@@ -247,125 +220,18 @@ __global__ __launch_bounds__(kThreads) void attend_split_kernel(const AttendPara
         for (int i = 0; i < GC; ++i) {
 #pragma unroll
             for (int e = 0; e < EPL; e += 4)
-                *reinterpret_cast<float4 *>(&s_acc[(rg * GC + i) * D + c * EPL + e]) =
+                *reinterpret_cast<float4 *>(&sm.acc[(rg * GC + i) * D + c * EPL + e]) =
                     make_float4(acc[h0 + i][e], acc[h0 + i][e + 1], acc[h0 + i][e + 2], acc[h0 + i][e + 3]);
             if (c == 0) {
-                s_m[rg][i] = m[h0 + i];
-                s_l[rg][i] = l[h0 + i];
+                sm.m[rg][i] = m[h0 + i];
+                sm.l[rg][i] = l[h0 + i];
             }
         }
         __syncthreads();
-        if (threadIdx.x < RG * GC) {
-            const int i = threadIdx.x % GC, x = threadIdx.x / GC;
-            float mx = s_m[0][i];
-#pragma unroll
-            for (int y = 1; y < RG; ++y) mx = fmaxf(mx, s_m[y][i]);
-            s_w[x][i] = fast_exp2(s_m[x][i] - mx);
-            if (x == 0) s_max[i] = mx;
-        }
-        __syncthreads();
-        for (int idx = threadIdx.x; idx < GC * D; idx += kThreads) {
-            const int i = idx / D, ch = idx % D;
-            float ls = 0.f, as = 0.f;
-#pragma unroll
-            for (int y = 0; y < RG; ++y) {
-                const float w = s_w[y][i];
-                ls = fmaf(s_l[y][i], w, ls);
-                as = fmaf(s_acc[(y * GC + i) * D + ch], w, as);
-            }
-            const int64_t head = (int64_t)b * p.num_q_heads + g * G + h0 + i;
-            if (ns == 1) {  // the only chunk: finish here, no partials
-                store_out<DT>(p.out, head * D + ch, ls > 0.f ? as / ls : 0.f);
-            } else {
-                const int64_t slot = head * p.num_splits + split;
-                publish(&p.part_acc[slot * D + ch], as);
-                if (ch == 0) {
-                    publish(&p.part_ml[slot * 2], s_max[i]);
-                    publish(&p.part_ml[slot * 2 + 1], ls);
-                }
-            }
-        }
+        fold_states<DT, D, G, GC, RG>(p, sm, b, g, split, ns, h0);
     }
     if (ns == 1) return;
-
-    // The chunk that finishes last merges all partials of its (sequence, KV head).
-    // Partials are published with device-scope write-through stores and every wave waits
-    // for its stores to complete before the barrier, so they are in memory before this
-    // workgroup's ticket is taken.  (A release fence in every workgroup would write back the
-    // whole L2 each time.)  The counter returns to zero for the next launch.
-    __shared__ int s_last;
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        int *counter = p.counters + b * p.num_kv_heads + g;
-        const int done = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        s_last = done == ns - 1;
-        if (s_last) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    __syncthreads();
-    if (!s_last) return;
-
-    // One pass over the partials: thread (sg, col) folds chunks sg, sg + NG, ... of one float4
-    // column of one head with the online rescaling rule, then the NG threads of a column
-    // are folded through LDS.  The partials are read with device-scope loads (they come
-    // from other workgroups' write-through stores), which needs no cache invalidate.
-    constexpr int COLS = G * D / 4;      // float4 columns over all heads of the group
-    constexpr int NG = kThreads / COLS;  // chunk groups working in parallel
-    static_assert(NG >= 1 && NG * COLS == kThreads, "G * D / 4 must divide the workgroup size");
-    const int col = threadIdx.x % COLS, sg = threadIdx.x / COLS;
-    const int hi = col / (D / 4), c4 = col % (D / 4);
-    const int64_t head = (int64_t)b * p.num_q_heads + g * G + hi;
-    const uint64_t *ml = reinterpret_cast<const uint64_t *>(p.part_ml) + head * p.num_splits;
-    const uint64_t *pa = reinterpret_cast<const uint64_t *>(p.part_acc) + (head * p.num_splits * (D / 4) + c4) * 2;
-    float mm = kEmptyMax, ll = 0.f;
-    float4 aa = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll 8
-    for (int s = sg; s < ns; s += NG) {
-        const uint64_t vml = coherent_load(ml + s);
-        const uint64_t lo = coherent_load(pa + (int64_t)s * (D / 2));
-        const uint64_t hi2 = coherent_load(pa + (int64_t)s * (D / 2) + 1);
-        const float2 v = make_float2(__uint_as_float((uint32_t)vml), __uint_as_float((uint32_t)(vml >> 32)));
-        const float4 x = make_float4(__uint_as_float((uint32_t)lo), __uint_as_float((uint32_t)(lo >> 32)),
-                                     __uint_as_float((uint32_t)hi2), __uint_as_float((uint32_t)(hi2 >> 32)));
-        const float mn = fmaxf(mm, v.x);
-        const float wa = fast_exp2(mm - mn), wb = fast_exp2(v.x - mn);
-        ll = ll * wa + v.y * wb;
-        aa.x = aa.x * wa + x.x * wb;
-        aa.y = aa.y * wa + x.y * wb;
-        aa.z = aa.z * wa + x.z * wb;
-        aa.w = aa.w * wa + x.w * wb;
-        mm = mn;
-    }
-    if constexpr (NG > 1) {
-        float4 *red_a = reinterpret_cast<float4 *>(s_acc);                   // [kThreads], s_acc is free now
-        float2 *red_ml = reinterpret_cast<float2 *>(red_a + kThreads);       // [kThreads]
-        red_a[threadIdx.x] = aa;
-        red_ml[threadIdx.x] = make_float2(mm, ll);
-        __syncthreads();
-        if (sg == 0) {
-#pragma unroll
-            for (int o = 1; o < NG; ++o) {
-                const float2 v = red_ml[o * COLS + col];
-                const float4 x = red_a[o * COLS + col];
-                const float mn = fmaxf(mm, v.x);
-                const float wa = fast_exp2(mm - mn), wb = fast_exp2(v.x - mn);
-                ll = ll * wa + v.y * wb;
-                aa.x = aa.x * wa + x.x * wb;
-                aa.y = aa.y * wa + x.y * wb;
-                aa.z = aa.z * wa + x.z * wb;
-                aa.w = aa.w * wa + x.w * wb;
-                mm = mn;
-            }
-        }
-    }
-    if (sg == 0) {
-        const float inv = ll > 0.f ? 1.f / ll : 0.f;
-        const int64_t oi = head * D + c4 * 4;
-        store_out<DT>(p.out, oi, aa.x * inv);
-        store_out<DT>(p.out, oi + 1, aa.y * inv);
-        store_out<DT>(p.out, oi + 2, aa.z * inv);
-        store_out<DT>(p.out, oi + 3, aa.w * inv);
-    }
+    finish_chunks<DT, D, G, GC, RG>(p, sm, b, g, ns);
 }
 
 template <int DT, int D, int G>

@@ -1,0 +1,209 @@
+// Shared by the attention kernels: constants, small device helpers, and the tail of a chunk -
+// folding the workgroup's online-softmax states through LDS, publishing the chunk's partial,
+// taking a ticket, and (in the chunk that finishes last) merging all partials of the
+// (sequence, KV head) and writing the output row.
+#pragma once
+#include "common.h"
+
+namespace tidal {
+namespace {
+
+constexpr int kWavesPerGroup = 4;
+constexpr int kThreads = kWavesPerGroup * kWave;
+constexpr float kEmptyMax = -3.0e38f;
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// 16-byte load of cache data that is read exactly once: the non-temporal hint keeps the
+// stream from displacing other lines (a plain 2 GiB streaming read measures ~6.3 TB/s with
+// ordinary loads and ~7.2 TB/s with this hint on MI355X).
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 stream_load16(const void *p) {
+    const u32x4_t v = __builtin_nontemporal_load(static_cast<const u32x4_t *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+__device__ __forceinline__ uint32_t bf16_bits_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;  // NaN stays NaN
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+template <int DT>
+__device__ __forceinline__ void store_out(void *out, int64_t i, float v) {
+    if constexpr (DT == TD_BF16)
+        static_cast<uint16_t *>(out)[i] = (uint16_t)bf16_bits_rne(v);
+    else
+        static_cast<float *>(out)[i] = v;
+}
+
+// Device-scope store that goes through to memory instead of staying in this XCD's L2, and
+// the matching load that does not trust this XCD's caches.
+__device__ __forceinline__ void publish(float *p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint64_t coherent_load(const uint64_t *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// The same device-scope (sc1) load, 16 and 8 bytes wide.  The compiler has no atomic load of
+// that width, so these are written as instructions; they only issue the load, and
+// wait_coherent_loads() - which names every destination as an operand, so nothing that uses
+// them can move above it - waits for all of them.
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void coherent_load16(f32x4_t &dst, const void *p) {
+    asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(dst) : "v"(p) : "memory");
+}
+__device__ __forceinline__ void coherent_load8(f32x2_t &dst, const void *p) {
+    asm volatile("global_load_dwordx2 %0, %1, off sc1" : "=v"(dst) : "v"(p) : "memory");
+}
+__device__ __forceinline__ void wait_coherent_loads(f32x4_t (&x)[8], f32x2_t (&v)[8]) {
+    asm volatile("s_waitcnt vmcnt(0)"
+                 : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7]),
+                   "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]), "+v"(v[4]), "+v"(v[5]), "+v"(v[6]), "+v"(v[7])
+                 :
+                 : "memory");
+}
+
+// LDS needed by fold_states / finish_chunks for RG states of GC heads each.
+template <int D, int GC, int RG>
+struct TailShared {
+    float m[RG][GC], l[RG][GC], w[RG][GC], max[GC];
+    // state accumulators [RG][GC][D]; reused by the final merge as [kThreads] float4 + float2
+    static constexpr int kAccFloats = RG * GC * D > kThreads * 6 ? RG * GC * D : kThreads * 6;
+    __align__(16) float acc[kAccFloats];
+    int last;
+};
+
+// Folds the RG online-softmax states of heads h0 .. h0+GC-1 (already in sm.m, sm.l, sm.acc;
+// the caller has synchronised after writing them) with the rescaling rule.  With a single
+// chunk the output row is written at once, otherwise the chunk's partial is published.
+template <int DT, int D, int G, int GC, int RG>
+__device__ __forceinline__ void fold_states(const AttendParams &p, TailShared<D, GC, RG> &sm, int b, int g,
+                                            int split, int ns, int h0) {
+    if (threadIdx.x < RG * GC) {
+        const int i = threadIdx.x % GC, x = threadIdx.x / GC;
+        float mx = sm.m[0][i];
+#pragma unroll
+        for (int y = 1; y < RG; ++y) mx = fmaxf(mx, sm.m[y][i]);
+        sm.w[x][i] = fast_exp2(sm.m[x][i] - mx);
+        if (x == 0) sm.max[i] = mx;
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < GC * D; idx += kThreads) {
+        const int i = idx / D, ch = idx % D;
+        float ls = 0.f, as = 0.f;
+#pragma unroll
+        for (int y = 0; y < RG; ++y) {
+            const float w = sm.w[y][i];
+            ls = fmaf(sm.l[y][i], w, ls);
+            as = fmaf(sm.acc[(y * GC + i) * D + ch], w, as);
+        }
+        const int64_t head = (int64_t)b * p.num_q_heads + g * G + h0 + i;
+        if (ns == 1) {  // the only chunk: finish here, no partials
+            store_out<DT>(p.out, head * D + ch, ls > 0.f ? as / ls : 0.f);
+        } else {
+            const int64_t slot = head * p.num_splits + split;
+            publish(&p.part_acc[slot * D + ch], as);
+            if (ch == 0) {
+                publish(&p.part_ml[slot * 2], sm.max[i]);
+                publish(&p.part_ml[slot * 2 + 1], ls);
+            }
+        }
+    }
+}
+
+// After every head's partial of this chunk has been published: the chunk that finishes last
+// merges all partials of its (sequence, KV head).  Partials are published with device-scope
+// write-through stores and every wave waits for its stores to complete before the barrier,
+// so they are in memory before this workgroup's ticket is taken.  (A release fence in every
+// workgroup would write back the whole L2 each time.)  The counter returns to zero for the
+// next launch.
+template <int DT, int D, int G, int GC, int RG>
+__device__ __forceinline__ void finish_chunks(const AttendParams &p, TailShared<D, GC, RG> &sm, int b, int g,
+                                              int ns) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int *counter = p.counters + b * p.num_kv_heads + g;
+        const int done = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sm.last = done == ns - 1;
+        if (sm.last) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (!sm.last) return;
+
+    // One pass over the partials: thread (sg, col) folds chunks sg, sg + NG, ... of one float4
+    // column of one head with the online rescaling rule, eight chunks in flight at a time,
+    // then the NG threads of a column are folded through LDS.  The partials are read with
+    // device-scope loads (they come from other workgroups' write-through stores), which
+    // needs no cache invalidate.
+    constexpr int COLS = G * D / 4;      // float4 columns over all heads of the group
+    constexpr int NG = kThreads / COLS;  // chunk groups working in parallel
+    static_assert(NG >= 1 && NG * COLS == kThreads, "G * D / 4 must divide the workgroup size");
+    const int col = threadIdx.x % COLS, sg = threadIdx.x / COLS;
+    const int hi = col / (D / 4), c4 = col % (D / 4);
+    const int64_t head = (int64_t)b * p.num_q_heads + g * G + hi;
+    const char *ml = reinterpret_cast<const char *>(p.part_ml + head * p.num_splits * 2);
+    const char *pa = reinterpret_cast<const char *>(p.part_acc + (head * p.num_splits * (D / 4) + c4) * 4);
+    float mm = kEmptyMax, ll = 0.f;
+    float4 aa = make_float4(0.f, 0.f, 0.f, 0.f);
+    constexpr int kBatch = 8;  // partials in flight per thread
+    for (int s0 = sg; s0 < ns; s0 += NG * kBatch) {
+        f32x4_t x[kBatch];
+        f32x2_t v[kBatch];
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            const int s = min(s0 + j * NG, ns - 1);  // clamped repeats are ignored below
+            coherent_load16(x[j], pa + (int64_t)s * (D * 4));
+            coherent_load8(v[j], ml + (int64_t)s * 8);
+        }
+        wait_coherent_loads(x, v);
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            if (s0 + j * NG < ns) {
+                const float mn = fmaxf(mm, v[j].x);
+                const float wa = fast_exp2(mm - mn), wb = fast_exp2(v[j].x - mn);
+                ll = ll * wa + v[j].y * wb;
+                aa.x = aa.x * wa + x[j].x * wb;
+                aa.y = aa.y * wa + x[j].y * wb;
+                aa.z = aa.z * wa + x[j].z * wb;
+                aa.w = aa.w * wa + x[j].w * wb;
+                mm = mn;
+            }
+        }
+    }
+    if constexpr (NG > 1) {
+        float4 *red_a = reinterpret_cast<float4 *>(sm.acc);             // [kThreads], sm.acc is free now
+        float2 *red_ml = reinterpret_cast<float2 *>(red_a + kThreads);  // [kThreads]
+        red_a[threadIdx.x] = aa;
+        red_ml[threadIdx.x] = make_float2(mm, ll);
+        __syncthreads();
+        if (sg == 0) {
+#pragma unroll
+            for (int o = 1; o < NG; ++o) {
+                const float2 v = red_ml[o * COLS + col];
+                const float4 x = red_a[o * COLS + col];
+                const float mn = fmaxf(mm, v.x);
+                const float wa = fast_exp2(mm - mn), wb = fast_exp2(v.x - mn);
+                ll = ll * wa + v.y * wb;
+                aa.x = aa.x * wa + x.x * wb;
+                aa.y = aa.y * wa + x.y * wb;
+                aa.z = aa.z * wa + x.z * wb;
+                aa.w = aa.w * wa + x.w * wb;
+                mm = mn;
+            }
+        }
+    }
+    if (sg == 0) {
+        const float inv = ll > 0.f ? 1.f / ll : 0.f;
+        const int64_t oi = head * D + c4 * 4;
+        store_out<DT>(p.out, oi, aa.x * inv);
+        store_out<DT>(p.out, oi + 1, aa.y * inv);
+        store_out<DT>(p.out, oi + 2, aa.z * inv);
+        store_out<DT>(p.out, oi + 3, aa.w * inv);
+    }
+}
+
+}  // namespace
+}  // namespace tidal

@@ -52,8 +52,11 @@ struct AttendParams {
 };
 
 // Enqueues the split attention kernel (the last chunk to finish merges the partials).
+// launch_attend: vector-ALU kernel for every supported dtype / head_dim;
+// launch_attend_mfma: matrix-core kernel, bf16 with head_dim 128 only.
 hipError_t launch_attend(int dtype, int head_dim, int group, int mode, const AttendParams &p,
                          hipStream_t stream);
+hipError_t launch_attend_mfma(int group, int mode, const AttendParams &p, hipStream_t stream);
 
 // argTopK over rows of fp32 scores.  scratch: topk_scratch_bytes(rows, max_len) bytes; reset
 // clears the per-row state first (not needed right after a selection attention launch).

@@ -66,7 +66,7 @@ def lib():
     L.td_decode_step.argtypes = [vp, shp, i32, ctypes.POINTER(i32), ctypes.POINTER(vp), ctypes.POINTER(vp),
                                  ctypes.POINTER(vp), i32, ctypes.POINTER(vp), vp, vp]
     L.td_decode_step.restype = ctypes.c_int
-    L.td_set_tuning.argtypes, L.td_set_tuning.restype = [vp, i32, i32, i32, i32], ctypes.c_int
+    L.td_set_tuning.argtypes, L.td_set_tuning.restype = [vp, i32, i32, i32, i32, i32], ctypes.c_int
     L.td_probe_stream.argtypes, L.td_probe_stream.restype = [vp, vp, vp, sz, vp], ctypes.c_int
     L.td_status_string.argtypes, L.td_status_string.restype = [ctypes.c_int], ctypes.c_char_p
     L.td_last_error.argtypes, L.td_last_error.restype = [vp], ctypes.c_char_p
@@ -122,9 +122,10 @@ class Tidal:
         if st != OK:
             raise TidalError(st, lib().td_last_error(self._ctx).decode())
 
-    def set_tuning(self, target_workgroups=0, min_chunk_dense=0, min_chunk_sparse=0, max_splits=0):
+    def set_tuning(self, target_workgroups=0, min_chunk_dense=0, min_chunk_sparse=0, max_splits=0,
+                   kernel_variant=0):
         self._check(lib().td_set_tuning(self._ctx, target_workgroups, min_chunk_dense, min_chunk_sparse,
-                                        max_splits))
+                                        max_splits, kernel_variant))
 
     def full_attend(self, shape, q, K, V, out):
         self._check(lib().td_full_attend(self._ctx, ctypes.byref(shape), q.data_ptr(), K.data_ptr(),
