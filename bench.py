@@ -84,7 +84,7 @@ def main():
         pos = torch.full((n_sel, w.batch, w.num_kv_heads, w.k), -1, dtype=torch.int32, device=dev)
         sets.append((qs, Ks, Vs, outs, pos))
         log("generated copy %d" % c)
-    shape = tidal.make_shape(sets[0][0][0], sets[0][1][0], lens)
+    shape = tidal.make_shape(sets[0][0][0], sets[0][1][0], lens, total_seq_len=sum(w.seq_lens))
     td = tidal.Tidal(shape, w.k)
     if args.tune:
         td.set_tuning(*[int(x) for x in args.tune.split(",")])

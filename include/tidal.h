@@ -84,6 +84,9 @@ typedef struct td_shape {
     int64_t kv_stride_tok;
     const int32_t *seq_lens;   /* DEVICE int32 [batch]; each in [1, max_seq_len] */
     int32_t max_seq_len;       /* HOST-known upper bound; sizes grids and workspace */
+    int64_t total_seq_len;     /* HOST hint: sum of seq_lens, or 0 if unknown.  Only steers the
+                                  launch plan (a ragged batch gets smaller chunks); results do
+                                  not depend on it */
 } td_shape;
 
 typedef struct td_ctx td_ctx;  /* opaque; owns the workspace (split partials, group scores) */

@@ -21,6 +21,7 @@ struct td_ctx {
 namespace {
 
 constexpr int32_t kDefaultTargetWorkgroups = 1024;
+constexpr int32_t kRaggedTargetWorkgroups = 8192;
 constexpr int32_t kDefaultMinChunkDense = 256;
 constexpr int32_t kDefaultMinChunkSparse = 128;
 constexpr int32_t kChunkGranule = 128;
@@ -52,6 +53,7 @@ const char *shape_problem(const td_shape *s, int32_t k, td_status *code) {
     if (s->kv_stride_tok % 8 || s->kv_stride_head % 8 || s->kv_stride_batch % 8)
         return "KV strides must be multiples of 8 elements";
     if (k > kSparseChunkMax * kSplitsMax) return "k is larger than 524288";
+    if (s->total_seq_len < 0) return "total_seq_len is negative";
     *code = TD_ERR_UNSUPPORTED;
     if (s->head_dim != 64 && s->head_dim != 128) return "head_dim must be 64 or 128";
     const int g = s->num_q_heads / s->num_kv_heads;
@@ -91,8 +93,12 @@ Workspace workspace_layout(const td_shape *s, int32_t k) {
 void plan_chunks(const td_ctx *ctx, const td_shape *s, bool sparse, int32_t tokens, int32_t *chunk,
                  int32_t *splits) {
     // sparse launches are latency-bound: fewer, fatter workgroups shorten the ticket and merge tail
-    const int32_t target = (ctx->target_workgroups > 0 ? ctx->target_workgroups : kDefaultTargetWorkgroups) /
-                           (sparse ? 2 : 1);
+    int32_t target = (ctx->target_workgroups > 0 ? ctx->target_workgroups : kDefaultTargetWorkgroups) / (sparse ? 2 : 1);
+    // a ragged batch (known from the host's hint) leaves many chunks of the grid empty and the
+    // rest unevenly spread over the CUs: smaller chunks balance it
+    const int64_t dense_tokens = (int64_t)s->batch * s->max_seq_len;
+    if (!sparse && ctx->target_workgroups == 0 && s->total_seq_len > 0 && s->total_seq_len * 10 < dense_tokens * 9)
+        target = kRaggedTargetWorkgroups;
     int32_t floor_chunk = sparse ? (ctx->min_chunk_sparse > 0 ? ctx->min_chunk_sparse : kDefaultMinChunkSparse)
                                  : (ctx->min_chunk_dense > 0 ? ctx->min_chunk_dense : kDefaultMinChunkDense);
     const int64_t groups = (int64_t)s->batch * s->num_kv_heads;

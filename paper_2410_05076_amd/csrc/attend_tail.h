@@ -68,7 +68,7 @@ __device__ __forceinline__ void wait_coherent_loads(f32x4_t (&x)[8], f32x2_t (&v
 // LDS needed by fold_states / finish_chunks for RG states of GC heads each.
 template <int D, int GC, int RG>
 struct TailShared {
-    float m[RG][GC], l[RG][GC], w[RG][GC], max[GC];
+    float m[RG][GC], l[RG][GC];
     // state accumulators [RG][GC][D]; reused by the final merge as [kThreads] float4 + float2
     static constexpr int kAccFloats = RG * GC * D > kThreads * 6 ? RG * GC * D : kThreads * 6;
     __align__(16) float acc[kAccFloats];
@@ -81,21 +81,15 @@ struct TailShared {
 template <int DT, int D, int G, int GC, int RG>
 __device__ __forceinline__ void fold_states(const AttendParams &p, TailShared<D, GC, RG> &sm, int b, int g,
                                             int split, int ns, int h0) {
-    if (threadIdx.x < RG * GC) {
-        const int i = threadIdx.x % GC, x = threadIdx.x / GC;
+    for (int idx = threadIdx.x; idx < GC * D; idx += kThreads) {
+        const int i = idx / D, ch = idx % D;
         float mx = sm.m[0][i];
 #pragma unroll
         for (int y = 1; y < RG; ++y) mx = fmaxf(mx, sm.m[y][i]);
-        sm.w[x][i] = fast_exp2(sm.m[x][i] - mx);
-        if (x == 0) sm.max[i] = mx;
-    }
-    __syncthreads();
-    for (int idx = threadIdx.x; idx < GC * D; idx += kThreads) {
-        const int i = idx / D, ch = idx % D;
         float ls = 0.f, as = 0.f;
 #pragma unroll
         for (int y = 0; y < RG; ++y) {
-            const float w = sm.w[y][i];
+            const float w = fast_exp2(sm.m[y][i] - mx);
             ls = fmaf(sm.l[y][i], w, ls);
             as = fmaf(sm.acc[(y * GC + i) * D + ch], w, as);
         }
@@ -106,7 +100,7 @@ __device__ __forceinline__ void fold_states(const AttendParams &p, TailShared<D,
             const int64_t slot = head * p.num_splits + split;
             publish(&p.part_acc[slot * D + ch], as);
             if (ch == 0) {
-                publish(&p.part_ml[slot * 2], sm.max[i]);
+                publish(&p.part_ml[slot * 2], mx);
                 publish(&p.part_ml[slot * 2 + 1], ls);
             }
         }

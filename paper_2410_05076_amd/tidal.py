@@ -28,7 +28,8 @@ class Shape(ctypes.Structure):
                 ("dtype", ctypes.c_int32), ("sm_scale", ctypes.c_float),
                 ("kv_stride_batch", ctypes.c_int64), ("kv_stride_head", ctypes.c_int64),
                 ("kv_stride_tok", ctypes.c_int64),
-                ("seq_lens", ctypes.c_void_p), ("max_seq_len", ctypes.c_int32)]
+                ("seq_lens", ctypes.c_void_p), ("max_seq_len", ctypes.c_int32),
+                ("total_seq_len", ctypes.c_int64)]
 
 
 class TidalError(RuntimeError):
@@ -82,12 +83,14 @@ def _dtype_code(t):
     raise TypeError("q, K, V must be bfloat16 or float32, got %s" % t)
 
 
-def make_shape(q, K, seq_lens, sm_scale=0.0):
-    """td_shape for q [B][Hq][d] and a cache tensor K [B][Hkv][N_max][d] (any strides with d contiguous)."""
+def make_shape(q, K, seq_lens, sm_scale=0.0, total_seq_len=0):
+    """td_shape for q [B][Hq][d] and a cache tensor K [B][Hkv][N_max][d] (any strides with d contiguous).
+
+    total_seq_len: the host's knowledge of sum(seq_lens), 0 if unknown (a launch-plan hint only)."""
     assert q.dim() == 3 and K.dim() == 4 and q.is_contiguous() and K.stride(3) == 1
     assert seq_lens.dtype == torch.int32 and seq_lens.is_contiguous() and seq_lens.numel() == q.shape[0]
     return Shape(q.shape[0], q.shape[1], K.shape[1], q.shape[2], _dtype_code(q.dtype), float(sm_scale),
-                 K.stride(0), K.stride(1), K.stride(2), seq_lens.data_ptr(), K.shape[2])
+                 K.stride(0), K.stride(1), K.stride(2), seq_lens.data_ptr(), K.shape[2], int(total_seq_len))
 
 
 def _stream():

@@ -15,7 +15,7 @@ def good_shape(**over):
     lens = ctypes.c_int32(100)
     f = dict(batch=1, num_q_heads=32, num_kv_heads=8, head_dim=128, dtype=tidal.BF16, sm_scale=0.0,
              kv_stride_batch=8 * 100 * 128, kv_stride_head=100 * 128, kv_stride_tok=128,
-             seq_lens=ctypes.addressof(lens), max_seq_len=100)
+             seq_lens=ctypes.addressof(lens), max_seq_len=100, total_seq_len=0)
     f.update(over)
     s = tidal.Shape(**f)
     s._keep = lens
@@ -49,6 +49,7 @@ def test_validate_accepts_the_benchmark_shapes():
     (dict(sm_scale=-1.0), 1, tidal.ERR_INVALID_ARG),
     (dict(kv_stride_tok=64), 1, tidal.ERR_INVALID_ARG),
     (dict(kv_stride_tok=132), 1, tidal.ERR_INVALID_ARG),
+    (dict(total_seq_len=-5), 1, tidal.ERR_INVALID_ARG),
     (dict(), 600000, tidal.ERR_INVALID_ARG),
     (dict(head_dim=96, kv_stride_tok=96), 1, tidal.ERR_UNSUPPORTED),
     (dict(num_q_heads=24, num_kv_heads=8), 1, tidal.ERR_UNSUPPORTED),

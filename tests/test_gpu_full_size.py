@@ -40,7 +40,7 @@ def run_step(w, sparse_to_check, graph=False, tag=""):
     qs, Ks, Vs = zip(*layers)
     del layers
     lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=DEV)
-    shape = tidal.make_shape(qs[0], Ks[0], lens)
+    shape = tidal.make_shape(qs[0], Ks[0], lens, total_seq_len=sum(w.seq_lens))
     td = tidal.Tidal(shape, w.k)
     outs = [torch.full_like(q, float("nan")) for q in qs]
     n_sel = sum(1 for x in w.schedule if x == W.SELECT)

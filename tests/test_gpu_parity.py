@@ -32,21 +32,23 @@ def host(t):
 class Case:
     """One workload on the device: context, shape, seq_lens."""
 
-    def __init__(self, w, K_example, q_example):
+    def __init__(self, w, K_example, q_example, kernel_variant=0):
         self.w = w
         self.lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=DEV)
-        self.shape = tidal.make_shape(q_example, K_example, self.lens)
+        self.shape = tidal.make_shape(q_example, K_example, self.lens, total_seq_len=sum(w.seq_lens))
         self.td = tidal.Tidal(self.shape, w.k)
+        if kernel_variant:
+            self.td.set_tuning(kernel_variant=kernel_variant)
 
     def out_like(self, q):
         return torch.full_like(q, float("nan"))
 
 
-def run_layer_checks(w, layer_kinds, tag):
+def run_layer_checks(w, layer_kinds, tag, kernel_variant=0):
     """Runs full / select / sparse on one layer each through the three entry points."""
     layers = device_layers(w, range(len(layer_kinds)))
     q0, K0, V0 = layers[0]
-    c = Case(w, K0, q0)
+    c = Case(w, K0, q0, kernel_variant)
     stats = {}
     rho = None
     for i, kind in enumerate(layer_kinds):
@@ -125,6 +127,19 @@ def test_scaled_configs(name, over, kinds):
     w = W.workload(name, **over)
     tag = "%s%s" % (name, sorted(over.items()))
     run_layer_checks(w, kinds, tag)
+
+
+@pytest.mark.parametrize("name,over", [
+    ("c2", dict(context=4099, k=300)),                                    # G = 4
+    ("c3", dict(context=8229, k=512, tau=512.0)),                         # G = 1
+    ("c4", dict(seq_lens=(777, 64, 1, 2500, 1300), k=256)),               # ragged, k > N for some
+    ("c2", dict(context=3000, k=200, num_q_heads=64)),                    # G = 8
+    ("c2", dict(context=1111, k=1111, num_q_heads=16)),                   # G = 2, k = N
+])
+def test_matrix_core_kernel_variant(name, over):
+    # the MFMA attention kernel (bf16, head_dim 128) is an option of td_set_tuning; same bar
+    w = W.workload(name, **over)
+    run_layer_checks(w, (D, S, P), "mfma %s%s" % (name, sorted(over.items())), kernel_variant=1)
 
 
 def test_sparse_with_k_equal_n_matches_full_attention():
