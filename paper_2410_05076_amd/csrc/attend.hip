@@ -67,8 +67,18 @@ struct Elems<TD_F32> {
     }
 };
 
-template <int DT, int D, int G, int MODE>
-__global__ __launch_bounds__(kThreads) void attend_split_kernel(const AttendParams p) {
+// Up to four query heads per group the streaming loop fits 128 registers, i.e. four
+// workgroups per CU; the attribute keeps the rarely executed final merge from raising the
+// kernel's register count above that.
+//
+// W is the number of wave64s per workgroup (4 or 8).  Eight-wave workgroups own chunks twice
+// as long, so a (sequence, KV head) has half as many partials to merge across workgroups -
+// the merge inside a workgroup goes through LDS and is much cheaper - which pays when the
+// launch is short enough for its tail to matter.
+template <int DT, int D, int G, int MODE, int W>
+__global__ __launch_bounds__(W *kWave) __attribute__((amdgpu_waves_per_eu(G <= 4 && MODE != kSparse ? 4 : 1)))
+void attend_split_kernel(const AttendParams p) {
+    constexpr int T = W * kWave;  // threads per workgroup
     using E = Elems<DT>;
     constexpr int EPL = E::kPerLane;
     constexpr int LPR = D / EPL;        // lanes per row
@@ -84,34 +94,54 @@ __global__ __launch_bounds__(kThreads) void attend_split_kernel(const AttendPara
 
     if constexpr (MODE == kSelect) {  // leave the row's top-k state clear for the kernels that follow
         TopkRow *row = static_cast<TopkRow *>(p.topk_scratch) + (b * p.num_kv_heads + g);
-        for (int i = split * kThreads + threadIdx.x; i < kTopkBins; i += p.num_splits * kThreads) row->hist[i] = 0;
+        for (int i = split * T + threadIdx.x; i < kTopkBins; i += p.num_splits * T) row->hist[i] = 0;
         if (split == 0 && threadIdx.x == 0) row->ncand = 0;
     }
-    const int N = min(max(p.seq_lens[b], 0), p.max_seq_len);
-    const int n_tok = MODE == kSparse ? (N > 0 ? p.k : 0) : N;
     // A workgroup owns p.chunk consecutive tokens (a multiple of the 128-token granule): a
     // contiguous stream per workgroup keeps TLB and DRAM-page locality.
-    constexpr int TILE = kWavesPerGroup * STEP;
+    constexpr int TILE = W * STEP;
     const int t0 = split * p.chunk;
+
+    // The first loads depend on the launch arguments only.  They are issued here, ahead of the
+    // read of the sequence length, so all of them are in flight together: this lane's slice of
+    // the G queries of the group and, in sparse mode, the chunk's positions (staged in LDS
+    // below, once the sequence length has said that the workgroup has work).
+    uint4 qraw[G];
+#pragma unroll
+    for (int i = 0; i < G; ++i)
+        qraw[i] = *(const uint4 *)((const char *)p.q +
+                                   (((int64_t)b * p.num_q_heads + g * G + i) * D + c * EPL) * E::kBytes);
+    constexpr int kPosPerThread = MODE == kSparse ? kSparseChunkMax / T : 1;
+    int pstage[kPosPerThread];
+    if constexpr (MODE == kSparse) {
+        const int32_t *pos = p.positions + ((int64_t)b * p.num_kv_heads + g) * p.k;
+        const int len = min(p.k - t0, p.chunk);
+#pragma unroll
+        for (int i = 0; i < kPosPerThread; ++i) {
+            const int j = i * T + threadIdx.x;
+            pstage[i] = i * T < len ? pos[t0 + min(j, len - 1)] : -1;  // the condition is workgroup-uniform
+        }
+    }
+    asm volatile("" ::: "memory");  // the loads above stay above the branch on the sequence length
+
+    const int N = min(max(p.seq_lens[b], 0), p.max_seq_len);
+    const int n_tok = MODE == kSparse ? (N > 0 ? p.k : 0) : N;
     if (t0 >= n_tok) return;
     const int t1 = min(n_tok, t0 + p.chunk);
     const int ns = (n_tok + p.chunk - 1) / p.chunk;  // workgroups of this (sequence, KV head) with work
 
     __shared__ int s_pos[MODE == kSparse ? kSparseChunkMax : 1];
     if constexpr (MODE == kSparse) {
-        const int32_t *pos = p.positions + ((int64_t)b * p.num_kv_heads + g) * p.k;
-        for (int i = threadIdx.x; i < t1 - t0; i += kThreads) s_pos[i] = pos[t0 + i];
+#pragma unroll
+        for (int i = 0; i < kPosPerThread; ++i) {
+            const int j = i * T + threadIdx.x;
+            if (j < t1 - t0) s_pos[j] = pstage[i];
+        }
         __syncthreads();
     }
-
-    // this lane's slice of the G queries of the group
     float qf[G][EPL];
 #pragma unroll
-    for (int i = 0; i < G; ++i) {
-        const char *qp = (const char *)p.q +
-                         (((int64_t)b * p.num_q_heads + g * G + i) * D + c * EPL) * E::kBytes;
-        E::unpack(*(const uint4 *)qp, qf[i]);
-    }
+    for (int i = 0; i < G; ++i) E::unpack(qraw[i], qf[i]);
 
     const int64_t row_bytes = p.stride_tok * E::kBytes;
     const int64_t head_off = ((int64_t)b * p.stride_batch + (int64_t)g * p.stride_head) * E::kBytes + c * 16;
@@ -150,6 +180,7 @@ __global__ __launch_bounds__(kThreads) void attend_split_kernel(const AttendPara
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) vraw[u] = stream_load16(Vb + off[u]);
+        __builtin_amdgcn_sched_barrier(0);  // every load is issued before the first one is consumed
 
         float s2[kUnroll][G], gsum[kUnroll];
 #pragma unroll
@@ -209,9 +240,9 @@ __global__ __launch_bounds__(kThreads) void attend_split_kernel(const AttendPara
 
     // ---- merge the online-softmax states of the workgroup's row groups through LDS,
     // at most four heads at a time to bound the LDS footprint
-    constexpr int RG = kWavesPerGroup * TPW;  // row groups per workgroup
+    constexpr int RG = W * TPW;  // row groups per workgroup
     constexpr int GC = G < 4 ? G : 4;         // heads per pass
-    __shared__ TailShared<D, GC, RG> sm;
+    __shared__ TailShared<D, GC, RG, T> sm;
     const int rg = wave * TPW + r;
 #pragma unroll
     for (int h0 = 0; h0 < G; h0 += GC) {
@@ -228,48 +259,61 @@ __global__ __launch_bounds__(kThreads) void attend_split_kernel(const AttendPara
             }
         }
         __syncthreads();
-        fold_states<DT, D, G, GC, RG>(p, sm, b, g, split, ns, h0);
+        fold_states<DT, D, G, GC, RG, T>(p, sm, b, g, split, ns, h0);
     }
     if (ns == 1) return;
-    finish_chunks<DT, D, G, GC, RG>(p, sm, b, g, ns);
+    finish_chunks<DT, D, G, GC, RG, T>(p, sm, b, g, ns);
 }
 
-template <int DT, int D, int G>
+template <int DT, int D, int G, int W>
 hipError_t launch_mode(int mode, const AttendParams &p, hipStream_t stream) {
-    const dim3 grid(p.num_splits, p.num_kv_heads, p.batch), block(kThreads);
+    const dim3 grid(p.num_splits, p.num_kv_heads, p.batch), block(W * kWave);
     switch (mode) {
     case kDense:
-        hipLaunchKernelGGL((attend_split_kernel<DT, D, G, kDense>), grid, block, 0, stream, p);
+        hipLaunchKernelGGL((attend_split_kernel<DT, D, G, kDense, W>), grid, block, 0, stream, p);
         break;
     case kSelect:
-        hipLaunchKernelGGL((attend_split_kernel<DT, D, G, kSelect>), grid, block, 0, stream, p);
+        hipLaunchKernelGGL((attend_split_kernel<DT, D, G, kSelect, W>), grid, block, 0, stream, p);
         break;
     default:
-        hipLaunchKernelGGL((attend_split_kernel<DT, D, G, kSparse>), grid, block, 0, stream, p);
+        hipLaunchKernelGGL((attend_split_kernel<DT, D, G, kSparse, W>), grid, block, 0, stream, p);
         break;
     }
     return hipGetLastError();
 }
 
+// Eight-wave workgroups exist for groups of up to four query heads (beyond that the LDS for
+// the workgroup's states would exceed what two workgroups per CU can hold).
+template <int DT, int D, int G>
+hipError_t launch_waves(int waves, int mode, const AttendParams &p, hipStream_t stream) {
+    if constexpr (G <= 4) {
+        if (waves == 8) return launch_mode<DT, D, G, 8>(mode, p, stream);
+    }
+    return launch_mode<DT, D, G, 4>(mode, p, stream);
+}
+
 template <int DT, int D>
-hipError_t launch_group(int group, int mode, const AttendParams &p, hipStream_t stream) {
+hipError_t launch_group(int group, int waves, int mode, const AttendParams &p, hipStream_t stream) {
     switch (group) {
-    case 1: return launch_mode<DT, D, 1>(mode, p, stream);
-    case 2: return launch_mode<DT, D, 2>(mode, p, stream);
-    case 4: return launch_mode<DT, D, 4>(mode, p, stream);
-    case 8: return launch_mode<DT, D, 8>(mode, p, stream);
+    case 1: return launch_waves<DT, D, 1>(waves, mode, p, stream);
+    case 2: return launch_waves<DT, D, 2>(waves, mode, p, stream);
+    case 4: return launch_waves<DT, D, 4>(waves, mode, p, stream);
+    case 8: return launch_waves<DT, D, 8>(waves, mode, p, stream);
     default: return hipErrorInvalidValue;
     }
 }
 
 }  // namespace
 
-hipError_t launch_attend(int dtype, int head_dim, int group, int mode, const AttendParams &p,
+bool attend_supports_waves(int group, int waves) { return waves == 4 || (waves == 8 && group <= 4); }
+
+hipError_t launch_attend(int dtype, int head_dim, int group, int waves, int mode, const AttendParams &p,
                          hipStream_t stream) {
-    if (dtype == TD_BF16 && head_dim == 128) return launch_group<TD_BF16, 128>(group, mode, p, stream);
-    if (dtype == TD_BF16 && head_dim == 64) return launch_group<TD_BF16, 64>(group, mode, p, stream);
-    if (dtype == TD_F32 && head_dim == 128) return launch_group<TD_F32, 128>(group, mode, p, stream);
-    if (dtype == TD_F32 && head_dim == 64) return launch_group<TD_F32, 64>(group, mode, p, stream);
+    if (!attend_supports_waves(group, waves)) return hipErrorInvalidValue;
+    if (dtype == TD_BF16 && head_dim == 128) return launch_group<TD_BF16, 128>(group, waves, mode, p, stream);
+    if (dtype == TD_BF16 && head_dim == 64) return launch_group<TD_BF16, 64>(group, waves, mode, p, stream);
+    if (dtype == TD_F32 && head_dim == 128) return launch_group<TD_F32, 128>(group, waves, mode, p, stream);
+    if (dtype == TD_F32 && head_dim == 64) return launch_group<TD_F32, 64>(group, waves, mode, p, stream);
     return hipErrorInvalidValue;
 }
 

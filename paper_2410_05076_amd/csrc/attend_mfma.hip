@@ -201,7 +201,7 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_kernel(const AttendParam
     l_run += __shfl_xor(l_run, 16);
     l_run += __shfl_xor(l_run, 32);
     constexpr int RG = kWavesPerGroup;
-    __shared__ TailShared<kD, G, RG> sm;
+    __shared__ TailShared<kD, G, RG, kThreads> sm;
     if (kb == 0 && n16 < G) {
         sm.m[wave][n16] = m_run;
         sm.l[wave][n16] = l_run;
@@ -216,9 +216,9 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_kernel(const AttendParam
         }
     }
     __syncthreads();
-    fold_states<TD_BF16, kD, G, G, RG>(p, sm, b, g, split, ns, 0);
+    fold_states<TD_BF16, kD, G, G, RG, kThreads>(p, sm, b, g, split, ns, 0);
     if (ns == 1) return;
-    finish_chunks<TD_BF16, kD, G, G, RG>(p, sm, b, g, ns);
+    finish_chunks<TD_BF16, kD, G, G, RG, kThreads>(p, sm, b, g, ns);
 }
 
 template <int G>

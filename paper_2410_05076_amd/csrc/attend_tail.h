@@ -8,7 +8,7 @@
 namespace tidal {
 namespace {
 
-constexpr int kWavesPerGroup = 4;
+constexpr int kWavesPerGroup = 4;  // default workgroup: four wave64s
 constexpr int kThreads = kWavesPerGroup * kWave;
 constexpr float kEmptyMax = -3.0e38f;
 
@@ -45,32 +45,29 @@ __device__ __forceinline__ void publish(float *p, float v) {
 __device__ __forceinline__ uint64_t coherent_load(const uint64_t *p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-// The same device-scope (sc1) load, 16 and 8 bytes wide.  The compiler has no atomic load of
-// that width, so these are written as instructions; they only issue the load, and
-// wait_coherent_loads() - which names every destination as an operand, so nothing that uses
-// them can move above it - waits for all of them.
-typedef float f32x4_t __attribute__((ext_vector_type(4)));
-typedef float f32x2_t __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ void coherent_load16(f32x4_t &dst, const void *p) {
-    asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(dst) : "v"(p) : "memory");
+// Device-scope 16- and 8-byte loads for the final merge, as buffer loads: the compiler has
+// no atomic load of 16 bytes, and a buffer load takes the scope as a cache-policy operand
+// (bit 4 = sc1 on gfx94x/gfx950) while staying an ordinary tracked load.  The resource
+// covers exactly the partials of one (sequence, KV head); its base is wave-uniform.
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+constexpr int kCachePolicySc1 = 16;
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t partial_resource(const float *base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(base), 0, bytes, 0x00020000);
 }
-__device__ __forceinline__ void coherent_load8(f32x2_t &dst, const void *p) {
-    asm volatile("global_load_dwordx2 %0, %1, off sc1" : "=v"(dst) : "v"(p) : "memory");
+__device__ __forceinline__ u32x4_t coherent_load16(__amdgpu_buffer_rsrc_t r, uint32_t byte_offset) {
+    return __builtin_amdgcn_raw_buffer_load_b128(r, byte_offset, 0, kCachePolicySc1);
 }
-__device__ __forceinline__ void wait_coherent_loads(f32x4_t (&x)[8], f32x2_t (&v)[8]) {
-    asm volatile("s_waitcnt vmcnt(0)"
-                 : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7]),
-                   "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]), "+v"(v[4]), "+v"(v[5]), "+v"(v[6]), "+v"(v[7])
-                 :
-                 : "memory");
+__device__ __forceinline__ u32x2_t coherent_load8(__amdgpu_buffer_rsrc_t r, uint32_t byte_offset) {
+    return __builtin_amdgcn_raw_buffer_load_b64(r, byte_offset, 0, kCachePolicySc1);
 }
 
-// LDS needed by fold_states / finish_chunks for RG states of GC heads each.
-template <int D, int GC, int RG>
+// LDS needed by fold_states / finish_chunks for RG states of GC heads each, in a workgroup
+// of T threads.
+template <int D, int GC, int RG, int T>
 struct TailShared {
     float m[RG][GC], l[RG][GC];
-    // state accumulators [RG][GC][D]; reused by the final merge as [kThreads] float4 + float2
-    static constexpr int kAccFloats = RG * GC * D > kThreads * 6 ? RG * GC * D : kThreads * 6;
+    // state accumulators [RG][GC][D]; reused by the final merge as [T] float4 + float2
+    static constexpr int kAccFloats = RG * GC * D > T * 6 ? RG * GC * D : T * 6;
     __align__(16) float acc[kAccFloats];
     int last;
 };
@@ -78,10 +75,10 @@ struct TailShared {
 // Folds the RG online-softmax states of heads h0 .. h0+GC-1 (already in sm.m, sm.l, sm.acc;
 // the caller has synchronised after writing them) with the rescaling rule.  With a single
 // chunk the output row is written at once, otherwise the chunk's partial is published.
-template <int DT, int D, int G, int GC, int RG>
-__device__ __forceinline__ void fold_states(const AttendParams &p, TailShared<D, GC, RG> &sm, int b, int g,
+template <int DT, int D, int G, int GC, int RG, int T>
+__device__ __forceinline__ void fold_states(const AttendParams &p, TailShared<D, GC, RG, T> &sm, int b, int g,
                                             int split, int ns, int h0) {
-    for (int idx = threadIdx.x; idx < GC * D; idx += kThreads) {
+    for (int idx = threadIdx.x; idx < GC * D; idx += T) {
         const int i = idx / D, ch = idx % D;
         float mx = sm.m[0][i];
 #pragma unroll
@@ -113,8 +110,8 @@ __device__ __forceinline__ void fold_states(const AttendParams &p, TailShared<D,
 // so they are in memory before this workgroup's ticket is taken.  (A release fence in every
 // workgroup would write back the whole L2 each time.)  The counter returns to zero for the
 // next launch.
-template <int DT, int D, int G, int GC, int RG>
-__device__ __forceinline__ void finish_chunks(const AttendParams &p, TailShared<D, GC, RG> &sm, int b, int g,
+template <int DT, int D, int G, int GC, int RG, int T>
+__device__ __forceinline__ void finish_chunks(const AttendParams &p, TailShared<D, GC, RG, T> &sm, int b, int g,
                                               int ns) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
@@ -131,45 +128,51 @@ __device__ __forceinline__ void finish_chunks(const AttendParams &p, TailShared<
     // column of one head with the online rescaling rule, eight chunks in flight at a time,
     // then the NG threads of a column are folded through LDS.  The partials are read with
     // device-scope loads (they come from other workgroups' write-through stores), which
-    // needs no cache invalidate.
-    constexpr int COLS = G * D / 4;      // float4 columns over all heads of the group
-    constexpr int NG = kThreads / COLS;  // chunk groups working in parallel
-    static_assert(NG >= 1 && NG * COLS == kThreads, "G * D / 4 must divide the workgroup size");
+    // needs no cache invalidate.  (A single CU sustains only about 30 GB/s on these loads
+    // however many are in flight, so this phase costs about 1 us per 32 KiB of partials.)
+    constexpr int COLS = G * D / 4;  // float4 columns over all heads of the group
+    constexpr int NG = T / COLS;     // chunk groups working in parallel
+    static_assert(NG >= 1 && NG * COLS == T, "G * D / 4 must divide the workgroup size");
     const int col = threadIdx.x % COLS, sg = threadIdx.x / COLS;
     const int hi = col / (D / 4), c4 = col % (D / 4);
-    const int64_t head = (int64_t)b * p.num_q_heads + g * G + hi;
-    const char *ml = reinterpret_cast<const char *>(p.part_ml + head * p.num_splits * 2);
-    const char *pa = reinterpret_cast<const char *>(p.part_acc + (head * p.num_splits * (D / 4) + c4) * 4);
+    const int64_t head0 = (int64_t)b * p.num_q_heads + g * G;
+    const int64_t head = head0 + hi;
+    const __amdgpu_buffer_rsrc_t pa =  // the group's partials, [G][num_splits][D]
+        partial_resource(p.part_acc + head0 * p.num_splits * D, (uint32_t)(G * p.num_splits * D) * 4);
+    const __amdgpu_buffer_rsrc_t pml =  // and their (max, sum) pairs, [G][num_splits][2]
+        partial_resource(p.part_ml + head0 * p.num_splits * 2, (uint32_t)(G * p.num_splits) * 8);
+    const uint32_t pa_off = ((uint32_t)(hi * p.num_splits) * D + c4 * 4) * 4;
+    const uint32_t pml_off = (uint32_t)(hi * p.num_splits) * 8;
     float mm = kEmptyMax, ll = 0.f;
     float4 aa = make_float4(0.f, 0.f, 0.f, 0.f);
     constexpr int kBatch = 8;  // partials in flight per thread
     for (int s0 = sg; s0 < ns; s0 += NG * kBatch) {
-        f32x4_t x[kBatch];
-        f32x2_t v[kBatch];
+        u32x4_t x[kBatch];
+        u32x2_t v[kBatch];
 #pragma unroll
         for (int j = 0; j < kBatch; ++j) {
-            const int s = min(s0 + j * NG, ns - 1);  // clamped repeats are ignored below
-            coherent_load16(x[j], pa + (int64_t)s * (D * 4));
-            coherent_load8(v[j], ml + (int64_t)s * 8);
+            const uint32_t s = min(s0 + j * NG, ns - 1);  // clamped repeats are ignored below
+            x[j] = coherent_load16(pa, pa_off + s * (D * 4));
+            v[j] = coherent_load8(pml, pml_off + s * 8);
         }
-        wait_coherent_loads(x, v);
 #pragma unroll
         for (int j = 0; j < kBatch; ++j) {
             if (s0 + j * NG < ns) {
-                const float mn = fmaxf(mm, v[j].x);
-                const float wa = fast_exp2(mm - mn), wb = fast_exp2(v[j].x - mn);
-                ll = ll * wa + v[j].y * wb;
-                aa.x = aa.x * wa + x[j].x * wb;
-                aa.y = aa.y * wa + x[j].y * wb;
-                aa.z = aa.z * wa + x[j].z * wb;
-                aa.w = aa.w * wa + x[j].w * wb;
+                const float mj = __uint_as_float(v[j].x);
+                const float mn = fmaxf(mm, mj);
+                const float wa = fast_exp2(mm - mn), wb = fast_exp2(mj - mn);
+                ll = ll * wa + __uint_as_float(v[j].y) * wb;
+                aa.x = aa.x * wa + __uint_as_float(x[j].x) * wb;
+                aa.y = aa.y * wa + __uint_as_float(x[j].y) * wb;
+                aa.z = aa.z * wa + __uint_as_float(x[j].z) * wb;
+                aa.w = aa.w * wa + __uint_as_float(x[j].w) * wb;
                 mm = mn;
             }
         }
     }
     if constexpr (NG > 1) {
-        float4 *red_a = reinterpret_cast<float4 *>(sm.acc);             // [kThreads], sm.acc is free now
-        float2 *red_ml = reinterpret_cast<float2 *>(red_a + kThreads);  // [kThreads]
+        float4 *red_a = reinterpret_cast<float4 *>(sm.acc);      // [T], sm.acc is free now
+        float2 *red_ml = reinterpret_cast<float2 *>(red_a + T);  // [T]
         red_a[threadIdx.x] = aa;
         red_ml[threadIdx.x] = make_float2(mm, ll);
         __syncthreads();

@@ -52,9 +52,11 @@ struct AttendParams {
 };
 
 // Enqueues the split attention kernel (the last chunk to finish merges the partials).
-// launch_attend: vector-ALU kernel for every supported dtype / head_dim;
+// launch_attend: vector-ALU kernel for every supported dtype / head_dim, with `waves` wave64s
+// per workgroup (4, or 8 where attend_supports_waves says so);
 // launch_attend_mfma: matrix-core kernel, bf16 with head_dim 128 only.
-hipError_t launch_attend(int dtype, int head_dim, int group, int mode, const AttendParams &p,
+bool attend_supports_waves(int group, int waves);
+hipError_t launch_attend(int dtype, int head_dim, int group, int waves, int mode, const AttendParams &p,
                          hipStream_t stream);
 hipError_t launch_attend_mfma(int group, int mode, const AttendParams &p, hipStream_t stream);
 

@@ -10,7 +10,8 @@ import os
 import torch
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libtidal.so")
+# TIDAL_LIBRARY names another build of the same library (A/B timing of two builds in one run)
+LIB_PATH = os.environ.get("TIDAL_LIBRARY") or os.path.join(HERE, "libtidal.so")
 
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = range(5)
 BF16, F32 = 0, 1

@@ -142,6 +142,22 @@ def test_matrix_core_kernel_variant(name, over):
     run_layer_checks(w, (D, S, P), "mfma %s%s" % (name, sorted(over.items())), kernel_variant=1)
 
 
+@pytest.mark.parametrize("variant", [2, 3])
+@pytest.mark.parametrize("name,over", [
+    ("c2", dict(context=4099, k=300)),                                    # G = 4
+    ("c3", dict(context=8229, k=512, tau=512.0)),                         # G = 1
+    ("c4", dict(seq_lens=(777, 64, 1, 2500, 1300), k=256)),               # ragged, k > N for some
+    ("c2", dict(context=3000, k=200, num_q_heads=64)),                    # G = 8: four waves either way
+    ("c1", dict(context=1500, k=128)),                                    # fp32 d64
+    ("c2", dict(context=900, k=100, head_dim=64, num_q_heads=16)),        # bf16 d64, G = 2
+])
+def test_workgroup_size_variants(name, over, variant):
+    # the library picks four or eight waves per workgroup by itself; here each is forced for
+    # every layer kind (2: four waves, 3: eight waves), same bar
+    w = W.workload(name, **over)
+    run_layer_checks(w, (D, S, P), "waves v%d %s%s" % (variant, name, sorted(over.items())), kernel_variant=variant)
+
+
 def test_sparse_with_k_equal_n_matches_full_attention():
     w = W.workload("c2", context=2048, k=2048)
     (q, K, V), = device_layers(w, [3])
