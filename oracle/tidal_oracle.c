@@ -17,6 +17,8 @@
  *   sparse : Eq. 1 restricted to the persisted positions rho
  *            (Alg. 1, "SparseAttention(q, C[rho])")
  *   step   : Alg. 1's layer loop, attention part only
+ *   paged  : the same results for a cache stored in pages behind a block
+ *            table (tdo_gather_pages states the mapping)
  *
  * Readings where the paper is silent (kept identical in the HIP path):
  *   - grouped-query attention: the G query heads that share a KV head select
@@ -278,6 +280,45 @@ int tdo_step(const tdo_shape *s, int32_t num_layers, const int32_t *schedule,
             return TDO_BAD_ARG;
         }
         if (e) return e;
+    }
+    return TDO_OK;
+}
+
+/*
+ * Paged KV cache.  Serving systems keep the cache C of Alg. 1 in fixed-size
+ * pages handed out by an allocator (the paper's full-attention baseline and
+ * the page-level method it compares with both work on such a cache; Sec. 2
+ * and Sec. 4.3).  Paging changes where a token is stored, not what is
+ * computed: logical token j of sequence b lives in page
+ * block_table[b][j / page_size] at slot j % page_size.  This function writes
+ * out the logical cache, [B][Hkv][max_seq_len][d] contiguous, so that the
+ * functions above define every paged result.  Element (page, head, slot, c)
+ * of the pool is at page*stride_page + head*stride_head + slot*stride_slot + c
+ * (elements of elem_bytes bytes).  Rows j >= seq_lens[b] of `logical` are
+ * left as they are.  A page id outside [0, num_pages) is an error.
+ */
+int tdo_gather_pages(int32_t batch, int32_t num_kv_heads, int32_t head_dim, int32_t elem_bytes,
+                     const int32_t *seq_lens, int32_t max_seq_len, int32_t page_size,
+                     int32_t num_pages, const int32_t *block_table, int64_t block_table_stride,
+                     int64_t stride_page, int64_t stride_head, int64_t stride_slot,
+                     const void *pool, void *logical) {
+    if (batch < 1 || num_kv_heads < 1 || head_dim < 1 || (elem_bytes != 2 && elem_bytes != 4) ||
+        !seq_lens || max_seq_len < 1 || page_size < 1 || num_pages < 1 || !block_table || !pool ||
+        !logical)
+        return TDO_BAD_ARG;
+    const size_t row = (size_t)head_dim * (size_t)elem_bytes;
+    for (int b = 0; b < batch; ++b) {
+        if (seq_lens[b] < 0 || seq_lens[b] > max_seq_len) return TDO_BAD_ARG;
+        for (int j = 0; j < seq_lens[b]; ++j) {
+            const int32_t page = block_table[b * block_table_stride + j / page_size];
+            const int slot = j % page_size;
+            if (page < 0 || page >= num_pages) return TDO_BAD_ARG;
+            for (int g = 0; g < num_kv_heads; ++g) {
+                const int64_t src = page * stride_page + g * stride_head + slot * stride_slot;
+                const int64_t dst = (((int64_t)b * num_kv_heads + g) * max_seq_len + j) * head_dim;
+                memcpy((char *)logical + dst * elem_bytes, (const char *)pool + src * elem_bytes, row);
+            }
+        }
     }
     return TDO_OK;
 }

@@ -44,7 +44,7 @@ def lib():
         if not os.path.exists(path):
             _build.build()
         _lib = ctypes.CDLL(path)
-        for name in ("tdo_full", "tdo_select", "tdo_sparse", "tdo_step", "tdo_topk_row"):
+        for name in ("tdo_full", "tdo_select", "tdo_sparse", "tdo_step", "tdo_topk_row", "tdo_gather_pages"):
             getattr(_lib, name).restype = ctypes.c_int
         _lib.tdo_num_threads.restype = ctypes.c_int
     return _lib
@@ -135,3 +135,26 @@ def step(schedule, qs, Ks, Vs, seq_lens, k, sm_scale=0.0):
                           arr(*[t.data_ptr() for t in Vs]), ctypes.c_int32(k),
                           arr(*[t.data_ptr() for t in outs]), _ptr(pos)))
     return outs, pos
+
+
+def gather_pages(pool, block_table, seq_lens, max_seq_len, fill=float("nan")):
+    """Logical cache [B][Hkv][max_seq_len][d] of a paged cache.
+
+    pool is indexed [page][KV head][slot][c] (any strides with c contiguous, so a
+    token-major pool is passed as a permuted view); block_table int32 [B][>= pages per
+    sequence].  Token j of sequence b is pool[block_table[b][j // page_size], :, j % page_size].
+    Rows j >= seq_lens[b] are set to `fill`."""
+    assert pool.device.type == "cpu" and pool.dim() == 4 and pool.stride(3) == 1
+    assert pool.dtype in (torch.bfloat16, torch.float32)
+    bt = block_table.to(torch.int32).contiguous()
+    lens = np.ascontiguousarray(np.asarray(seq_lens, dtype=np.int32))
+    B = lens.shape[0]
+    assert bt.dim() == 2 and bt.shape[0] == B
+    num_pages, Hkv, page_size, d = pool.shape
+    logical = torch.full((B, Hkv, max_seq_len, d), fill, dtype=pool.dtype)
+    _check(lib().tdo_gather_pages(
+        ctypes.c_int32(B), ctypes.c_int32(Hkv), ctypes.c_int32(d), ctypes.c_int32(pool.element_size()),
+        ctypes.c_void_p(lens.ctypes.data), ctypes.c_int32(max_seq_len), ctypes.c_int32(page_size),
+        ctypes.c_int32(num_pages), _ptr(bt), ctypes.c_int64(bt.stride(0)), ctypes.c_int64(pool.stride(0)),
+        ctypes.c_int64(pool.stride(1)), ctypes.c_int64(pool.stride(2)), _ptr(pool), _ptr(logical)))
+    return logical

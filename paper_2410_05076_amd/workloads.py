@@ -220,3 +220,47 @@ def make_layer(w, layer, device="cpu", heavy=None, ranks=None):
             K[b, :, w.seq_lens[b]:] = float("nan")
             V[b, :, w.seq_lens[b]:] = float("nan")
     return q, K, V
+
+
+def page_table(w, page_size, seed=0, spare=0.125, device="cpu"):
+    """Block table of a paged cache for workload w: int32 [B][max_pages] and the pool size.
+
+    Every sequence gets ceil(N_b / page_size) pages drawn without order from a pool that is
+    `spare` larger than needed (an allocator under churn hands out scattered pages);
+    unused table entries are -1."""
+    gen = torch.Generator().manual_seed(w.seed + 77 * w.index + 13 * page_size + seed)
+    need = [(n + page_size - 1) // page_size for n in w.seq_lens]
+    max_pages = (w.max_seq_len + page_size - 1) // page_size
+    num_pages = int(sum(need) * (1.0 + spare)) + 1
+    perm = torch.randperm(num_pages, generator=gen)
+    table = torch.full((w.batch, max_pages), -1, dtype=torch.int32)
+    at = 0
+    for b, n in enumerate(need):
+        table[b, :n] = perm[at:at + n].to(torch.int32)
+        at += n
+    return table.to(device), num_pages
+
+
+def paginate(x, table, num_pages, page_size, layout="HND"):
+    """Scatters a logical cache x [B][Hkv][N_max][d] into a page pool by `table`.
+
+    Returns (pool, view): pool is the storage, [page][Hkv][slot][d] for layout "HND" or
+    [page][slot][Hkv][d] for "NHD"; view is the same memory indexed [page][Hkv][slot][d].
+    Pages that no sequence owns and slots never written stay NaN."""
+    B, Hkv, N, d = x.shape
+    max_pages = table.shape[1]
+    pad = max_pages * page_size - N
+    if pad:
+        x = torch.cat([x, torch.full((B, Hkv, pad, d), float("nan"), dtype=x.dtype, device=x.device)], 2)
+    pages = x.view(B, Hkv, max_pages, page_size, d).permute(0, 2, 1, 3, 4)   # [B][page][Hkv][slot][d]
+    if layout == "HND":
+        pool = torch.full((num_pages, Hkv, page_size, d), float("nan"), dtype=x.dtype, device=x.device)
+        view = pool
+    elif layout == "NHD":
+        pool = torch.full((num_pages, page_size, Hkv, d), float("nan"), dtype=x.dtype, device=x.device)
+        view = pool.permute(0, 2, 1, 3)
+    else:
+        raise ValueError(layout)
+    owned = table >= 0
+    view[table[owned].long()] = pages[owned]
+    return pool, view

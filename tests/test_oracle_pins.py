@@ -293,3 +293,70 @@ def test_paper_constants():
     assert [s64.count(W.DENSE), s64.count(W.SELECT), s64.count(W.SPARSE)] == c["layers_64"]["dense_select_sparse"]
     w = W.workload("c3")       # Llama-2-7B shape at 128K tokens: the footnote's 64 GB KV cache
     assert w.num_layers * w.kv_bytes_per_layer() == c["kv_cache_bytes_llama2_7b_128k"] == 64 * 2**30
+
+
+# ---- paged cache: the mapping (block table, slot) -> logical token, pinned independently
+
+
+def _toy_pool(num_pages, Hkv, P, d, dtype, seed):
+    g = torch.Generator().manual_seed(seed)
+    return torch.randn((num_pages, Hkv, P, d), generator=g).to(dtype)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("P", [1, 4, 16])
+def test_gather_pages_matches_direct_indexing(dtype, P):
+    # the definition written out with plain indexing, no shared code
+    Hkv, d, lens = 3, 8, [37, 5, 16]
+    N = max(lens)
+    pool = _toy_pool(40, Hkv, P, d, dtype, 3)
+    g = torch.Generator().manual_seed(4)
+    table = torch.stack([torch.randperm(40, generator=g)[: (N + P - 1) // P] for _ in lens]).to(torch.int32)
+    got = O.gather_pages(pool, table, lens, N, fill=0.0)
+    for b, n in enumerate(lens):
+        for j in range(N):
+            want = pool[table[b, j // P], :, j % P] if j < n else torch.zeros(Hkv, d, dtype=dtype)
+            assert torch.equal(got[b, :, j], want), (b, j)
+
+
+def test_gather_pages_inverts_the_workload_pagination():
+    # the generator's scatter and the oracle's gather are written separately; both layouts
+    w = W.workload("c4", seq_lens=(50, 7, 33), k=8)
+    q, K, V = W.make_layer(w, 0)
+    for P, layout in ((4, "HND"), (16, "NHD"), (1, "HND")):
+        table, num_pages = W.page_table(w, P)
+        pool, view = W.paginate(K, table, num_pages, P, layout)
+        back = O.gather_pages(view, table, w.seq_lens, w.max_seq_len)
+        for b, n in enumerate(w.seq_lens):
+            assert torch.equal(back[b, :, :n].view(torch.int16), K[b, :, :n].view(torch.int16)), (P, layout, b)
+            assert torch.isnan(back[b, :, n:].float()).all()
+
+
+def test_gather_pages_identity_table_is_a_reshape():
+    P, Hkv, d, N = 8, 2, 4, 32
+    pool = _toy_pool(N // P, Hkv, P, d, torch.float32, 9)
+    table = torch.arange(N // P, dtype=torch.int32)[None]
+    got = O.gather_pages(pool, table, [N], N)
+    assert torch.equal(got[0], pool.permute(1, 0, 2, 3).reshape(Hkv, N, d))
+
+
+def test_gather_pages_rejects_a_page_outside_the_pool():
+    pool = _toy_pool(4, 1, 4, 4, torch.float32, 1)
+    with pytest.raises(RuntimeError):
+        O.gather_pages(pool, torch.tensor([[0, 4]], dtype=torch.int32), [8], 8)
+    with pytest.raises(RuntimeError):
+        O.gather_pages(pool, torch.tensor([[0, -1]], dtype=torch.int32), [8], 8)
+
+
+def test_paged_full_attention_equals_contiguous_for_any_page_permutation():
+    # paging only moves rows: attention over the gathered cache is bit-identical to the original
+    w = W.workload("c1", context=200, k=16)
+    q, K, V = W.make_layer(w, 1)
+    want = O.full(q, K, V, w.seq_lens)
+    for seed in (0, 1):
+        table, num_pages = W.page_table(w, 16, seed=seed)
+        Kp, Kv = W.paginate(K, table, num_pages, 16)
+        Vp, Vv = W.paginate(V, table, num_pages, 16)
+        got = O.full(q, O.gather_pages(Kv, table, w.seq_lens, w.max_seq_len, fill=0.0),
+                          O.gather_pages(Vv, table, w.seq_lens, w.max_seq_len, fill=0.0), w.seq_lens)
+        assert torch.equal(got, want)
