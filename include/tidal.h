@@ -29,6 +29,18 @@
  *              Token j of sequence b is valid for 0 <= j < seq_lens[b]; the
  *              cache already holds the current token (Alg. 1 appends first).
  *     Pointers must be 16-byte aligned.
+ *   - Paged cache (shape.page_size > 0; serving systems hand the cache out in
+ *     pages, as the paged full-attention baseline and the page-level method
+ *     of the paper's Sec. 4 do): K and V point to page pools shared by all
+ *     sequences; element (page p, KV head g, slot s, c) lives at
+ *     p*kv_stride_batch + g*kv_stride_head + s*kv_stride_tok + c, and token j
+ *     of sequence b is in page block_table[b*block_table_stride + j/page_size]
+ *     at slot j % page_size.  Scores, positions and seq_lens stay in logical
+ *     token indices, so every call means the same as on the contiguous cache
+ *     holding the same tokens.  Only entries of pages that hold a token
+ *     j < seq_lens[b] are read; an id outside [0, num_pages) is clamped into
+ *     the pool (no access outside it; the result for that sequence is then
+ *     unspecified).  The layers of td_decode_step share one block table.
  *   - Query head h reads KV head h / (num_q_heads / num_kv_heads).
  *   - positions : int32 [batch][num_kv_heads][k], ascending token indices; if
  *     k > seq_lens[b] only the first seq_lens[b] entries are tokens and the
@@ -87,6 +99,11 @@ typedef struct td_shape {
     int64_t total_seq_len;     /* HOST hint: sum of seq_lens, or 0 if unknown.  Only steers the
                                   launch plan (a ragged batch gets smaller chunks); results do
                                   not depend on it */
+    /* Paged cache (page_size == 0: the contiguous cache described above, the rest unused). */
+    int32_t page_size;         /* tokens per page, a power of two */
+    int32_t num_pages;         /* pages in the pools that K and V point to */
+    const int32_t *block_table; /* DEVICE int32 [batch][block_table_stride] page ids */
+    int64_t block_table_stride; /* entries per sequence, >= ceil(max_seq_len / page_size) */
 } td_shape;
 
 typedef struct td_ctx td_ctx;  /* opaque; owns the workspace (split partials, group scores) */
@@ -148,7 +165,7 @@ td_status td_decode_step(td_ctx *ctx, const td_shape *shape, int32_t num_layers,
  * full and for sparse attention, the largest number of chunks per
  * (sequence, KV head), and the attention kernel (0: the vector-ALU kernel, the
  * faster one on MI355X, with the workgroup size chosen per launch; 1: the
- * matrix-core kernel where it applies - bf16, head_dim 128; 2 / 3: the
+ * matrix-core kernel where it applies - bf16, head_dim 128, contiguous cache; 2 / 3: the
  * vector-ALU kernel with four / eight waves per workgroup in every launch,
  * eight only for groups of up to four query heads).  The workspace size does
  * not depend on them. */

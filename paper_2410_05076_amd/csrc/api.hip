@@ -37,6 +37,13 @@ td_status fail(td_ctx *ctx, td_status s, const char *fmt, const char *detail = "
     return s;
 }
 
+// Longest chunk of a paged full / selection launch: its pages' table entries fit the LDS stage
+// (a chunk may start inside a page), rounded down to the chunk granule.
+int64_t paged_chunk_limit(int32_t page_size) {
+    const int64_t tokens = (int64_t)(kPageStageMax - 1) * page_size;
+    return std::max<int64_t>(kChunkGranule, tokens / kChunkGranule * kChunkGranule);
+}
+
 // Why a shape or budget is unusable, or nullptr.  Host only.
 const char *shape_problem(const td_shape *s, int32_t k, td_status *code) {
     *code = TD_ERR_INVALID_ARG;
@@ -54,12 +61,23 @@ const char *shape_problem(const td_shape *s, int32_t k, td_status *code) {
         return "KV strides must be multiples of 8 elements";
     if (k > kSparseChunkMax * kSplitsMax) return "k is larger than 524288";
     if (s->total_seq_len < 0) return "total_seq_len is negative";
+    if (s->page_size < 0 || (s->page_size & (s->page_size - 1))) return "page_size is not a power of two";
+    if (s->page_size > 0) {
+        if (!s->block_table) return "block_table is NULL";
+        if (s->num_pages < 1) return "num_pages < 1";
+        if (s->block_table_stride < ((int64_t)s->max_seq_len + s->page_size - 1) / s->page_size)
+            return "block_table_stride is smaller than the pages of max_seq_len tokens";
+        if (s->kv_stride_batch < 1) return "page stride < 1";
+    }
     *code = TD_ERR_UNSUPPORTED;
     if (s->head_dim != 64 && s->head_dim != 128) return "head_dim must be 64 or 128";
     const int g = s->num_q_heads / s->num_kv_heads;
     if (g != 1 && g != 2 && g != 4 && g != 8) return "group size must be 1, 2, 4 or 8";
     if (s->batch > 65535 || s->num_kv_heads > 65535 || (int64_t)s->batch * s->num_kv_heads > 65535)
         return "batch * num_kv_heads above 65535";
+    // a paged chunk stages its block-table entries in LDS; kSplitsMax chunks must cover the context
+    if (s->page_size > 0 && (int64_t)s->max_seq_len > (int64_t)kSplitsMax * paged_chunk_limit(s->page_size))
+        return "max_seq_len is too long for this page size";
     *code = TD_OK;
     return nullptr;
 }
@@ -117,6 +135,7 @@ void plan_chunks(const td_ctx *ctx, const td_shape *s, bool sparse, int32_t wave
     c = std::max(c, ceil_div(tokens, cap));
     c = (int32_t)align_up((size_t)c, kChunkGranule);
     if (sparse) c = std::min(c, kSparseChunkMax);
+    if (!sparse && s->page_size > 0) c = (int32_t)std::min<int64_t>(c, paged_chunk_limit(s->page_size));
     *chunk = c;
     *splits = ceil_div(tokens, c);
 }
@@ -137,6 +156,12 @@ td_status attend(td_ctx *ctx, const td_shape *s, int mode, const void *q, const 
     p.counters = reinterpret_cast<int32_t *>(ctx->workspace + w.counters);
     p.topk_scratch = ctx->workspace + w.topk;
     p.stride_batch = s->kv_stride_batch;
+    if (s->page_size > 0) {
+        p.block_table = s->block_table;
+        p.bt_stride = s->block_table_stride;
+        p.num_pages = s->num_pages;
+        while ((1 << p.page_shift) < s->page_size) ++p.page_shift;
+    }
     p.stride_head = s->kv_stride_head;
     p.stride_tok = s->kv_stride_tok;
     p.batch = s->batch;
@@ -146,7 +171,7 @@ td_status attend(td_ctx *ctx, const td_shape *s, int mode, const void *q, const 
     p.k = k;
     p.scale = s->sm_scale > 0.f ? s->sm_scale : 1.0f / sqrtf((float)s->head_dim);
     const int group = s->num_q_heads / s->num_kv_heads;
-    const bool mfma = s->dtype == TD_BF16 && s->head_dim == 128 && ctx->kernel_variant == 1;
+    const bool mfma = s->dtype == TD_BF16 && s->head_dim == 128 && ctx->kernel_variant == 1 && s->page_size == 0;
     // Workgroup size of the vector-ALU kernel.  Full and selection layers use eight waves (half
     // as many partials to merge across workgroups; measured 3 to 9 % faster per launch on the
     // uniform workloads) unless the batch is ragged, where many small chunks balance better;

@@ -75,7 +75,14 @@ struct Elems<TD_F32> {
 // as long, so a (sequence, KV head) has half as many partials to merge across workgroups -
 // the merge inside a workgroup goes through LDS and is much cheaper - which pays when the
 // launch is short enough for its tail to matter.
-template <int DT, int D, int G, int MODE, int W>
+//
+// PAGED: the cache is a pool of pages behind a block table.  Logical token j of sequence b is
+// in page block_table[b][j >> page_shift] at slot j & (page_size - 1); p.stride_batch is then
+// the stride between pages.  Everything else (chunks, scores, positions) stays in logical
+// token indices.  Full and selection layers stage the chunk's slice of the block table in
+// LDS; sparse layers look the page of every position up while they stage the positions.
+// Page ids are clamped into the pool, so a wrong table cannot cause an access outside it.
+template <int DT, int D, int G, int MODE, int W, bool PAGED>
 __global__ __launch_bounds__(W *kWave) __attribute__((amdgpu_waves_per_eu(G <= 4 && MODE != kSparse ? 4 : 1)))
 void attend_split_kernel(const AttendParams p) {
     constexpr int T = W * kWave;  // threads per workgroup
@@ -122,6 +129,21 @@ void attend_split_kernel(const AttendParams p) {
             pstage[i] = i * T < len ? pos[t0 + min(j, len - 1)] : -1;  // the condition is workgroup-uniform
         }
     }
+    // paged full / selection layers: the block-table entries of the chunk's pages (the chunk is
+    // bounded by max_seq_len here, by the sequence length below)
+    constexpr bool kStageTable = PAGED && MODE != kSparse;
+    constexpr int kTablePerThread = kStageTable ? kPageStageMax / T : 1;
+    int tstage[kTablePerThread];
+    const int first_page = PAGED ? t0 >> p.page_shift : 0;
+    if constexpr (kStageTable) {
+        const int32_t *table = p.block_table + (int64_t)b * p.bt_stride + first_page;
+        const int pages = ((min(p.max_seq_len, t0 + p.chunk) - 1) >> p.page_shift) - first_page + 1;
+#pragma unroll
+        for (int i = 0; i < kTablePerThread; ++i) {
+            const int j = i * T + threadIdx.x;
+            tstage[i] = i * T < pages ? table[min(j, pages - 1)] : 0;  // workgroup-uniform condition
+        }
+    }
     asm volatile("" ::: "memory");  // the loads above stay above the branch on the sequence length
 
     const int N = min(max(p.seq_lens[b], 0), p.max_seq_len);
@@ -131,11 +153,26 @@ void attend_split_kernel(const AttendParams p) {
     const int ns = (n_tok + p.chunk - 1) / p.chunk;  // workgroups of this (sequence, KV head) with work
 
     __shared__ int s_pos[MODE == kSparse ? kSparseChunkMax : 1];
+    __shared__ int s_page[PAGED ? (MODE == kSparse ? kSparseChunkMax : kPageStageMax) : 1];
     if constexpr (MODE == kSparse) {
 #pragma unroll
         for (int i = 0; i < kPosPerThread; ++i) {
             const int j = i * T + threadIdx.x;
-            if (j < t1 - t0) s_pos[j] = pstage[i];
+            if (j < t1 - t0) {
+                s_pos[j] = pstage[i];
+                if constexpr (PAGED) {  // the page of the row that the gather will read (row 0 if masked)
+                    const int pj = pstage[i] >= 0 && pstage[i] < N ? pstage[i] : 0;
+                    s_page[j] = p.block_table[(int64_t)b * p.bt_stride + (pj >> p.page_shift)];
+                }
+            }
+        }
+        __syncthreads();
+    } else if constexpr (PAGED) {
+        const int pages = ((t1 - 1) >> p.page_shift) - first_page + 1;
+#pragma unroll
+        for (int i = 0; i < kTablePerThread; ++i) {
+            const int j = i * T + threadIdx.x;
+            if (j < pages) s_page[j] = tstage[i];
         }
         __syncthreads();
     }
@@ -144,7 +181,10 @@ void attend_split_kernel(const AttendParams p) {
     for (int i = 0; i < G; ++i) E::unpack(qraw[i], qf[i]);
 
     const int64_t row_bytes = p.stride_tok * E::kBytes;
-    const int64_t head_off = ((int64_t)b * p.stride_batch + (int64_t)g * p.stride_head) * E::kBytes + c * 16;
+    const int64_t head_off =
+        ((PAGED ? 0 : (int64_t)b * p.stride_batch) + (int64_t)g * p.stride_head) * E::kBytes + c * 16;
+    const int64_t page_bytes = p.stride_batch * E::kBytes;  // paged only
+    const int slot_mask = PAGED ? (1 << p.page_shift) - 1 : 0;
     const char *Kb = (const char *)p.K + head_off;
     const char *Vb = (const char *)p.V + head_off;
 
@@ -166,16 +206,24 @@ void attend_split_kernel(const AttendParams p) {
         for (int u = 0; u < kUnroll; ++u) {
             const int t = base + u * TPW + r;
             bool ok = t < t1;
-            int row;
+            int row, page = 0;
             if constexpr (MODE == kSparse) {
-                const int pj = ok ? s_pos[t - t0] : -1;
-                ok = pj >= 0 && pj < N;
-                row = ok ? pj : 0;
+                // lanes beyond the chunk read what the chunk's first entry reads, masked
+                const int idx = ok ? t - t0 : 0;
+                const int pj = s_pos[idx];
+                if constexpr (PAGED) page = s_page[idx];  // of row pj, or of row 0 if pj is not a token
+                const bool token = pj >= 0 && pj < N;
+                ok = ok && token;
+                row = token ? pj : 0;
             } else {
                 row = ok ? t : t1 - 1;
+                if constexpr (PAGED) page = s_page[(row >> p.page_shift) - first_page];
             }
             valid[u] = ok;
-            off[u] = (int64_t)row * row_bytes;
+            if constexpr (PAGED)
+                off[u] = (int64_t)min(max(page, 0), p.num_pages - 1) * page_bytes + (int64_t)(row & slot_mask) * row_bytes;
+            else
+                off[u] = (int64_t)row * row_bytes;
             kraw[u] = stream_load16(Kb + off[u]);
         }
 #pragma unroll
@@ -265,21 +313,27 @@ void attend_split_kernel(const AttendParams p) {
     finish_chunks<DT, D, G, GC, RG, T>(p, sm, b, g, ns);
 }
 
-template <int DT, int D, int G, int W>
+template <int DT, int D, int G, int W, bool PAGED>
 hipError_t launch_mode(int mode, const AttendParams &p, hipStream_t stream) {
     const dim3 grid(p.num_splits, p.num_kv_heads, p.batch), block(W * kWave);
     switch (mode) {
     case kDense:
-        hipLaunchKernelGGL((attend_split_kernel<DT, D, G, kDense, W>), grid, block, 0, stream, p);
+        hipLaunchKernelGGL((attend_split_kernel<DT, D, G, kDense, W, PAGED>), grid, block, 0, stream, p);
         break;
     case kSelect:
-        hipLaunchKernelGGL((attend_split_kernel<DT, D, G, kSelect, W>), grid, block, 0, stream, p);
+        hipLaunchKernelGGL((attend_split_kernel<DT, D, G, kSelect, W, PAGED>), grid, block, 0, stream, p);
         break;
     default:
-        hipLaunchKernelGGL((attend_split_kernel<DT, D, G, kSparse, W>), grid, block, 0, stream, p);
+        hipLaunchKernelGGL((attend_split_kernel<DT, D, G, kSparse, W, PAGED>), grid, block, 0, stream, p);
         break;
     }
     return hipGetLastError();
+}
+
+template <int DT, int D, int G, int W>
+hipError_t launch_paged(int mode, const AttendParams &p, hipStream_t stream) {
+    return p.block_table ? launch_mode<DT, D, G, W, true>(mode, p, stream)
+                         : launch_mode<DT, D, G, W, false>(mode, p, stream);
 }
 
 // Eight-wave workgroups exist for groups of up to four query heads (beyond that the LDS for
@@ -287,9 +341,9 @@ hipError_t launch_mode(int mode, const AttendParams &p, hipStream_t stream) {
 template <int DT, int D, int G>
 hipError_t launch_waves(int waves, int mode, const AttendParams &p, hipStream_t stream) {
     if constexpr (G <= 4) {
-        if (waves == 8) return launch_mode<DT, D, G, 8>(mode, p, stream);
+        if (waves == 8) return launch_paged<DT, D, G, 8>(mode, p, stream);
     }
-    return launch_mode<DT, D, G, 4>(mode, p, stream);
+    return launch_paged<DT, D, G, 4>(mode, p, stream);
 }
 
 template <int DT, int D>

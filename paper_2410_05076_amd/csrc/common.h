@@ -9,6 +9,7 @@ namespace tidal {
 
 constexpr int kWave = 64;
 constexpr int kSplitsMax = 256;        // upper bound on token chunks per (sequence, KV head)
+constexpr int kPageStageMax = 1024;    // block-table entries of one chunk are staged in LDS
 constexpr int kSparseChunkMax = 2048;  // positions of one chunk are staged in LDS
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kCountersMax = 65536;    // ticket counters, one per (sequence, KV head)
@@ -41,7 +42,11 @@ struct AttendParams {
     int32_t *counters;         // [B][Hkv] chunks finished so far; zero between launches
     void *topk_scratch;        // select: TopkRow [B][Hkv], histogram and candidate count cleared here
     void *out;                 // [B][Hq][D]
-    int64_t stride_batch, stride_head, stride_tok;  // elements
+    int64_t stride_batch, stride_head, stride_tok;  // elements; paged: stride_batch is the page stride
+    const int32_t *block_table;  // paged cache: [B][bt_stride] page ids, else nullptr
+    int64_t bt_stride;
+    int32_t page_shift;  // log2(page size)
+    int32_t num_pages;   // pages in the pool
     int64_t score_stride;
     int32_t batch, num_q_heads, num_kv_heads;
     int32_t max_seq_len;

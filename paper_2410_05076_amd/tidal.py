@@ -30,7 +30,9 @@ class Shape(ctypes.Structure):
                 ("kv_stride_batch", ctypes.c_int64), ("kv_stride_head", ctypes.c_int64),
                 ("kv_stride_tok", ctypes.c_int64),
                 ("seq_lens", ctypes.c_void_p), ("max_seq_len", ctypes.c_int32),
-                ("total_seq_len", ctypes.c_int64)]
+                ("total_seq_len", ctypes.c_int64),
+                ("page_size", ctypes.c_int32), ("num_pages", ctypes.c_int32),
+                ("block_table", ctypes.c_void_p), ("block_table_stride", ctypes.c_int64)]
 
 
 class TidalError(RuntimeError):
@@ -91,7 +93,20 @@ def make_shape(q, K, seq_lens, sm_scale=0.0, total_seq_len=0):
     assert q.dim() == 3 and K.dim() == 4 and q.is_contiguous() and K.stride(3) == 1
     assert seq_lens.dtype == torch.int32 and seq_lens.is_contiguous() and seq_lens.numel() == q.shape[0]
     return Shape(q.shape[0], q.shape[1], K.shape[1], q.shape[2], _dtype_code(q.dtype), float(sm_scale),
-                 K.stride(0), K.stride(1), K.stride(2), seq_lens.data_ptr(), K.shape[2], int(total_seq_len))
+                 K.stride(0), K.stride(1), K.stride(2), seq_lens.data_ptr(), K.shape[2], int(total_seq_len),
+                 0, 0, None, 0)
+
+
+def make_paged_shape(q, pool, block_table, seq_lens, max_seq_len, sm_scale=0.0, total_seq_len=0):
+    """td_shape for a paged cache: pool indexed [page][Hkv][slot][d] (any strides with d contiguous;
+    a token-major pool is passed as a permuted view), block_table int32 [B][entries per sequence]."""
+    assert q.dim() == 3 and pool.dim() == 4 and q.is_contiguous() and pool.stride(3) == 1
+    assert seq_lens.dtype == torch.int32 and seq_lens.is_contiguous() and seq_lens.numel() == q.shape[0]
+    assert block_table.dtype == torch.int32 and block_table.dim() == 2 and block_table.stride(1) == 1
+    assert block_table.shape[0] == q.shape[0]
+    return Shape(q.shape[0], q.shape[1], pool.shape[1], q.shape[2], _dtype_code(q.dtype), float(sm_scale),
+                 pool.stride(0), pool.stride(1), pool.stride(2), seq_lens.data_ptr(), int(max_seq_len),
+                 int(total_seq_len), pool.shape[2], pool.shape[0], block_table.data_ptr(), block_table.stride(0))
 
 
 def _stream():

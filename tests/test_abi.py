@@ -40,6 +40,35 @@ def test_validate_accepts_the_benchmark_shapes():
                                                  kv_stride_tok=64)), 128) == tidal.OK
 
 
+def paged(**over):
+    table = (ctypes.c_int32 * 8)(*range(8))
+    f = dict(page_size=16, num_pages=8, block_table=ctypes.addressof(table), block_table_stride=8,
+             kv_stride_batch=8 * 16 * 128, kv_stride_head=16 * 128)
+    f.update(over)
+    s = good_shape(**f)
+    s._table = table
+    return s
+
+
+def test_validate_accepts_a_paged_shape():
+    L = tidal.lib()
+    assert L.td_validate(ctypes.byref(paged()), 64) == tidal.OK
+    assert L.td_validate(ctypes.byref(paged(page_size=1, block_table_stride=100)), 64) == tidal.OK
+
+
+@pytest.mark.parametrize("over,code", [
+    (dict(page_size=12), tidal.ERR_INVALID_ARG),              # not a power of two
+    (dict(page_size=-16), tidal.ERR_INVALID_ARG),
+    (dict(block_table=None), tidal.ERR_INVALID_ARG),
+    (dict(num_pages=0), tidal.ERR_INVALID_ARG),
+    (dict(block_table_stride=6), tidal.ERR_INVALID_ARG),      # 100 tokens need 7 pages of 16
+    (dict(page_size=1, block_table_stride=400000, max_seq_len=400000), tidal.ERR_UNSUPPORTED),
+])
+def test_validate_rejects_paged(over, code):
+    L = tidal.lib()
+    assert L.td_validate(ctypes.byref(paged(**over)), 64) == code
+
+
 @pytest.mark.parametrize("over,k,code", [
     (dict(batch=0), 1, tidal.ERR_INVALID_ARG),
     (dict(num_q_heads=30), 1, tidal.ERR_INVALID_ARG),
