@@ -47,6 +47,10 @@ def main():
     ap.add_argument("--kernel-reps", type=int, default=24)
     ap.add_argument("--probe-only", action="store_true",
                     help="run only the plain streaming kernels (1 GiB read, 1 GiB copy): counter calibration")
+    ap.add_argument("--page-size", type=int, default=0,
+                    help="hold the cache in pages of this many tokens behind a shuffled block table (0: contiguous)")
+    ap.add_argument("--page-layout", default="HND", choices=["HND", "NHD"],
+                    help="inside a page: [KV head][slot][d] or [slot][KV head][d]")
     ap.add_argument("--tune", default="", help="target_workgroups,min_chunk_dense,min_chunk_sparse,max_splits,kernel_variant (0 = default)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -79,12 +83,26 @@ def main():
         heavy = W.heavy_positions(wc)
         ranks = W.zipf_ranks(wc) if wc.structure == "zipf" else None
         layers = [W.make_layer(wc, i, dev, heavy=heavy, ranks=ranks) for i in range(wc.num_layers)]
+        if args.page_size:      # the same tokens, scattered over a page pool; all copies share the table
+            if c == 0:
+                table, num_pages = W.page_table(w, args.page_size, device=dev)
+            paged = []
+            for q, K, V in layers:
+                Kp, Kv = W.paginate(K, table, num_pages, args.page_size, args.page_layout)
+                Vp, _ = W.paginate(V, table, num_pages, args.page_size, args.page_layout)
+                paged.append((q, Kp, Vp))
+                pool_view = Kv
+            layers = paged
         qs, Ks, Vs = zip(*layers)
         outs = [torch.zeros_like(q) for q in qs]
         pos = torch.full((n_sel, w.batch, w.num_kv_heads, w.k), -1, dtype=torch.int32, device=dev)
         sets.append((qs, Ks, Vs, outs, pos))
         log("generated copy %d" % c)
-    shape = tidal.make_shape(sets[0][0][0], sets[0][1][0], lens, total_seq_len=sum(w.seq_lens))
+    if args.page_size:
+        shape = tidal.make_paged_shape(sets[0][0][0], pool_view, table, lens, w.max_seq_len,
+                                       total_seq_len=sum(w.seq_lens))
+    else:
+        shape = tidal.make_shape(sets[0][0][0], sets[0][1][0], lens, total_seq_len=sum(w.seq_lens))
     td = tidal.Tidal(shape, w.k)
     if args.tune:
         td.set_tuning(*[int(x) for x in args.tune.split(",")])
@@ -192,7 +210,7 @@ def main():
     log("plain streaming kernels: read %.0f GB/s, copy %.0f GB/s (read + write bytes)"
         % (probe["read_GBps"], probe["copy_GBps"]))
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.page_size:
         cpu = cpu_baseline(w, sets[0], torch)
 
     out = {
@@ -200,7 +218,9 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": DESCRIPTIONS[w.name], "k": w.k, "input_copies_rotated": copies,
+        "config": {"workload": DESCRIPTIONS[w.name] + (", cache in pages of %d tokens (%s) behind a shuffled block table"
+                                                       % (args.page_size, args.page_layout) if args.page_size else ""),
+                   "k": w.k, "input_copies_rotated": copies,
                    "launch": "hip graph replay of td_decode_step" if use_graph else "eager td_decode_step"},
         "step_hbm": {"algorithmic_bytes": step_bytes,
                      "achieved_GBps": round(step_bytes / (us_per_step * 1e-6) / 1e9, 1),
