@@ -32,15 +32,26 @@ def free():
     torch.cuda.empty_cache()
 
 
-def run_step(w, sparse_to_check, graph=False, tag=""):
+def run_step(w, sparse_to_check, graph=False, tag="", page_size=0):
     t0 = time.time()
     heavy = W.heavy_positions(w)
     ranks = W.zipf_ranks(w) if w.structure == "zipf" else None
     layers = [W.make_layer(w, i, DEV, heavy=heavy, ranks=ranks) for i in range(w.num_layers)]
+    lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=DEV)
+    if page_size:   # the same tokens in a shuffled page pool; the oracle gathers them back itself
+        table, num_pages = W.page_table(w, page_size, device=DEV)
+        paged = []
+        for q, K, V in layers:
+            Kp, Kv = W.paginate(K, table, num_pages, page_size)
+            Vp, _ = W.paginate(V, table, num_pages, page_size)
+            paged.append((q, Kp, Vp))
+        layers = paged
+        del paged, K, V
+        shape = tidal.make_paged_shape(layers[0][0], Kv, table, lens, w.max_seq_len, total_seq_len=sum(w.seq_lens))
     qs, Ks, Vs = zip(*layers)
     del layers
-    lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=DEV)
-    shape = tidal.make_shape(qs[0], Ks[0], lens, total_seq_len=sum(w.seq_lens))
+    if not page_size:
+        shape = tidal.make_shape(qs[0], Ks[0], lens, total_seq_len=sum(w.seq_lens))
     td = tidal.Tidal(shape, w.k)
     outs = [torch.full_like(q, float("nan")) for q in qs]
     n_sel = sum(1 for x in w.schedule if x == W.SELECT)
@@ -75,6 +86,9 @@ def run_step(w, sparse_to_check, graph=False, tag=""):
         if kind == W.SPARSE and i not in sparse_to_check:
             continue
         q, K, V = qs[i].cpu(), Ks[i].cpu(), Vs[i].cpu()
+        if page_size:
+            K = O.gather_pages(K, table.cpu(), w.seq_lens, w.max_seq_len)
+            V = O.gather_pages(V, table.cpu(), w.seq_lens, w.max_seq_len)
         if kind == W.DENSE:
             ref = O.full(q, K, V, w.seq_lens)
         elif kind == W.SELECT:
@@ -96,6 +110,11 @@ def run_step(w, sparse_to_check, graph=False, tag=""):
 def test_c2_full_decode_step_eager_and_graph():
     w = W.workload("c2")
     run_step(w, set(range(w.num_layers)), graph=True, tag="c2")
+
+
+def test_c2_paged_decode_step_eager_and_graph():
+    w = W.workload("c2")
+    run_step(w, {3, 12, 14, 31}, graph=True, tag="c2 pages of 16", page_size=16)
 
 
 def test_c3_full_size():
