@@ -27,6 +27,8 @@ DESCRIPTIONS = {
     "c3": "c3 Llama-2-7B MHA shape: 32 layers, batch 1, 32 q / 32 KV heads, d 128, context 131072, k 4096, bf16 KV",
     "c4": "c4 batched Llama-3-8B shape: 32 layers, batch 16, ragged contexts 8192..65536, k 2048, bf16 KV",
     "c5": "c5 Llama-3-8B shape: 32 layers, batch 4, context 131072, k sweep, bf16 KV, Zipf(1.1) mass",
+    "c6": "c6 64-layer model with the 70B head shape: 64 layers (2 full, selection at 2 and 31, 60 sparse), batch 1, "
+          "64 q / 8 KV heads, d 128, context 32768, k 2048, bf16 KV",
 }
 
 

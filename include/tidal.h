@@ -163,12 +163,14 @@ td_status td_decode_step(td_ctx *ctx, const td_shape *shape, int32_t num_layers,
 /* Tuning knobs for measurement sweeps (0 keeps the default): target number of
  * workgroups per attention launch, the smallest token chunk per workgroup for
  * full and for sparse attention, the largest number of chunks per
- * (sequence, KV head), and the attention kernel (0: the vector-ALU kernel, the
- * faster one on MI355X, with the workgroup size chosen per launch; 1: the
- * matrix-core kernel where it applies - bf16, head_dim 128, contiguous cache; 2 / 3: the
- * vector-ALU kernel with four / eight waves per workgroup in every launch,
- * eight only for groups of up to four query heads).  The workspace size does
- * not depend on them. */
+ * (sequence, KV head), and the attention kernel (0: chosen per launch - the
+ * matrix-core kernel where it applies (bf16, head_dim 128) and is the faster
+ * one (groups of four or more query heads; full layers of smaller groups), else
+ * the vector-ALU kernel; four or eight waves per workgroup; 1: the matrix-core
+ * kernel wherever it applies; 2 / 3:
+ * the vector-ALU kernel with four / eight waves per workgroup in every launch;
+ * 4 / 5: the same for the matrix-core kernel).  The workspace size does not
+ * depend on them. */
 td_status td_set_tuning(td_ctx *ctx, int32_t target_workgroups, int32_t min_chunk_dense,
                         int32_t min_chunk_sparse, int32_t max_splits, int32_t kernel_variant);
 

@@ -171,17 +171,26 @@ td_status attend(td_ctx *ctx, const td_shape *s, int mode, const void *q, const 
     p.k = k;
     p.scale = s->sm_scale > 0.f ? s->sm_scale : 1.0f / sqrtf((float)s->head_dim);
     const int group = s->num_q_heads / s->num_kv_heads;
-    const bool mfma = s->dtype == TD_BF16 && s->head_dim == 128 && ctx->kernel_variant == 1 && s->page_size == 0;
+    // The matrix-core kernel (bf16, head_dim 128) serves up to 16 query heads from one K/V tile
+    // for the same instruction count.  Measured per launch against the vector-ALU kernel: groups
+    // of eight 28.6 vs 43.3 us (full) and 11.2 vs 15.1 us (sparse); groups of four 26.6 vs 28.0 us
+    // and 9.5 vs 10.0 us at 32K tokens, 328 vs 351 us at 4 x 128K; a single head per KV head
+    // 319-327 vs 334 us for a full layer, but 20.0 vs 18.6 us for a sparse one, where most of the
+    // 16-row tile is empty.  Hence: every layer kind for groups of four and more, full layers
+    // only for smaller groups.
+    const bool mfma_ok = s->dtype == TD_BF16 && s->head_dim == 128;
+    const int32_t kv = ctx->kernel_variant;
+    const bool mfma = mfma_ok && (kv == 1 || kv == 4 || kv == 5 || (kv == 0 && (group >= 4 || mode == kDense)));
     // Workgroup size of the vector-ALU kernel.  Full and selection layers use eight waves (half
     // as many partials to merge across workgroups; measured 3 to 9 % faster per launch on the
     // uniform workloads) unless the batch is ragged, where many small chunks balance better;
     // sparse layers are one short burst per wave and finish sooner with four.
     int waves = mode != kSparse && !ragged_batch(s) ? 8 : 4;
-    if (ctx->kernel_variant == 2) waves = 4;
-    if (ctx->kernel_variant == 3) waves = 8;
+    if (kv == 2 || kv == 4) waves = 4;
+    if (kv == 3 || kv == 5) waves = 8;
     if (!attend_supports_waves(group, waves)) waves = 4;
     plan_chunks(ctx, s, mode == kSparse, waves, mode == kSparse ? k : s->max_seq_len, &p.chunk, &p.num_splits);
-    const hipError_t e = mfma ? launch_attend_mfma(group, mode, p, stream)
+    const hipError_t e = mfma ? launch_attend_mfma(group, waves, mode, p, stream)
                               : launch_attend(s->dtype, s->head_dim, group, waves, mode, p, stream);
     if (e != hipSuccess) return fail(ctx, TD_ERR_HIP, "attention launch failed: %s", hipGetErrorString(e));
     return TD_OK;
@@ -267,7 +276,7 @@ td_status td_set_tuning(td_ctx *ctx, int32_t target_workgroups, int32_t min_chun
                         int32_t min_chunk_sparse, int32_t max_splits, int32_t kernel_variant) {
     if (!ctx) return TD_ERR_INVALID_ARG;
     if (target_workgroups < 0 || min_chunk_dense < 0 || min_chunk_sparse < 0 || max_splits < 0 ||
-        kernel_variant < 0 || kernel_variant > 3)
+        kernel_variant < 0 || kernel_variant > 5)
         return fail(ctx, TD_ERR_INVALID_ARG, "%s", "tuning values must be >= 0");
     ctx->target_workgroups = target_workgroups;
     ctx->min_chunk_dense = min_chunk_dense;

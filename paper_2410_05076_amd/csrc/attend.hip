@@ -336,13 +336,9 @@ hipError_t launch_paged(int mode, const AttendParams &p, hipStream_t stream) {
                          : launch_mode<DT, D, G, W, false>(mode, p, stream);
 }
 
-// Eight-wave workgroups exist for groups of up to four query heads (beyond that the LDS for
-// the workgroup's states would exceed what two workgroups per CU can hold).
 template <int DT, int D, int G>
 hipError_t launch_waves(int waves, int mode, const AttendParams &p, hipStream_t stream) {
-    if constexpr (G <= 4) {
-        if (waves == 8) return launch_paged<DT, D, G, 8>(mode, p, stream);
-    }
+    if (waves == 8) return launch_paged<DT, D, G, 8>(mode, p, stream);
     return launch_paged<DT, D, G, 4>(mode, p, stream);
 }
 
@@ -359,7 +355,7 @@ hipError_t launch_group(int group, int waves, int mode, const AttendParams &p, h
 
 }  // namespace
 
-bool attend_supports_waves(int group, int waves) { return waves == 4 || (waves == 8 && group <= 4); }
+bool attend_supports_waves(int group, int waves) { return (waves == 4 || waves == 8) && group >= 1; }
 
 hipError_t launch_attend(int dtype, int head_dim, int group, int waves, int mode, const AttendParams &p,
                          hipStream_t stream) {

@@ -1,11 +1,12 @@
 // Decode attention for bf16 caches with head_dim 128 on the gfx950 matrix cores.
 //
-// Same decomposition and the same tail as attend.hip (one workgroup of four wave64s per chunk
-// of consecutive tokens of a (sequence, KV head), all G query heads of the group served from
-// one fetch of K and V, partials + ticket + last-chunk merge), but both contractions of Eq. 1
-// run on MFMA so that the vector ALU only does the softmax bookkeeping.  With G = 4 the plain
-// VALU kernel spends ~140 vector instructions per 2 KiB of K+V fetched, which is about 60 %
-// of the issue slots at HBM speed; here it is ~70 per 8 KiB.
+// Same decomposition and the same tail as attend.hip (one workgroup per chunk of consecutive
+// tokens of a (sequence, KV head), all G query heads of the group served from one fetch of K
+// and V, partials + ticket + last-chunk merge), but both contractions of Eq. 1 run on MFMA so
+// that the vector ALU only does the softmax bookkeeping, and the instruction count does not
+// grow with G (a 16-row tile holds up to 16 heads).  With G = 4 the plain VALU kernel spends
+// ~140 vector instructions per 2 KiB of K+V fetched, about 60 % of the issue slots at HBM
+// speed, and still wins; with G = 8 it is bound by its arithmetic and this kernel is faster.
 //
 // A wave handles 16 tokens per iteration, lane = (n16 = lane % 16, kb = lane / 16):
 //   S^T = K Q^T   4 x v_mfma_f32_16x16x32_bf16.  A = K tile: lane (n16, kb) loads 16 bytes of
@@ -48,32 +49,29 @@ __device__ __forceinline__ s16x4 pack_pairs(uint32_t a1, uint32_t a0, uint32_t b
 constexpr uint32_t kLowHalves = 0x05040100u;   // (x1.lo16 << 16) | x0.lo16
 constexpr uint32_t kHighHalves = 0x07060302u;  // (x1.hi16 << 16) | x0.hi16
 
-template <int G, int MODE>
-__global__ __launch_bounds__(kThreads) void attend_mfma_kernel(const AttendParams p) {
+// W wave64s per workgroup (4 or 8) and PAGED as in attend.hip.  A sparse layer is one short
+// burst per wave, so there a wave takes two 16-token tiles per iteration (all 16 row loads in
+// flight at once); full and selection layers take one.
+template <int G, int MODE, int W, bool PAGED>
+__global__ __launch_bounds__(W *kWave) __attribute__((amdgpu_waves_per_eu(MODE != kSparse ? 4 : 1)))
+void attend_mfma_kernel(const AttendParams p) {
+    constexpr int T = W * kWave;
+    constexpr int kTiles = MODE == kSparse ? 2 : 1;
+    constexpr int STEP = kTiles * kWaveTokens;  // tokens per wave per iteration
     const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
     const int n16 = lane & 15, kb = lane >> 4;
 
     if constexpr (MODE == kSelect) {  // leave the row's top-k state clear for the kernels that follow
         TopkRow *row = static_cast<TopkRow *>(p.topk_scratch) + (b * p.num_kv_heads + g);
-        for (int i = split * kThreads + threadIdx.x; i < kTopkBins; i += p.num_splits * kThreads) row->hist[i] = 0;
+        for (int i = split * T + threadIdx.x; i < kTopkBins; i += p.num_splits * T) row->hist[i] = 0;
         if (split == 0 && threadIdx.x == 0) row->ncand = 0;
     }
-    const int N = min(max(p.seq_lens[b], 0), p.max_seq_len);
-    const int n_tok = MODE == kSparse ? (N > 0 ? p.k : 0) : N;
     const int t0 = split * p.chunk;
-    if (t0 >= n_tok) return;
-    const int t1 = min(n_tok, t0 + p.chunk);
-    const int ns = (n_tok + p.chunk - 1) / p.chunk;  // workgroups of this (sequence, KV head) with work
 
-    __shared__ int s_pos[MODE == kSparse ? kSparseChunkMax : 1];
-    if constexpr (MODE == kSparse) {
-        const int32_t *pos = p.positions + ((int64_t)b * p.num_kv_heads + g) * p.k;
-        for (int i = threadIdx.x; i < t1 - t0; i += kThreads) s_pos[i] = pos[t0 + i];
-        __syncthreads();
-    }
-
-    // Q^T as B operand: lane (n16 = head, kb) holds d-octet 4s + kb of head n16
+    // Loads that depend on the launch arguments only, issued ahead of the read of the sequence
+    // length: Q^T as B operand (lane (n16 = head, kb) holds d-octet 4s + kb of head n16), the
+    // chunk's positions (sparse) or block-table entries (paged full / selection layers).
     bf16x8 qfrag[4];
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
@@ -83,12 +81,92 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_kernel(const AttendParam
                                                  (((int64_t)b * p.num_q_heads + g * G + n16) * kD + (4 * s + kb) * 8) * 2);
         qfrag[s] = __builtin_bit_cast(bf16x8, v);
     }
+    constexpr int kPosPerThread = MODE == kSparse ? kSparseChunkMax / T : 1;
+    int pstage[kPosPerThread];
+    if constexpr (MODE == kSparse) {
+        const int32_t *pos = p.positions + ((int64_t)b * p.num_kv_heads + g) * p.k;
+        const int len = min(p.k - t0, p.chunk);
+#pragma unroll
+        for (int i = 0; i < kPosPerThread; ++i) {
+            const int j = i * T + threadIdx.x;
+            pstage[i] = i * T < len ? pos[t0 + min(j, len - 1)] : -1;  // workgroup-uniform condition
+        }
+    }
+    constexpr bool kStageTable = PAGED && MODE != kSparse;
+    constexpr int kTablePerThread = kStageTable ? kPageStageMax / T : 1;
+    int tstage[kTablePerThread];
+    const int first_page = PAGED ? t0 >> p.page_shift : 0;
+    if constexpr (kStageTable) {
+        const int32_t *table = p.block_table + (int64_t)b * p.bt_stride + first_page;
+        const int pages = ((min(p.max_seq_len, t0 + p.chunk) - 1) >> p.page_shift) - first_page + 1;
+#pragma unroll
+        for (int i = 0; i < kTablePerThread; ++i) {
+            const int j = i * T + threadIdx.x;
+            tstage[i] = i * T < pages ? table[min(j, pages - 1)] : 0;
+        }
+    }
+    asm volatile("" ::: "memory");  // the loads above stay above the branch on the sequence length
+
+    const int N = min(max(p.seq_lens[b], 0), p.max_seq_len);
+    const int n_tok = MODE == kSparse ? (N > 0 ? p.k : 0) : N;
+    if (t0 >= n_tok) return;
+    const int t1 = min(n_tok, t0 + p.chunk);
+    const int ns = (n_tok + p.chunk - 1) / p.chunk;  // workgroups of this (sequence, KV head) with work
+
+    __shared__ int s_pos[MODE == kSparse ? kSparseChunkMax : 1];
+    __shared__ int s_page[PAGED ? (MODE == kSparse ? kSparseChunkMax : kPageStageMax) : 1];
+    if constexpr (MODE == kSparse) {
+#pragma unroll
+        for (int i = 0; i < kPosPerThread; ++i) {
+            const int j = i * T + threadIdx.x;
+            if (j < t1 - t0) {
+                s_pos[j] = pstage[i];
+                if constexpr (PAGED) {  // the page of the row that the gather will read (row 0 if masked)
+                    const int pj = pstage[i] >= 0 && pstage[i] < N ? pstage[i] : 0;
+                    s_page[j] = p.block_table[(int64_t)b * p.bt_stride + (pj >> p.page_shift)];
+                }
+            }
+        }
+        __syncthreads();
+    } else if constexpr (PAGED) {
+        const int pages = ((t1 - 1) >> p.page_shift) - first_page + 1;
+#pragma unroll
+        for (int i = 0; i < kTablePerThread; ++i) {
+            const int j = i * T + threadIdx.x;
+            if (j < pages) s_page[j] = tstage[i];
+        }
+        __syncthreads();
+    }
 
     const int64_t row_bytes = p.stride_tok * 2;
-    const int64_t head_off = ((int64_t)b * p.stride_batch + (int64_t)g * p.stride_head) * 2;
+    const int64_t head_off = ((PAGED ? 0 : (int64_t)b * p.stride_batch) + (int64_t)g * p.stride_head) * 2;
+    const int64_t page_bytes = p.stride_batch * 2;  // paged only
+    const int slot_mask = PAGED ? (1 << p.page_shift) - 1 : 0;
     const char *Kb = static_cast<const char *>(p.K) + head_off + kb * 16;   // + 64 s per step
     const char *Vb = static_cast<const char *>(p.V) + head_off + n16 * 16;
     float *score_row = MODE == kSelect ? p.scores + ((int64_t)b * p.num_kv_heads + g) * p.score_stride : nullptr;
+
+    // Where the row for slot t of the chunk lives (byte offset inside the head's cache); lanes
+    // beyond the chunk, and positions that are no token, read a row that exists and are masked.
+    auto locate = [&](int t, bool &ok, int &row) -> int64_t {
+        ok = t < t1;
+        int page = 0;
+        if constexpr (MODE == kSparse) {
+            const int idx = ok ? t - t0 : 0;
+            const int pj = s_pos[idx];
+            if constexpr (PAGED) page = s_page[idx];
+            const bool token = pj >= 0 && pj < N;
+            ok = ok && token;
+            row = token ? pj : 0;
+        } else {
+            row = ok ? t : t1 - 1;
+            if constexpr (PAGED) page = s_page[(row >> p.page_shift) - first_page];
+        }
+        if constexpr (PAGED)
+            return (int64_t)min(max(page, 0), p.num_pages - 1) * page_bytes + (int64_t)(row & slot_mask) * row_bytes;
+        else
+            return (int64_t)row * row_bytes;
+    };
 
     float m_run = kEmptyMax, l_run = 0.f;  // head n16, the same in the four kb lanes
     f32x4 acc[8];
@@ -96,112 +174,107 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_kernel(const AttendParam
     for (int e = 0; e < 8; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
     const float scale2 = p.scale * kLog2e;
 
-    for (int base = t0 + wave * kWaveTokens; base < t1; base += kWavesPerGroup * kWaveTokens) {
-        // K: token base + n16
-        int rowk;
-        {
-            const int t = base + n16;
-            bool ok = t < t1;
-            if constexpr (MODE == kSparse) {
-                const int pj = ok ? s_pos[t - t0] : -1;
-                ok = pj >= 0 && pj < N;
-                rowk = ok ? pj : 0;
-            } else {
-                rowk = ok ? t : t1 - 1;
-            }
+    for (int base = t0 + wave * STEP; base < t1; base += W * STEP) {
+        uint4 kraw[kTiles][4], vraw[kTiles][4];
+        bool valid[kTiles][4];
+        int tok[kTiles][4];
+#pragma unroll
+        for (int x = 0; x < kTiles; ++x) {
+            // K: token base + 16x + n16
+            bool okk;
+            int rowk;
+            const char *kp = Kb + locate(base + kWaveTokens * x + n16, okk, rowk);
+#pragma unroll
+            for (int s = 0; s < 4; ++s) kraw[x][s] = stream_load16(kp + 64 * s);
+            // V: tokens base + 16x + 4kb + u; their validity is also the validity of this lane's logits
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                vraw[x][u] = stream_load16(Vb + locate(base + kWaveTokens * x + 4 * kb + u, valid[x][u], tok[x][u]));
         }
-        const char *kp = Kb + (int64_t)rowk * row_bytes;
-        uint4 kraw[4];
+        __builtin_amdgcn_sched_barrier(0);  // every load is issued before the first one is consumed
+
 #pragma unroll
-        for (int s = 0; s < 4; ++s) kraw[s] = stream_load16(kp + 64 * s);
-        // V: tokens base + 4kb + u; their validity is also the validity of this lane's logits
-        uint4 vraw[4];
-        bool valid[4];
-        int tok[4];
+        for (int x = 0; x < kTiles; ++x) {
+            f32x4 st = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int t = base + 4 * kb + u;
-            bool ok = t < t1;
-            int row;
-            if constexpr (MODE == kSparse) {
-                const int pj = ok ? s_pos[t - t0] : -1;
-                ok = pj >= 0 && pj < N;
-                row = ok ? pj : 0;
-            } else {
-                row = ok ? t : t1 - 1;
+            for (int s = 0; s < 4; ++s)
+                st = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kraw[x][s]), qfrag[s], st, 0, 0, 0);
+
+            if constexpr (MODE == kSelect) {
+                // sum of the group's scaled logits per token: heads sit in lanes n16 = 0..G-1 of a
+                // 16-lane row (lanes >= G hold zeros)
+                float gs[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    gs[i] = st[i] * p.scale;
+                    gs[i] += dpp_f<0xB1>(gs[i]);                       // quad_perm [1,0,3,2]
+                    gs[i] += dpp_f<0x4E>(gs[i]);                       // quad_perm [2,3,0,1]
+                    if constexpr (G > 4) gs[i] += dpp_f<0x141>(gs[i]); // row_half_mirror
+                }
+                // lane (0, kb) holds the sums of the four consecutive tokens base + 4kb ..: one
+                // 16-byte store where the row allows it, so a tile's 16 scores are one 64-byte write
+                if (n16 == 0) {
+                    float *dst = score_row + tok[x][0];
+                    if (valid[x][3] && (reinterpret_cast<uintptr_t>(dst) & 15u) == 0) {
+                        *reinterpret_cast<float4 *>(dst) = make_float4(gs[0], gs[1], gs[2], gs[3]);
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            if (valid[x][i]) score_row[tok[x][i]] = gs[i];
+                    }
+                }
             }
-            valid[u] = ok;
-            tok[u] = row;
-            vraw[u] = stream_load16(Vb + (int64_t)row * row_bytes);
-        }
 
-        f32x4 st = {0.f, 0.f, 0.f, 0.f};
+            float s2[4];
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
-            st = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kraw[s]), qfrag[s], st, 0, 0, 0);
+            for (int i = 0; i < 4; ++i) s2[i] = valid[x][i] ? st[i] * scale2 : -INFINITY;
+            float tm = fmaxf(fmaxf(s2[0], s2[1]), fmaxf(s2[2], s2[3]));
+            tm = fmaxf(tm, __shfl_xor(tm, 16));
+            tm = fmaxf(tm, __shfl_xor(tm, 32));
+            const float m_new = fmaxf(m_run, tm);
+            const float alpha = fast_exp2(m_run - m_new);
+            float pr[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) pr[i] = fast_exp2(s2[i] - m_new);
+            l_run = l_run * alpha + ((pr[0] + pr[1]) + (pr[2] + pr[3]));
+            if (__any(m_new != m_run)) {  // some head's maximum moved: rescale its accumulators
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float a = __shfl(alpha, 4 * kb + i);  // head 4kb + i keeps its state in lane 4kb + i
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc[e][i] *= a;
+                }
+            }
+            m_run = m_new;
 
-        if constexpr (MODE == kSelect) {
-            // sum of the group's scaled logits per token: heads sit in lanes n16 = 0..G-1 of a
-            // 16-lane row (lanes >= G hold zeros)
+            // P (tokens 4kb .. 4kb+3 of head n16) as two bf16 parts
+            uint32_t ph[4], pl[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                float gs = st[i] * p.scale;
-                gs += dpp_f<0xB1>(gs);                       // quad_perm [1,0,3,2]
-                gs += dpp_f<0x4E>(gs);                       // quad_perm [2,3,0,1]
-                if constexpr (G > 4) gs += dpp_f<0x141>(gs); // row_half_mirror
-                if (n16 == 0 && valid[i]) score_row[tok[i]] = gs;
+                ph[i] = __float_as_uint(pr[i]) & 0xffff0000u;
+                pl[i] = __float_as_uint(pr[i] - __uint_as_float(ph[i]));
             }
-        }
-
-        float s2[4];
+            const s16x4 p_hi = pack_pairs(ph[1], ph[0], ph[3], ph[2], kHighHalves);
+            const s16x4 p_lo = pack_pairs(pl[1], pl[0], pl[3], pl[2], kHighHalves);
+            const uint32_t vw[4][4] = {{vraw[x][0].x, vraw[x][0].y, vraw[x][0].z, vraw[x][0].w},
+                                       {vraw[x][1].x, vraw[x][1].y, vraw[x][1].z, vraw[x][1].w},
+                                       {vraw[x][2].x, vraw[x][2].y, vraw[x][2].z, vraw[x][2].w},
+                                       {vraw[x][3].x, vraw[x][3].y, vraw[x][3].z, vraw[x][3].w}};
 #pragma unroll
-        for (int i = 0; i < 4; ++i) s2[i] = valid[i] ? st[i] * scale2 : -INFINITY;
-        float tm = fmaxf(fmaxf(s2[0], s2[1]), fmaxf(s2[2], s2[3]));
-        tm = fmaxf(tm, __shfl_xor(tm, 16));
-        tm = fmaxf(tm, __shfl_xor(tm, 32));
-        const float m_new = fmaxf(m_run, tm);
-        const float alpha = fast_exp2(m_run - m_new);
-        float pr[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) pr[i] = fast_exp2(s2[i] - m_new);
-        l_run = l_run * alpha + ((pr[0] + pr[1]) + (pr[2] + pr[3]));
-        if (__any(m_new != m_run)) {  // some head's maximum moved: rescale its accumulators
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float a = __shfl(alpha, 4 * kb + i);  // head 4kb + i keeps its state in lane 4kb + i
-#pragma unroll
-                for (int e = 0; e < 8; ++e) acc[e][i] *= a;
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t sel = (e & 1) ? kHighHalves : kLowHalves;
+                const s16x4 vf = pack_pairs(vw[1][e >> 1], vw[0][e >> 1], vw[3][e >> 1], vw[2][e >> 1], sel);
+                acc[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_hi, vf, acc[e], 0, 0, 0);
+                acc[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_lo, vf, acc[e], 0, 0, 0);
             }
-        }
-        m_run = m_new;
-
-        // P (tokens 4kb .. 4kb+3 of head n16) as two bf16 parts
-        uint32_t ph[4], pl[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            ph[i] = __float_as_uint(pr[i]) & 0xffff0000u;
-            pl[i] = __float_as_uint(pr[i] - __uint_as_float(ph[i]));
-        }
-        const s16x4 p_hi = pack_pairs(ph[1], ph[0], ph[3], ph[2], kHighHalves);
-        const s16x4 p_lo = pack_pairs(pl[1], pl[0], pl[3], pl[2], kHighHalves);
-        const uint32_t vw[4][4] = {{vraw[0].x, vraw[0].y, vraw[0].z, vraw[0].w},
-                                   {vraw[1].x, vraw[1].y, vraw[1].z, vraw[1].w},
-                                   {vraw[2].x, vraw[2].y, vraw[2].z, vraw[2].w},
-                                   {vraw[3].x, vraw[3].y, vraw[3].z, vraw[3].w}};
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const uint32_t sel = (e & 1) ? kHighHalves : kLowHalves;
-            const s16x4 vf = pack_pairs(vw[1][e >> 1], vw[0][e >> 1], vw[3][e >> 1], vw[2][e >> 1], sel);
-            acc[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_hi, vf, acc[e], 0, 0, 0);
-            acc[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_lo, vf, acc[e], 0, 0, 0);
         }
     }
 
     // ---- one state per wave into LDS, then the common tail
     l_run += __shfl_xor(l_run, 16);
     l_run += __shfl_xor(l_run, 32);
-    constexpr int RG = kWavesPerGroup;
-    __shared__ TailShared<kD, G, RG, kThreads> sm;
+    constexpr int RG = W;
+    __shared__ TailShared<kD, G, RG, T> sm;
     if (kb == 0 && n16 < G) {
         sm.m[wave][n16] = m_run;
         sm.l[wave][n16] = l_run;
@@ -216,36 +289,44 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_kernel(const AttendParam
         }
     }
     __syncthreads();
-    fold_states<TD_BF16, kD, G, G, RG, kThreads>(p, sm, b, g, split, ns, 0);
+    fold_states<TD_BF16, kD, G, G, RG, T>(p, sm, b, g, split, ns, 0);
     if (ns == 1) return;
-    finish_chunks<TD_BF16, kD, G, G, RG, kThreads>(p, sm, b, g, ns);
+    finish_chunks<TD_BF16, kD, G, G, RG, T>(p, sm, b, g, ns);
 }
 
-template <int G>
+template <int G, int W, bool PAGED>
 hipError_t launch_mfma_mode(int mode, const AttendParams &p, hipStream_t stream) {
-    const dim3 grid(p.num_splits, p.num_kv_heads, p.batch), block(kThreads);
+    const dim3 grid(p.num_splits, p.num_kv_heads, p.batch), block(W * kWave);
     switch (mode) {
     case kDense:
-        hipLaunchKernelGGL((attend_mfma_kernel<G, kDense>), grid, block, 0, stream, p);
+        hipLaunchKernelGGL((attend_mfma_kernel<G, kDense, W, PAGED>), grid, block, 0, stream, p);
         break;
     case kSelect:
-        hipLaunchKernelGGL((attend_mfma_kernel<G, kSelect>), grid, block, 0, stream, p);
+        hipLaunchKernelGGL((attend_mfma_kernel<G, kSelect, W, PAGED>), grid, block, 0, stream, p);
         break;
     default:
-        hipLaunchKernelGGL((attend_mfma_kernel<G, kSparse>), grid, block, 0, stream, p);
+        hipLaunchKernelGGL((attend_mfma_kernel<G, kSparse, W, PAGED>), grid, block, 0, stream, p);
         break;
     }
     return hipGetLastError();
 }
 
+template <int G>
+hipError_t launch_mfma_group(int waves, int mode, const AttendParams &p, hipStream_t stream) {
+    if (waves == 8)
+        return p.block_table ? launch_mfma_mode<G, 8, true>(mode, p, stream) : launch_mfma_mode<G, 8, false>(mode, p, stream);
+    return p.block_table ? launch_mfma_mode<G, 4, true>(mode, p, stream) : launch_mfma_mode<G, 4, false>(mode, p, stream);
+}
+
 }  // namespace
 
-hipError_t launch_attend_mfma(int group, int mode, const AttendParams &p, hipStream_t stream) {
+hipError_t launch_attend_mfma(int group, int waves, int mode, const AttendParams &p, hipStream_t stream) {
+    if (waves != 4 && waves != 8) return hipErrorInvalidValue;
     switch (group) {
-    case 1: return launch_mfma_mode<1>(mode, p, stream);
-    case 2: return launch_mfma_mode<2>(mode, p, stream);
-    case 4: return launch_mfma_mode<4>(mode, p, stream);
-    case 8: return launch_mfma_mode<8>(mode, p, stream);
+    case 1: return launch_mfma_group<1>(waves, mode, p, stream);
+    case 2: return launch_mfma_group<2>(waves, mode, p, stream);
+    case 4: return launch_mfma_group<4>(waves, mode, p, stream);
+    case 8: return launch_mfma_group<8>(waves, mode, p, stream);
     default: return hipErrorInvalidValue;
     }
 }

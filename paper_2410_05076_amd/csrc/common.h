@@ -59,11 +59,11 @@ struct AttendParams {
 // Enqueues the split attention kernel (the last chunk to finish merges the partials).
 // launch_attend: vector-ALU kernel for every supported dtype / head_dim, with `waves` wave64s
 // per workgroup (4, or 8 where attend_supports_waves says so);
-// launch_attend_mfma: matrix-core kernel, bf16 with head_dim 128 only.
+// launch_attend_mfma: matrix-core kernel, bf16 with head_dim 128 only, 4 or 8 waves.
 bool attend_supports_waves(int group, int waves);
 hipError_t launch_attend(int dtype, int head_dim, int group, int waves, int mode, const AttendParams &p,
                          hipStream_t stream);
-hipError_t launch_attend_mfma(int group, int mode, const AttendParams &p, hipStream_t stream);
+hipError_t launch_attend_mfma(int group, int waves, int mode, const AttendParams &p, hipStream_t stream);
 
 // argTopK over rows of fp32 scores.  scratch: topk_scratch_bytes(rows, max_len) bytes; reset
 // clears the per-row state first (not needed right after a selection attention launch).

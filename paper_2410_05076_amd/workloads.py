@@ -39,7 +39,7 @@ def schedule_for(num_layers, select_layers=(2, 13), num_dense=2):
 @dataclass(frozen=True)
 class Workload:
     name: str
-    index: int              # 1..5, the configuration it is modelled on
+    index: int              # 1..6, the configuration it is modelled on
     schedule: tuple         # per layer DENSE / SELECT / SPARSE
     batch: int
     num_q_heads: int
@@ -104,7 +104,7 @@ def _ragged_lens(batch, lo, hi, seed):
 
 
 def workload(name, **over):
-    """The five benchmark configurations (c1..c5); keyword overrides give scaled-down cases.
+    """The benchmark configurations c1..c5 and the 64-layer c6; keyword overrides give scaled-down cases.
 
     Overrides: context (all sequences), seq_lens, k, batch, schedule, n_heavy, tau,
     num_q_heads, num_kv_heads, head_dim, dtype.
@@ -125,6 +125,11 @@ def workload(name, **over):
                      n_heavy=256, delta=4.0)
     elif name == "c5":
         w = Workload("c5", 5, s32, 4, 32, 8, 128, "bf16", 4096, (131072,) * 4, "zipf")
+    elif name == "c6":
+        # the 64-layer model of Sec. 4.3 (2 full + 2 selection + 60 sparse layers) with the 70B
+        # head shape, 64 query heads on 8 KV heads; re-selection at layer 31 (App. A, 70B table)
+        w = Workload("c6", 6, schedule_for(64, select_layers=(2, 31)), 1, 64, 8, 128, "bf16", 2048, (32768,),
+                     "cluster", n_heavy=256, delta=3.0)
     else:
         raise ValueError("unknown workload %r" % (name,))
     if "batch" in over and "seq_lens" not in over and "context" not in over:

@@ -103,6 +103,16 @@ def test_paged_layers_both_workgroup_sizes(variant):
     run_paged_checks(w, 16, "NHD", (D, S, P), "paged v%d" % variant, kernel_variant=variant)
 
 
+@pytest.mark.parametrize("variant", [0, 4, 5])
+def test_paged_layers_matrix_core_kernel(variant):
+    # groups of eight query heads run on the matrix-core kernel by default (variant 0)
+    w = W.workload("c6", context=5100, k=300)
+    run_paged_checks(w, 16, "HND", (D, S, P), "paged mfma v%d" % variant, kernel_variant=variant)
+    if variant:
+        w = W.workload("c2", context=4099, k=300)
+        run_paged_checks(w, 32, "NHD", (D, S, P), "paged mfma v%d" % variant, kernel_variant=variant)
+
+
 def test_paged_decode_step_matches_oracle_and_contiguous_run():
     w = W.workload("c1")
     layers = device_layers(w, range(w.num_layers))

@@ -136,10 +136,13 @@ def test_scaled_configs(name, over, kinds):
     ("c2", dict(context=3000, k=200, num_q_heads=64)),                    # G = 8
     ("c2", dict(context=1111, k=1111, num_q_heads=16)),                   # G = 2, k = N
 ])
-def test_matrix_core_kernel_variant(name, over):
-    # the MFMA attention kernel (bf16, head_dim 128) is an option of td_set_tuning; same bar
+@pytest.mark.parametrize("variant", [1, 4, 5])
+def test_matrix_core_kernel_variant(name, over, variant):
+    # the MFMA attention kernel (bf16, head_dim 128) is what groups of eight query heads get and
+    # an option of td_set_tuning otherwise (1: workgroup size chosen by the library, 4 / 5: four /
+    # eight waves); same bar
     w = W.workload(name, **over)
-    run_layer_checks(w, (D, S, P), "mfma %s%s" % (name, sorted(over.items())), kernel_variant=1)
+    run_layer_checks(w, (D, S, P), "mfma v%d %s%s" % (variant, name, sorted(over.items())), kernel_variant=variant)
 
 
 @pytest.mark.parametrize("variant", [2, 3])
