@@ -199,7 +199,7 @@ def main():
     if os.path.exists(tpath):
         with open(tpath) as f:
             traffic = json.load(f).get("hbm_bytes_per_launch")
-    roofline = {"kernel": "attend_split_kernel (full attention layer: K and V of one layer streamed once)",
+    roofline = {"kernel": "full-attention layer launch (attend_mfma_kernel for bf16 head_dim 128, else attend_split_kernel): K and V of one layer streamed once",
                 "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "algorithmic_bytes_per_launch": dense_bytes, "avg_launch_us": dense_us}
