@@ -215,6 +215,84 @@ int tdo_select(const tdo_shape *s, const void *q, const void *K, const void *V, 
     return err;
 }
 
+/*
+ * Variants of the selection rule for grouped-query attention.  The paper
+ * describes selection per attention head (Sec. 3.1) and does not say how the
+ * query heads that share a KV head agree on one token set; tdo_select above
+ * takes the sum of the group's scaled logits.  The alternatives:
+ *   TDO_REDUCE_MAX  r_g[j] = max_{h in g} s_h[j], one rho per KV head;
+ *   TDO_PER_HEAD    no reduction: rho_h = argTopK(s_h, k) for every query head,
+ *                   the paper's literal rule; positions are [B][Hq][k] and a
+ *                   sparse layer gathers each head's own rows (tdo_sparse_per_head).
+ * scores (optional): fp32 [B][Hkv][max_seq_len] for the reductions,
+ * [B][Hq][max_seq_len] for TDO_PER_HEAD.
+ */
+enum { TDO_REDUCE_SUM = 0, TDO_REDUCE_MAX = 1, TDO_PER_HEAD = 2 };
+
+int tdo_select_variant(const tdo_shape *s, int variant, const void *q, const void *K, const void *V,
+                       int32_t k, float *out, int32_t *positions, float *scores) {
+    if (variant == TDO_REDUCE_SUM) return tdo_select(s, q, K, V, k, out, positions, scores);
+    if (!shape_ok(s) || !positions || k < 1 || (variant != TDO_REDUCE_MAX && variant != TDO_PER_HEAD))
+        return TDO_BAD_ARG;
+    const int G = s->num_q_heads / s->num_kv_heads;
+    const int64_t maxN = s->max_seq_len;
+    float *logits = (float *)malloc((size_t)s->batch * s->num_q_heads * maxN * sizeof(float));
+    if (!logits) return TDO_NO_MEM;
+    int err = tdo_full(s, q, K, V, out, logits);
+    const int rows = variant == TDO_PER_HEAD ? s->num_q_heads : s->num_kv_heads;
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int b = 0; b < s->batch; ++b)
+        for (int x = 0; x < rows; ++x) {
+            int N = s->seq_lens[b];
+            float *r = (float *)malloc((size_t)N * sizeof(float));
+            if (!r) { err = TDO_NO_MEM; continue; }
+            for (int j = 0; j < N; ++j) {
+                if (variant == TDO_PER_HEAD) {
+                    r[j] = logits[((int64_t)b * s->num_q_heads + x) * maxN + j];
+                } else {
+                    float best = logits[((int64_t)b * s->num_q_heads + x * G) * maxN + j];
+                    for (int i = 1; i < G; ++i) {
+                        float v = logits[((int64_t)b * s->num_q_heads + x * G + i) * maxN + j];
+                        if (v > best) best = v;
+                    }
+                    r[j] = best;
+                }
+            }
+            int e = tdo_topk_row(r, N, k, positions + ((int64_t)b * rows + x) * k);
+            if (e) err = e;
+            if (scores) memcpy(scores + ((int64_t)b * rows + x) * maxN, r, (size_t)N * sizeof(float));
+            free(r);
+        }
+    free(logits);
+    return err;
+}
+
+/* Sparse attention with one rho per query head: positions [B][Hq][k]; head h
+ * attends over its own rows of KV head h / G.  Otherwise as tdo_sparse. */
+int tdo_sparse_per_head(const tdo_shape *s, const void *q, const void *K, const void *V,
+                        const int32_t *positions, int32_t k, float *out) {
+    if (!shape_ok(s) || !q || !K || !V || !out || !positions || k < 1) return TDO_BAD_ARG;
+    const int G = s->num_q_heads / s->num_kv_heads, d = s->head_dim;
+    const float scale = scale_of(s);
+    for (int b = 0; b < s->batch; ++b)
+        for (int64_t t = 0; t < (int64_t)s->num_q_heads * k; ++t)
+            if (positions[(int64_t)b * s->num_q_heads * k + t] >= s->seq_lens[b])
+                return TDO_BAD_POSITION;
+    int err = TDO_OK;
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int b = 0; b < s->batch; ++b)
+        for (int h = 0; h < s->num_q_heads; ++h) {
+            float *work = (float *)malloc((size_t)k * sizeof(float));
+            if (!work) { err = TDO_NO_MEM; continue; }
+            int64_t qo = ((int64_t)b * s->num_q_heads + h) * d;
+            int64_t kvo = b * s->kv_stride_batch + (h / G) * s->kv_stride_head;
+            attend_one(q, qo, K, V, kvo, s->kv_stride_tok, d, s->dtype, scale,
+                       positions + ((int64_t)b * s->num_q_heads + h) * k, k, out + qo, NULL, work);
+            free(work);
+        }
+    return err;
+}
+
 /* Position persistent sparse attention (Alg. 1, sparse layer): Eq. 1 over the
  * non-negative entries of positions [B][Hkv][k] only.  An entry >= N_b is an
  * error.  A (b, g) with no valid entry yields zeros. */

@@ -44,7 +44,8 @@ def lib():
         if not os.path.exists(path):
             _build.build()
         _lib = ctypes.CDLL(path)
-        for name in ("tdo_full", "tdo_select", "tdo_sparse", "tdo_step", "tdo_topk_row", "tdo_gather_pages"):
+        for name in ("tdo_full", "tdo_select", "tdo_sparse", "tdo_step", "tdo_topk_row", "tdo_gather_pages",
+                     "tdo_select_variant", "tdo_sparse_per_head"):
             getattr(_lib, name).restype = ctypes.c_int
         _lib.tdo_num_threads.restype = ctypes.c_int
     return _lib
@@ -106,6 +107,34 @@ def sparse(q, K, V, seq_lens, positions, sm_scale=0.0):
     out = torch.zeros(q.shape, dtype=torch.float32)
     _check(lib().tdo_sparse(ctypes.byref(s), _ptr(q), _ptr(K), _ptr(V), _ptr(positions),
                             ctypes.c_int32(positions.shape[2]), _ptr(out)))
+    return out
+
+
+REDUCE_SUM, REDUCE_MAX, PER_HEAD = 0, 1, 2
+
+
+def select_variant(q, K, V, seq_lens, k, variant, sm_scale=0.0):
+    """Selection layer with another grouped-query rule: REDUCE_MAX (max of the group's logits, one
+    rho per KV head) or PER_HEAD (the paper's per-head rule: positions and scores per query head).
+    Returns (out, positions, scores)."""
+    s, lens = _shape(q, K, V, seq_lens, sm_scale)
+    rows = q.shape[1] if variant == PER_HEAD else K.shape[1]
+    out = torch.zeros(q.shape, dtype=torch.float32)
+    pos = torch.zeros((q.shape[0], rows, k), dtype=torch.int32)
+    scores = torch.full((q.shape[0], rows, K.shape[2]), float("-inf"))
+    _check(lib().tdo_select_variant(ctypes.byref(s), ctypes.c_int(variant), _ptr(q), _ptr(K), _ptr(V),
+                                    ctypes.c_int32(k), _ptr(out), _ptr(pos), _ptr(scores)))
+    return out, pos, scores
+
+
+def sparse_per_head(q, K, V, seq_lens, positions, sm_scale=0.0):
+    """Sparse attention with one rho per query head: positions int32 [B][Hq][k]."""
+    s, lens = _shape(q, K, V, seq_lens, sm_scale)
+    positions = positions.to(torch.int32).contiguous()
+    assert positions.dim() == 3 and positions.shape[:2] == (q.shape[0], q.shape[1])
+    out = torch.zeros(q.shape, dtype=torch.float32)
+    _check(lib().tdo_sparse_per_head(ctypes.byref(s), _ptr(q), _ptr(K), _ptr(V), _ptr(positions),
+                                     ctypes.c_int32(positions.shape[2]), _ptr(out)))
     return out
 
 

@@ -360,3 +360,66 @@ def test_paged_full_attention_equals_contiguous_for_any_page_permutation():
         got = O.full(q, O.gather_pages(Kv, table, w.seq_lens, w.max_seq_len, fill=0.0),
                           O.gather_pages(Vv, table, w.seq_lens, w.max_seq_len, fill=0.0), w.seq_lens)
         assert torch.equal(got, want)
+
+
+# ---- other grouped-query selection rules (max over the group, per-head as in Sec. 3.1)
+
+
+def _small_gqa(seed=5):
+    g = torch.Generator().manual_seed(seed)
+    B, Hq, Hkv, N, d = 2, 6, 2, 40, 8
+    q = torch.randn((B, Hq, d), generator=g)
+    K = torch.randn((B, Hkv, N, d), generator=g)
+    V = torch.randn((B, Hkv, N, d), generator=g)
+    return q, K, V, [40, 23]
+
+
+def test_per_head_selection_is_the_single_head_rule_applied_to_each_head():
+    # repeating each KV head G times turns GQA into MHA, where tdo_select is the paper's per-head rule
+    q, K, V, lens = _small_gqa()
+    G = q.shape[1] // K.shape[1]
+    out, pos, sc = O.select_variant(q, K, V, lens, 7, O.PER_HEAD)
+    Kr, Vr = K.repeat_interleave(G, 1), V.repeat_interleave(G, 1)
+    out2, pos2, sc2 = O.select(q, Kr, Vr, lens, 7, return_scores=True)
+    assert torch.equal(pos, pos2) and torch.equal(out, out2)
+    for b, n in enumerate(lens):
+        assert torch.equal(sc[b, :, :n], sc2[b, :, :n])
+    sp = O.sparse_per_head(q, K, V, lens, pos)
+    assert torch.equal(sp, O.sparse(q, Kr, Vr, lens, pos2))
+
+
+def test_max_reduction_against_float64_ranking():
+    q, K, V, lens = _small_gqa(6)
+    G = q.shape[1] // K.shape[1]
+    out, pos, sc = O.select_variant(q, K, V, lens, 5, O.REDUCE_MAX)
+    assert torch.equal(out, O.full(q, K, V, lens))
+    for b, n in enumerate(lens):
+        for g in range(K.shape[1]):
+            s64 = torch.stack([(K[b, g, :n].double() @ q[b, g * G + i].double()) / math.sqrt(q.shape[2])
+                               for i in range(G)]).max(0).values
+            assert torch.allclose(sc[b, g, :n].double(), s64, atol=1e-5)
+            want = sorted(torch.topk(s64, 5).indices.tolist())
+            assert pos[b, g].tolist() == want
+
+
+def test_reductions_coincide_for_a_single_head_per_group():
+    g = torch.Generator().manual_seed(7)
+    q = torch.randn((1, 3, 8), generator=g)
+    K = torch.randn((1, 3, 30, 8), generator=g)
+    V = torch.randn((1, 3, 30, 8), generator=g)
+    base = O.select(q, K, V, [30], 6)
+    for variant in (O.REDUCE_MAX, O.PER_HEAD):
+        out, pos, _ = O.select_variant(q, K, V, [30], 6, variant)
+        assert torch.equal(pos, base[1]) and torch.equal(out, base[0])
+
+
+def test_max_and_sum_differ_when_one_head_dominates():
+    # token 3 is loved by head 0 and disliked by head 1: the max keeps it, the sum drops it
+    d = 4
+    q = torch.zeros((1, 2, d)); q[0, 0, 0] = 2.0; q[0, 1, 1] = 2.0
+    K = torch.zeros((1, 1, 6, d)); V = torch.zeros((1, 1, 6, d))
+    K[0, 0, 3, 0], K[0, 0, 3, 1] = 5.0, -9.0
+    K[0, 0, 1, 0], K[0, 0, 1, 1] = 1.0, 1.0
+    _, pos_sum = O.select(q, K, V, [6], 1)
+    _, pos_max, _ = O.select_variant(q, K, V, [6], 1, O.REDUCE_MAX)
+    assert pos_sum[0, 0].tolist() == [1] and pos_max[0, 0].tolist() == [3]
