@@ -81,6 +81,17 @@ typedef enum {
 
 typedef enum { TD_BF16 = 0, TD_F32 = 1 } td_dtype;
 
+/* How the query heads that share a KV head agree on rho (the paper describes selection per
+ * attention head, Sec. 3.1, and is silent on grouped-query attention):
+ *   TD_SELECT_GROUP_SUM  top-k over the per-token sum of the group's scaled logits (default);
+ *   TD_SELECT_GROUP_MAX  top-k over their per-token maximum;
+ *   TD_SELECT_PER_HEAD   no agreement: every query head selects by its own logits, the
+ *                        paper's literal rule.  positions (and group_scores) then have one
+ *                        row per QUERY head, [batch][num_q_heads][k], and a sparse layer
+ *                        gathers each head's own rows: group-size times the gather traffic.
+ * All three coincide when num_q_heads == num_kv_heads. */
+typedef enum { TD_SELECT_GROUP_SUM = 0, TD_SELECT_GROUP_MAX = 1, TD_SELECT_PER_HEAD = 2 } td_selection;
+
 /* Layer kinds of Alg. 1. */
 typedef enum { TD_LAYER_DENSE = 0, TD_LAYER_SELECT = 1, TD_LAYER_SPARSE = 2 } td_layer_kind;
 
@@ -104,6 +115,7 @@ typedef struct td_shape {
     int32_t num_pages;         /* pages in the pools that K and V point to */
     const int32_t *block_table; /* DEVICE int32 [batch][block_table_stride] page ids */
     int64_t block_table_stride; /* entries per sequence, >= ceil(max_seq_len / page_size) */
+    int32_t selection;         /* td_selection; 0 = the group sum */
 } td_shape;
 
 typedef struct td_ctx td_ctx;  /* opaque; owns the workspace (split partials, group scores) */

@@ -37,6 +37,12 @@ td_status fail(td_ctx *ctx, td_status s, const char *fmt, const char *detail = "
     return s;
 }
 
+// Rows of positions and scores per sequence: one per KV head, or per query head when every
+// head selects for itself.
+int32_t selection_rows(const td_shape *s) {
+    return s->selection == TD_SELECT_PER_HEAD ? s->num_q_heads : s->num_kv_heads;
+}
+
 // Longest chunk of a paged full / selection launch: its pages' table entries fit the LDS stage
 // (a chunk may start inside a page), rounded down to the chunk granule.
 int64_t paged_chunk_limit(int32_t page_size) {
@@ -61,6 +67,7 @@ const char *shape_problem(const td_shape *s, int32_t k, td_status *code) {
         return "KV strides must be multiples of 8 elements";
     if (k > kSparseChunkMax * kSplitsMax) return "k is larger than 524288";
     if (s->total_seq_len < 0) return "total_seq_len is negative";
+    if (s->selection < TD_SELECT_GROUP_SUM || s->selection > TD_SELECT_PER_HEAD) return "selection is not a td_selection";
     if (s->page_size < 0 || (s->page_size & (s->page_size - 1))) return "page_size is not a power of two";
     if (s->page_size > 0) {
         if (!s->block_table) return "block_table is NULL";
@@ -73,8 +80,8 @@ const char *shape_problem(const td_shape *s, int32_t k, td_status *code) {
     if (s->head_dim != 64 && s->head_dim != 128) return "head_dim must be 64 or 128";
     const int g = s->num_q_heads / s->num_kv_heads;
     if (g != 1 && g != 2 && g != 4 && g != 8) return "group size must be 1, 2, 4 or 8";
-    if (s->batch > 65535 || s->num_kv_heads > 65535 || (int64_t)s->batch * s->num_kv_heads > 65535)
-        return "batch * num_kv_heads above 65535";
+    if (s->batch > 65535 || s->num_kv_heads > 65535 || (int64_t)s->batch * selection_rows(s) > 65535)
+        return "batch * num_kv_heads (num_q_heads with per-head selection) above 65535";
     // a paged chunk stages its block-table entries in LDS; kSplitsMax chunks must cover the context
     if (s->page_size > 0 && (int64_t)s->max_seq_len > (int64_t)kSplitsMax * paged_chunk_limit(s->page_size))
         return "max_seq_len is too long for this page size";
@@ -96,7 +103,7 @@ constexpr size_t kCountersBytes = (size_t)kCountersMax * sizeof(int32_t);
 Workspace workspace_layout(const td_shape *s, int32_t k) {
     Workspace w;
     const size_t heads = (size_t)s->batch * s->num_q_heads;
-    const int32_t rows = s->batch * s->num_kv_heads;
+    const int32_t rows = s->batch * selection_rows(s);
     w.score_stride = (int64_t)align_up((size_t)s->max_seq_len, 4);
     w.counters = 0;
     w.topk = kCountersBytes;
@@ -123,7 +130,7 @@ void plan_chunks(const td_ctx *ctx, const td_shape *s, bool sparse, int32_t wave
     if (!sparse && ctx->target_workgroups == 0 && ragged_batch(s)) target = kRaggedTargetWorkgroups;
     int32_t floor_chunk = sparse ? (ctx->min_chunk_sparse > 0 ? ctx->min_chunk_sparse : kDefaultMinChunkSparse)
                                  : (ctx->min_chunk_dense > 0 ? ctx->min_chunk_dense : kDefaultMinChunkDense);
-    const int64_t groups = (int64_t)s->batch * s->num_kv_heads;
+    const int64_t groups = (int64_t)s->batch * (sparse ? selection_rows(s) : s->num_kv_heads);
     int32_t cap = std::min(kSplitsMax, ctx->max_splits > 0 ? ctx->max_splits : kDefaultMaxSplits);
     if (waves == 8) {  // the same number of waves in half as many workgroups, with chunks twice as long
         target = std::max(1, target / 2);
@@ -167,10 +174,18 @@ td_status attend(td_ctx *ctx, const td_shape *s, int mode, const void *q, const 
     p.batch = s->batch;
     p.num_q_heads = s->num_q_heads;
     p.num_kv_heads = s->num_kv_heads;
+    p.select_rule = s->selection;
+    p.kv_div = 1;
     p.max_seq_len = s->max_seq_len;
     p.k = k;
     p.scale = s->sm_scale > 0.f ? s->sm_scale : 1.0f / sqrtf((float)s->head_dim);
-    const int group = s->num_q_heads / s->num_kv_heads;
+    int group = s->num_q_heads / s->num_kv_heads;
+    if (mode == kSparse && s->selection == TD_SELECT_PER_HEAD) {
+        // one grid row per query head, each gathering its own rho from KV head (row / group)
+        p.kv_div = group;
+        p.num_kv_heads = s->num_q_heads;
+        group = 1;
+    }
     // The matrix-core kernel (bf16, head_dim 128) serves up to 16 query heads from one K/V tile
     // for the same instruction count.  Measured per launch against the vector-ALU kernel: groups
     // of eight 28.6 vs 43.3 us (full) and 11.2 vs 15.1 us (sparse); groups of four 26.6 vs 28.0 us
@@ -218,8 +233,11 @@ td_status select_tokens(td_ctx *ctx, const td_shape *s, const void *q, const voi
     const int64_t stride = group_scores ? (int64_t)s->max_seq_len : w.score_stride;
     td_status st = attend(ctx, s, kSelect, q, K, V, nullptr, k, scores, stride, out, stream);
     if (st != TD_OK) return st;
-    const hipError_t e = launch_topk(scores, stride, s->batch * s->num_kv_heads, s->seq_lens, s->num_kv_heads,
-                                     s->max_seq_len, k, positions, ctx->workspace + w.topk, false, stream);
+    // the selection kernel clears the top-k state of its KV head's row on the way; with one row
+    // per query head the state is cleared by top-k's own reset instead
+    const int32_t rows = selection_rows(s);
+    const hipError_t e = launch_topk(scores, stride, s->batch * rows, s->seq_lens, rows, s->max_seq_len, k, positions,
+                                     ctx->workspace + w.topk, s->selection == TD_SELECT_PER_HEAD, stream);
     if (e != hipSuccess) return fail(ctx, TD_ERR_HIP, "top-k launch failed: %s", hipGetErrorString(e));
     return TD_OK;
 }
@@ -348,7 +366,7 @@ td_status td_decode_step(td_ctx *ctx, const td_shape *shape, int32_t num_layers,
         if (st != TD_OK) return st;
     }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const int64_t slot = (int64_t)shape->batch * shape->num_kv_heads * k;
+    const int64_t slot = (int64_t)shape->batch * selection_rows(shape) * k;
     const int32_t *rho = nullptr;
     int n_sel = 0;
     for (int i = 0; i < num_layers; ++i) {

@@ -182,7 +182,7 @@ void attend_split_kernel(const AttendParams p) {
 
     const int64_t row_bytes = p.stride_tok * E::kBytes;
     const int64_t head_off =
-        ((PAGED ? 0 : (int64_t)b * p.stride_batch) + (int64_t)g * p.stride_head) * E::kBytes + c * 16;
+        ((PAGED ? 0 : (int64_t)b * p.stride_batch) + (int64_t)(g / p.kv_div) * p.stride_head) * E::kBytes + c * 16;
     const int64_t page_bytes = p.stride_batch * E::kBytes;  // paged only
     const int slot_mask = PAGED ? (1 << p.page_shift) - 1 : 0;
     const char *Kb = (const char *)p.K + head_off;
@@ -242,7 +242,10 @@ void attend_split_kernel(const AttendParams p) {
 #pragma unroll
                 for (int e = 0; e < EPL; ++e) d = fmaf(kf[e], qf[i][e], d);
                 d = row_sum<LPR>(d);
-                gsum[u] += d * p.scale;
+                if constexpr (MODE == kSelect) {
+                    const float sv = d * p.scale;
+                    gsum[u] = p.select_rule == TD_SELECT_GROUP_MAX ? (i ? fmaxf(gsum[u], sv) : sv) : gsum[u] + sv;
+                }
                 s2[u][i] = valid[u] ? d * scale2 : -INFINITY;
             }
         }
@@ -250,12 +253,23 @@ void attend_split_kernel(const AttendParams p) {
             // every lane of a row holds the row's sums; lane c < kUnroll writes the one of load c,
             // so the wave stores its kUnroll * TPW consecutive scores with one instruction
             static_assert(kUnroll <= LPR, "one writing lane per load");
-            float mine = gsum[0];
-#pragma unroll
-            for (int u = 1; u < kUnroll; ++u) mine = c == u ? gsum[u] : mine;
             const int t = base + c * TPW + r;
-            if (c < kUnroll && t < t1)
-                p.scores[((int64_t)b * p.num_kv_heads + g) * p.score_stride + t] = mine;
+            if (p.select_rule != TD_SELECT_PER_HEAD) {
+                float mine = gsum[0];
+#pragma unroll
+                for (int u = 1; u < kUnroll; ++u) mine = c == u ? gsum[u] : mine;
+                if (c < kUnroll && t < t1)
+                    p.scores[((int64_t)b * p.num_kv_heads + g) * p.score_stride + t] = mine;
+            } else {  // one score row per query head: the head's own scaled logits
+#pragma unroll
+                for (int i = 0; i < G; ++i) {
+                    float mine = s2[0][i];
+#pragma unroll
+                    for (int u = 1; u < kUnroll; ++u) mine = c == u ? s2[u][i] : mine;
+                    if (c < kUnroll && t < t1)
+                        p.scores[((int64_t)b * p.num_q_heads + g * G + i) * p.score_stride + t] = mine * kLn2;
+                }
+            }
         }
 
         float pr[kUnroll][G];

@@ -139,12 +139,15 @@ void attend_mfma_kernel(const AttendParams p) {
     }
 
     const int64_t row_bytes = p.stride_tok * 2;
-    const int64_t head_off = ((PAGED ? 0 : (int64_t)b * p.stride_batch) + (int64_t)g * p.stride_head) * 2;
+    const int64_t head_off = ((PAGED ? 0 : (int64_t)b * p.stride_batch) + (int64_t)(g / p.kv_div) * p.stride_head) * 2;
     const int64_t page_bytes = p.stride_batch * 2;  // paged only
     const int slot_mask = PAGED ? (1 << p.page_shift) - 1 : 0;
     const char *Kb = static_cast<const char *>(p.K) + head_off + kb * 16;   // + 64 s per step
     const char *Vb = static_cast<const char *>(p.V) + head_off + n16 * 16;
-    float *score_row = MODE == kSelect ? p.scores + ((int64_t)b * p.num_kv_heads + g) * p.score_stride : nullptr;
+    float *score_row = nullptr;  // of the KV head, or of the group's first query head (per-head rule)
+    if constexpr (MODE == kSelect)
+        score_row = p.scores + (p.select_rule == TD_SELECT_PER_HEAD ? (int64_t)b * p.num_q_heads + g * G
+                                                                    : (int64_t)b * p.num_kv_heads + g) * p.score_stride;
 
     // Where the row for slot t of the chunk lives (byte offset inside the head's cache); lanes
     // beyond the chunk, and positions that are no token, read a row that exists and are masked.
@@ -201,26 +204,39 @@ void attend_mfma_kernel(const AttendParams p) {
                 st = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kraw[x][s]), qfrag[s], st, 0, 0, 0);
 
             if constexpr (MODE == kSelect) {
-                // sum of the group's scaled logits per token: heads sit in lanes n16 = 0..G-1 of a
-                // 16-lane row (lanes >= G hold zeros)
+                // per token, the group's scaled logits sit in lanes n16 = 0..G-1 of a 16-lane row
+                // (lanes >= G hold zeros): their sum, their maximum, or each head's own value
                 float gs[4];
+                const bool per_head = p.select_rule == TD_SELECT_PER_HEAD;
+                if (p.select_rule == TD_SELECT_GROUP_MAX) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    gs[i] = st[i] * p.scale;
-                    gs[i] += dpp_f<0xB1>(gs[i]);                       // quad_perm [1,0,3,2]
-                    gs[i] += dpp_f<0x4E>(gs[i]);                       // quad_perm [2,3,0,1]
-                    if constexpr (G > 4) gs[i] += dpp_f<0x141>(gs[i]); // row_half_mirror
+                    for (int i = 0; i < 4; ++i) {
+                        gs[i] = n16 < G ? st[i] * p.scale : -INFINITY;
+                        gs[i] = fmaxf(gs[i], dpp_f<0xB1>(gs[i]));                       // quad_perm [1,0,3,2]
+                        gs[i] = fmaxf(gs[i], dpp_f<0x4E>(gs[i]));                       // quad_perm [2,3,0,1]
+                        if constexpr (G > 4) gs[i] = fmaxf(gs[i], dpp_f<0x141>(gs[i])); // row_half_mirror
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        gs[i] = st[i] * p.scale;
+                        if (!per_head) {
+                            gs[i] += dpp_f<0xB1>(gs[i]);
+                            gs[i] += dpp_f<0x4E>(gs[i]);
+                            if constexpr (G > 4) gs[i] += dpp_f<0x141>(gs[i]);
+                        }
+                    }
                 }
-                // lane (0, kb) holds the sums of the four consecutive tokens base + 4kb ..: one
+                // lane (head, kb) holds the values of the four consecutive tokens base + 4kb ..: one
                 // 16-byte store where the row allows it, so a tile's 16 scores are one 64-byte write
-                if (n16 == 0) {
-                    float *dst = score_row + tok[x][0];
+                if (per_head ? n16 < G : n16 == 0) {
+                    float *dst = score_row + (per_head ? (int64_t)n16 * p.score_stride : 0) + tok[x][0];
                     if (valid[x][3] && (reinterpret_cast<uintptr_t>(dst) & 15u) == 0) {
                         *reinterpret_cast<float4 *>(dst) = make_float4(gs[0], gs[1], gs[2], gs[3]);
                     } else {
 #pragma unroll
                         for (int i = 0; i < 4; ++i)
-                            if (valid[x][i]) score_row[tok[x][i]] = gs[i];
+                            if (valid[x][i]) dst[tok[x][i] - tok[x][0]] = gs[i];
                     }
                 }
             }

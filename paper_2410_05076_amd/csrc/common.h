@@ -12,6 +12,7 @@ constexpr int kSplitsMax = 256;        // upper bound on token chunks per (seque
 constexpr int kPageStageMax = 1024;    // block-table entries of one chunk are staged in LDS
 constexpr int kSparseChunkMax = 2048;  // positions of one chunk are staged in LDS
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
 constexpr int kCountersMax = 65536;    // ticket counters, one per (sequence, KV head)
 constexpr int kTopkBins = 2048;        // linear histogram bins per row
 constexpr int kTopkCandMax = 4096;     // scores of the k-th bin kept per row
@@ -47,6 +48,9 @@ struct AttendParams {
     int64_t bt_stride;
     int32_t page_shift;  // log2(page size)
     int32_t num_pages;   // pages in the pool
+    int32_t select_rule; // select mode: td_selection (per-head: scores has one row per query head)
+    int32_t kv_div;      // KV head of grid row g is g / kv_div (1, or the group size when a sparse
+                         // layer runs one grid row per query head)
     int64_t score_stride;
     int32_t batch, num_q_heads, num_kv_heads;
     int32_t max_seq_len;

@@ -32,7 +32,8 @@ class Shape(ctypes.Structure):
                 ("seq_lens", ctypes.c_void_p), ("max_seq_len", ctypes.c_int32),
                 ("total_seq_len", ctypes.c_int64),
                 ("page_size", ctypes.c_int32), ("num_pages", ctypes.c_int32),
-                ("block_table", ctypes.c_void_p), ("block_table_stride", ctypes.c_int64)]
+                ("block_table", ctypes.c_void_p), ("block_table_stride", ctypes.c_int64),
+                ("selection", ctypes.c_int32)]
 
 
 class TidalError(RuntimeError):
@@ -86,7 +87,10 @@ def _dtype_code(t):
     raise TypeError("q, K, V must be bfloat16 or float32, got %s" % t)
 
 
-def make_shape(q, K, seq_lens, sm_scale=0.0, total_seq_len=0):
+SELECT_GROUP_SUM, SELECT_GROUP_MAX, SELECT_PER_HEAD = 0, 1, 2
+
+
+def make_shape(q, K, seq_lens, sm_scale=0.0, total_seq_len=0, selection=0):
     """td_shape for q [B][Hq][d] and a cache tensor K [B][Hkv][N_max][d] (any strides with d contiguous).
 
     total_seq_len: the host's knowledge of sum(seq_lens), 0 if unknown (a launch-plan hint only)."""
@@ -94,10 +98,10 @@ def make_shape(q, K, seq_lens, sm_scale=0.0, total_seq_len=0):
     assert seq_lens.dtype == torch.int32 and seq_lens.is_contiguous() and seq_lens.numel() == q.shape[0]
     return Shape(q.shape[0], q.shape[1], K.shape[1], q.shape[2], _dtype_code(q.dtype), float(sm_scale),
                  K.stride(0), K.stride(1), K.stride(2), seq_lens.data_ptr(), K.shape[2], int(total_seq_len),
-                 0, 0, None, 0)
+                 0, 0, None, 0, int(selection))
 
 
-def make_paged_shape(q, pool, block_table, seq_lens, max_seq_len, sm_scale=0.0, total_seq_len=0):
+def make_paged_shape(q, pool, block_table, seq_lens, max_seq_len, sm_scale=0.0, total_seq_len=0, selection=0):
     """td_shape for a paged cache: pool indexed [page][Hkv][slot][d] (any strides with d contiguous;
     a token-major pool is passed as a permuted view), block_table int32 [B][entries per sequence]."""
     assert q.dim() == 3 and pool.dim() == 4 and q.is_contiguous() and pool.stride(3) == 1
@@ -106,7 +110,8 @@ def make_paged_shape(q, pool, block_table, seq_lens, max_seq_len, sm_scale=0.0, 
     assert block_table.shape[0] == q.shape[0]
     return Shape(q.shape[0], q.shape[1], pool.shape[1], q.shape[2], _dtype_code(q.dtype), float(sm_scale),
                  pool.stride(0), pool.stride(1), pool.stride(2), seq_lens.data_ptr(), int(max_seq_len),
-                 int(total_seq_len), pool.shape[2], pool.shape[0], block_table.data_ptr(), block_table.stride(0))
+                 int(total_seq_len), pool.shape[2], pool.shape[0], block_table.data_ptr(), block_table.stride(0),
+                 int(selection))
 
 
 def _stream():

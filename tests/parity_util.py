@@ -1,7 +1,12 @@
 """Helpers for the GPU parity tests: tolerances and the position-parity rule.
 
 Outputs: max-abs error <= 1e-2 and relative L2 error <= 5e-3 against the fp32
-oracle (bf16 inputs, fp32 accumulation, bf16-rounded output).
+oracle (bf16 inputs, fp32 accumulation, bf16-rounded output).  A bf16 output
+element of magnitude 4 or more cannot meet 1e-2 in any implementation: the
+correctly rounded value is up to half a unit in the last place, 2^-8 * 4 =
+1.56e-2, away from the fp32 result.  For such elements (none in the benchmark
+configurations, some in the tests of peaked selections) the bar is 1.25 half
+units of the element's own bf16 spacing; below magnitude 4 it is 1e-2 as stated.
 Positions: bit-exact against the oracle except inside a band around the
 oracle's k-th largest score s*: with tau = 1e-4 * max(|s*|, 1), every token
 scoring above s* + tau must be selected, none below s* - tau may be, and the
@@ -20,9 +25,15 @@ def check_output(gpu_out, oracle_out, what=""):
     o = oracle_out.float()
     assert g.shape == o.shape, what
     assert torch.isfinite(g).all(), "%s: non-finite output" % what
-    max_abs = (g - o).abs().max().item()
+    err = (g - o).abs()
+    max_abs = err.max().item()
     rel = ((g - o).norm() / o.norm().clamp_min(1e-30)).item()
-    assert max_abs <= MAX_ABS, "%s: max-abs %.3e" % (what, max_abs)
+    bar = torch.full_like(o, MAX_ABS)
+    if gpu_out.dtype == torch.bfloat16:
+        half_ulp = torch.exp2(torch.floor(torch.log2(o.abs().clamp_min(1e-30))) - 8.0)
+        bar = torch.maximum(bar, 1.25 * half_ulp)
+    worst = (err - bar).max().item()
+    assert worst <= 0.0, "%s: max-abs %.3e (%.3e over the bar)" % (what, max_abs, worst)
     assert rel <= REL_L2, "%s: rel-L2 %.3e" % (what, rel)
     return max_abs, rel
 
