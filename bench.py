@@ -53,6 +53,8 @@ def main():
                     help="hold the cache in pages of this many tokens behind a shuffled block table (0: contiguous)")
     ap.add_argument("--page-layout", default="HND", choices=["HND", "NHD"],
                     help="inside a page: [KV head][slot][d] or [slot][KV head][d]")
+    ap.add_argument("--selection", default="sum", choices=["sum", "max", "per_head"],
+                    help="grouped-query selection rule (td_shape.selection)")
     ap.add_argument("--tune", default="", help="target_workgroups,min_chunk_dense,min_chunk_sparse,max_splits,kernel_variant (0 = default)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -79,6 +81,8 @@ def main():
 
     lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=dev)
     n_sel = sum(1 for x in w.schedule if x == W.SELECT)
+    selection = {"sum": tidal.SELECT_GROUP_SUM, "max": tidal.SELECT_GROUP_MAX, "per_head": tidal.SELECT_PER_HEAD}[args.selection]
+    sel_rows = w.num_q_heads if args.selection == "per_head" else w.num_kv_heads
     sets = []
     for c in range(copies):
         wc = W.workload(args.workload, seed=w.seed + 7919 * c, **over)
@@ -97,14 +101,15 @@ def main():
             layers = paged
         qs, Ks, Vs = zip(*layers)
         outs = [torch.zeros_like(q) for q in qs]
-        pos = torch.full((n_sel, w.batch, w.num_kv_heads, w.k), -1, dtype=torch.int32, device=dev)
+        pos = torch.full((n_sel, w.batch, sel_rows, w.k), -1, dtype=torch.int32, device=dev)
         sets.append((qs, Ks, Vs, outs, pos))
         log("generated copy %d" % c)
     if args.page_size:
         shape = tidal.make_paged_shape(sets[0][0][0], pool_view, table, lens, w.max_seq_len,
-                                       total_seq_len=sum(w.seq_lens))
+                                       total_seq_len=sum(w.seq_lens), selection=selection)
     else:
-        shape = tidal.make_shape(sets[0][0][0], sets[0][1][0], lens, total_seq_len=sum(w.seq_lens))
+        shape = tidal.make_shape(sets[0][0][0], sets[0][1][0], lens, total_seq_len=sum(w.seq_lens),
+                                 selection=selection)
     td = tidal.Tidal(shape, w.k)
     if args.tune:
         td.set_tuning(*[int(x) for x in args.tune.split(",")])
@@ -212,7 +217,7 @@ def main():
     log("plain streaming kernels: read %.0f GB/s, copy %.0f GB/s (read + write bytes)"
         % (probe["read_GBps"], probe["copy_GBps"]))
     cpu = None
-    if not args.no_cpu_baseline and not args.page_size:
+    if not args.no_cpu_baseline and not args.page_size and args.selection == "sum":
         cpu = cpu_baseline(w, sets[0], torch)
 
     out = {
@@ -222,7 +227,7 @@ def main():
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": DESCRIPTIONS[w.name] + (", cache in pages of %d tokens (%s) behind a shuffled block table"
                                                        % (args.page_size, args.page_layout) if args.page_size else ""),
-                   "k": w.k, "input_copies_rotated": copies,
+                   "k": w.k, "selection": args.selection, "input_copies_rotated": copies,
                    "launch": "hip graph replay of td_decode_step" if use_graph else "eager td_decode_step"},
         "step_hbm": {"algorithmic_bytes": step_bytes,
                      "achieved_GBps": round(step_bytes / (us_per_step * 1e-6) / 1e9, 1),
