@@ -401,6 +401,29 @@ int tdo_gather_pages(int32_t batch, int32_t num_kv_heads, int32_t head_dim, int3
     return TDO_OK;
 }
 
+/*
+ * C.append(k, v) of Alg. 1: every layer appends the current token's key and
+ * value to its cache before it attends.  seq_lens already counts the current
+ * token, so the new row is row seq_lens[b] - 1 of sequence b.  k_new, v_new:
+ * [B][Hkv][d] in the cache dtype (the key arrives with its rotary embedding
+ * applied; that belongs to the projection f(W, x) of Alg. 1, not to this
+ * path).  K, V are written in place; attention afterwards is the functions above.
+ */
+int tdo_append(const tdo_shape *s, void *K, void *V, const void *k_new, const void *v_new) {
+    if (!shape_ok(s) || !K || !V || !k_new || !v_new) return TDO_BAD_ARG;
+    const size_t eb = s->dtype == TDO_F32 ? 4 : 2;
+    const size_t row = (size_t)s->head_dim * eb;
+    for (int b = 0; b < s->batch; ++b)
+        for (int g = 0; g < s->num_kv_heads; ++g) {
+            const int64_t dst = b * s->kv_stride_batch + g * s->kv_stride_head +
+                                (int64_t)(s->seq_lens[b] - 1) * s->kv_stride_tok;
+            const int64_t src = ((int64_t)b * s->num_kv_heads + g) * s->head_dim;
+            memcpy((char *)K + dst * eb, (const char *)k_new + src * eb, row);
+            memcpy((char *)V + dst * eb, (const char *)v_new + src * eb, row);
+        }
+    return TDO_OK;
+}
+
 int tdo_num_threads(void) {
 #ifdef _OPENMP
     return omp_get_max_threads();

@@ -45,7 +45,7 @@ def lib():
             _build.build()
         _lib = ctypes.CDLL(path)
         for name in ("tdo_full", "tdo_select", "tdo_sparse", "tdo_step", "tdo_topk_row", "tdo_gather_pages",
-                     "tdo_select_variant", "tdo_sparse_per_head"):
+                     "tdo_select_variant", "tdo_sparse_per_head", "tdo_append"):
             getattr(_lib, name).restype = ctypes.c_int
         _lib.tdo_num_threads.restype = ctypes.c_int
     return _lib
@@ -187,3 +187,13 @@ def gather_pages(pool, block_table, seq_lens, max_seq_len, fill=float("nan")):
         ctypes.c_int32(num_pages), _ptr(bt), ctypes.c_int64(bt.stride(0)), ctypes.c_int64(pool.stride(0)),
         ctypes.c_int64(pool.stride(1)), ctypes.c_int64(pool.stride(2)), _ptr(pool), _ptr(logical)))
     return logical
+
+
+def append(K, V, k_new, v_new, seq_lens):
+    """C.append(k, v) of Alg. 1, in place: row seq_lens[b] - 1 of K and V takes k_new, v_new [B][Hkv][d]."""
+    assert k_new.dim() == 3 and k_new.shape == v_new.shape and k_new.is_contiguous() and v_new.is_contiguous()
+    assert k_new.dtype == K.dtype == V.dtype == v_new.dtype
+    q_like = torch.zeros((K.shape[0], K.shape[1], K.shape[3]), dtype=K.dtype)
+    s, lens = _shape(q_like, K, V, seq_lens, 0.0)
+    assert k_new.shape == q_like.shape
+    _check(lib().tdo_append(ctypes.byref(s), _ptr(K), _ptr(V), _ptr(k_new), _ptr(v_new)))

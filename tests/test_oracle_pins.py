@@ -423,3 +423,36 @@ def test_max_and_sum_differ_when_one_head_dominates():
     _, pos_sum = O.select(q, K, V, [6], 1)
     _, pos_max, _ = O.select_variant(q, K, V, [6], 1, O.REDUCE_MAX)
     assert pos_sum[0, 0].tolist() == [1] and pos_max[0, 0].tolist() == [3]
+
+
+# ---- C.append(k, v) of Alg. 1
+
+
+def test_append_writes_the_last_row_of_every_sequence_and_nothing_else():
+    g = torch.Generator().manual_seed(11)
+    B, Hkv, N, d = 3, 2, 20, 8
+    lens = [20, 7, 1]
+    for dtype in (torch.float32, torch.bfloat16):
+        K = torch.randn((B, Hkv, N, d), generator=g).to(dtype)
+        V = torch.randn((B, Hkv, N, d), generator=g).to(dtype)
+        kn = torch.randn((B, Hkv, d), generator=g).to(dtype)
+        vn = torch.randn((B, Hkv, d), generator=g).to(dtype)
+        K0, V0 = K.clone(), V.clone()
+        O.append(K, V, kn, vn, lens)
+        for b, n in enumerate(lens):
+            assert torch.equal(K[b, :, n - 1], kn[b]) and torch.equal(V[b, :, n - 1], vn[b])
+            keep = [j for j in range(N) if j != n - 1]
+            assert torch.equal(K[b, :, keep], K0[b, :, keep]) and torch.equal(V[b, :, keep], V0[b, :, keep])
+
+
+def test_append_then_attend_equals_attention_over_the_concatenated_cache():
+    # Alg. 1 appends first and attends over the whole cache: the new token is visible to itself
+    g = torch.Generator().manual_seed(12)
+    q = torch.randn((1, 2, 8), generator=g)
+    K = torch.randn((1, 2, 10, 8), generator=g)
+    V = torch.randn((1, 2, 10, 8), generator=g)
+    kn = torch.randn((1, 2, 8), generator=g)
+    vn = torch.randn((1, 2, 8), generator=g)
+    want = O.full(q, torch.cat([K[:, :, :9], kn[:, :, None]], 2), torch.cat([V[:, :, :9], vn[:, :, None]], 2), [10])
+    O.append(K, V, kn, vn, [10])
+    assert torch.equal(O.full(q, K, V, [10]), want)
