@@ -53,6 +53,8 @@ def main():
                     help="hold the cache in pages of this many tokens behind a shuffled block table (0: contiguous)")
     ap.add_argument("--page-layout", default="HND", choices=["HND", "NHD"],
                     help="inside a page: [KV head][slot][d] or [slot][KV head][d]")
+    ap.add_argument("--append", action="store_true",
+                    help="time td_decode_step_append: every layer also appends the current token's k, v to its cache")
     ap.add_argument("--selection", default="sum", choices=["sum", "max", "per_head"],
                     help="grouped-query selection rule (td_shape.selection)")
     ap.add_argument("--tune", default="", help="target_workgroups,min_chunk_dense,min_chunk_sparse,max_splits,kernel_variant (0 = default)")
@@ -83,7 +85,7 @@ def main():
     n_sel = sum(1 for x in w.schedule if x == W.SELECT)
     selection = {"sum": tidal.SELECT_GROUP_SUM, "max": tidal.SELECT_GROUP_MAX, "per_head": tidal.SELECT_PER_HEAD}[args.selection]
     sel_rows = w.num_q_heads if args.selection == "per_head" else w.num_kv_heads
-    sets = []
+    sets, all_news = [], []
     for c in range(copies):
         wc = W.workload(args.workload, seed=w.seed + 7919 * c, **over)
         heavy = W.heavy_positions(wc)
@@ -99,10 +101,19 @@ def main():
                 paged.append((q, Kp, Vp))
                 pool_view = Kv
             layers = paged
+        if args.append and not args.page_size:   # the current token's rows, handed over separately
+            news = [(torch.stack([K[b, :, n - 1] for b, n in enumerate(w.seq_lens)]).contiguous(),
+                     torch.stack([V[b, :, n - 1] for b, n in enumerate(w.seq_lens)]).contiguous()) for _, K, V in layers]
+        elif args.append:
+            news = [(torch.randn((w.batch, w.num_kv_heads, w.head_dim), device=dev).to(w.torch_dtype),
+                     torch.randn((w.batch, w.num_kv_heads, w.head_dim), device=dev).to(w.torch_dtype)) for _ in layers]
+        else:
+            news = None
         qs, Ks, Vs = zip(*layers)
         outs = [torch.zeros_like(q) for q in qs]
         pos = torch.full((n_sel, w.batch, sel_rows, w.k), -1, dtype=torch.int32, device=dev)
         sets.append((qs, Ks, Vs, outs, pos))
+        all_news.append(news)
         log("generated copy %d" % c)
     if args.page_size:
         shape = tidal.make_paged_shape(sets[0][0][0], pool_view, table, lens, w.max_seq_len,
@@ -116,7 +127,11 @@ def main():
 
     def enqueue(c):
         qs, Ks, Vs, outs, pos = sets[c]
-        td.decode_step(shape, w.schedule, qs, Ks, Vs, w.k, outs, pos)
+        if args.append:
+            td.decode_step_append(shape, w.schedule, qs, [a for a, _ in all_news[c]], [b for _, b in all_news[c]],
+                                  Ks, Vs, w.k, outs, pos)
+        else:
+            td.decode_step(shape, w.schedule, qs, Ks, Vs, w.k, outs, pos)
 
     for c in range(copies):
         enqueue(c)
@@ -228,7 +243,8 @@ def main():
         "config": {"workload": DESCRIPTIONS[w.name] + (", cache in pages of %d tokens (%s) behind a shuffled block table"
                                                        % (args.page_size, args.page_layout) if args.page_size else ""),
                    "k": w.k, "selection": args.selection, "input_copies_rotated": copies,
-                   "launch": "hip graph replay of td_decode_step" if use_graph else "eager td_decode_step"},
+                   "launch": ("hip graph replay of " if use_graph else "eager ") +
+                             ("td_decode_step_append" if args.append else "td_decode_step")},
         "step_hbm": {"algorithmic_bytes": step_bytes,
                      "achieved_GBps": round(step_bytes / (us_per_step * 1e-6) / 1e9, 1),
                      "frac_of_peak": round(step_bytes / (us_per_step * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)},

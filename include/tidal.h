@@ -172,6 +172,22 @@ td_status td_decode_step(td_ctx *ctx, const td_shape *shape, int32_t num_layers,
                          const void *const *K_layers, const void *const *V_layers, int32_t k,
                          void *const *out_layers, int32_t *positions, void *hip_stream);
 
+/* The same with C.append(k, v) of Alg. 1 fused into each layer's launch: layer
+ * i first appends the current token's key and value, k_new_layers[i] and
+ * v_new_layers[i] ([batch][num_kv_heads][head_dim], element type `dtype`,
+ * 16-byte aligned; the key already carries its rotary embedding - that is
+ * part of the projection that produces q, k, v), as token seq_lens[b] - 1 of
+ * K_layers[i] / V_layers[i] (seq_lens counts the current token) and then
+ * attends over the cache including it.  The caches are written in place (one
+ * row per sequence and KV head, through the block table if paged); rows
+ * before seq_lens[b] - 1 must already hold the earlier tokens, that row's old
+ * contents are never read. */
+td_status td_decode_step_append(td_ctx *ctx, const td_shape *shape, int32_t num_layers,
+                                const int32_t *schedule, const void *const *q_layers,
+                                const void *const *k_new_layers, const void *const *v_new_layers,
+                                void *const *K_layers, void *const *V_layers, int32_t k,
+                                void *const *out_layers, int32_t *positions, void *hip_stream);
+
 /* Tuning knobs for measurement sweeps (0 keeps the default): target number of
  * workgroups per attention launch, the smallest token chunk per workgroup for
  * full and for sparse attention, the largest number of chunks per

@@ -149,11 +149,12 @@ void plan_chunks(const td_ctx *ctx, const td_shape *s, bool sparse, int32_t wave
 
 td_status attend(td_ctx *ctx, const td_shape *s, int mode, const void *q, const void *K, const void *V,
                  const int32_t *positions, int32_t k, float *scores, int64_t score_stride, void *out,
-                 hipStream_t stream) {
+                 hipStream_t stream, const void *k_new = nullptr, const void *v_new = nullptr) {
     const Workspace w = workspace_layout(s, mode == kDense ? 0 : k);
     AttendParams p;
     memset(&p, 0, sizeof p);
     p.q = q; p.K = K; p.V = V; p.out = out;
+    p.k_new = k_new; p.v_new = v_new;
     p.seq_lens = s->seq_lens;
     p.positions = positions;
     p.scores = scores;
@@ -227,11 +228,12 @@ td_status check_call(td_ctx *ctx, const td_shape *s, int32_t k, bool needs_k, co
 }
 
 td_status select_tokens(td_ctx *ctx, const td_shape *s, const void *q, const void *K, const void *V,
-                        int32_t k, void *out, int32_t *positions, float *group_scores, hipStream_t stream) {
+                        int32_t k, void *out, int32_t *positions, float *group_scores, hipStream_t stream,
+                        const void *k_new = nullptr, const void *v_new = nullptr) {
     const Workspace w = workspace_layout(s, k);
     float *scores = group_scores ? group_scores : reinterpret_cast<float *>(ctx->workspace + w.scores);
     const int64_t stride = group_scores ? (int64_t)s->max_seq_len : w.score_stride;
-    td_status st = attend(ctx, s, kSelect, q, K, V, nullptr, k, scores, stride, out, stream);
+    td_status st = attend(ctx, s, kSelect, q, K, V, nullptr, k, scores, stride, out, stream, k_new, v_new);
     if (st != TD_OK) return st;
     // the selection kernel clears the top-k state of its KV head's row on the way; with one row
     // per query head the state is cleared by top-k's own reset instead
@@ -239,6 +241,53 @@ td_status select_tokens(td_ctx *ctx, const td_shape *s, const void *q, const voi
     const hipError_t e = launch_topk(scores, stride, s->batch * rows, s->seq_lens, rows, s->max_seq_len, k, positions,
                                      ctx->workspace + w.topk, s->selection == TD_SELECT_PER_HEAD, stream);
     if (e != hipSuccess) return fail(ctx, TD_ERR_HIP, "top-k launch failed: %s", hipGetErrorString(e));
+    return TD_OK;
+}
+
+td_status decode_step(td_ctx *ctx, const td_shape *shape, int32_t num_layers, const int32_t *schedule,
+                      const void *const *q_layers, const void *const *k_new_layers, const void *const *v_new_layers,
+                      const void *const *K_layers, const void *const *V_layers, int32_t k, void *const *out_layers,
+                      int32_t *positions, void *hip_stream) {
+    if (!ctx) return TD_ERR_INVALID_ARG;
+    if (num_layers < 1 || !schedule || !q_layers || !K_layers || !V_layers || !out_layers)
+        return fail(ctx, TD_ERR_INVALID_ARG, "%s", "num_layers < 1 or a layer array is NULL");
+    bool any_budget = false, selected = false;
+    for (int i = 0; i < num_layers; ++i) {
+        if (schedule[i] < TD_LAYER_DENSE || schedule[i] > TD_LAYER_SPARSE)
+            return fail(ctx, TD_ERR_INVALID_ARG, "%s", "schedule entry is not a td_layer_kind");
+        if (schedule[i] == TD_LAYER_SELECT) selected = true;
+        if (schedule[i] == TD_LAYER_SPARSE && !selected)
+            return fail(ctx, TD_ERR_INVALID_ARG, "%s", "sparse layer before any selection layer");
+        if (schedule[i] != TD_LAYER_DENSE) any_budget = true;
+    }
+    if (any_budget && !positions) return fail(ctx, TD_ERR_INVALID_ARG, "%s", "positions is NULL");
+    for (int i = 0; i < num_layers; ++i) {
+        td_status st = check_call(ctx, shape, k, any_budget, q_layers[i], K_layers[i], V_layers[i], out_layers[i]);
+        if (st != TD_OK) return st;
+        if (k_new_layers && (!k_new_layers[i] || !v_new_layers[i] || misaligned(k_new_layers[i]) || misaligned(v_new_layers[i])))
+            return fail(ctx, TD_ERR_INVALID_ARG, "%s", "k_new / v_new of a layer is NULL or not 16-byte aligned");
+    }
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int64_t slot = (int64_t)shape->batch * selection_rows(shape) * k;
+    const int32_t *rho = nullptr;
+    int n_sel = 0;
+    for (int i = 0; i < num_layers; ++i) {
+        td_status st;
+        const void *kn = k_new_layers ? k_new_layers[i] : nullptr, *vn = k_new_layers ? v_new_layers[i] : nullptr;
+        if (schedule[i] == TD_LAYER_DENSE) {
+            st = attend(ctx, shape, kDense, q_layers[i], K_layers[i], V_layers[i], nullptr, 0, nullptr, 0,
+                        out_layers[i], stream, kn, vn);
+        } else if (schedule[i] == TD_LAYER_SELECT) {
+            int32_t *dst = positions + slot * n_sel++;
+            st = select_tokens(ctx, shape, q_layers[i], K_layers[i], V_layers[i], k, out_layers[i], dst, nullptr, stream,
+                               kn, vn);
+            rho = dst;
+        } else {
+            st = attend(ctx, shape, kSparse, q_layers[i], K_layers[i], V_layers[i], rho, k, nullptr, 0,
+                        out_layers[i], stream, kn, vn);
+        }
+        if (st != TD_OK) return st;
+    }
     return TD_OK;
 }
 
@@ -348,43 +397,19 @@ td_status td_topk(td_ctx *ctx, const float *scores, int64_t row_stride, int32_t 
 td_status td_decode_step(td_ctx *ctx, const td_shape *shape, int32_t num_layers, const int32_t *schedule,
                          const void *const *q_layers, const void *const *K_layers, const void *const *V_layers,
                          int32_t k, void *const *out_layers, int32_t *positions, void *hip_stream) {
+    return decode_step(ctx, shape, num_layers, schedule, q_layers, nullptr, nullptr, K_layers, V_layers, k, out_layers,
+                       positions, hip_stream);
+}
+
+td_status td_decode_step_append(td_ctx *ctx, const td_shape *shape, int32_t num_layers, const int32_t *schedule,
+                                const void *const *q_layers, const void *const *k_new_layers,
+                                const void *const *v_new_layers, void *const *K_layers, void *const *V_layers,
+                                int32_t k, void *const *out_layers, int32_t *positions, void *hip_stream) {
     if (!ctx) return TD_ERR_INVALID_ARG;
-    if (num_layers < 1 || !schedule || !q_layers || !K_layers || !V_layers || !out_layers)
-        return fail(ctx, TD_ERR_INVALID_ARG, "%s", "num_layers < 1 or a layer array is NULL");
-    bool any_budget = false, selected = false;
-    for (int i = 0; i < num_layers; ++i) {
-        if (schedule[i] < TD_LAYER_DENSE || schedule[i] > TD_LAYER_SPARSE)
-            return fail(ctx, TD_ERR_INVALID_ARG, "%s", "schedule entry is not a td_layer_kind");
-        if (schedule[i] == TD_LAYER_SELECT) selected = true;
-        if (schedule[i] == TD_LAYER_SPARSE && !selected)
-            return fail(ctx, TD_ERR_INVALID_ARG, "%s", "sparse layer before any selection layer");
-        if (schedule[i] != TD_LAYER_DENSE) any_budget = true;
-    }
-    if (any_budget && !positions) return fail(ctx, TD_ERR_INVALID_ARG, "%s", "positions is NULL");
-    for (int i = 0; i < num_layers; ++i) {
-        td_status st = check_call(ctx, shape, k, any_budget, q_layers[i], K_layers[i], V_layers[i], out_layers[i]);
-        if (st != TD_OK) return st;
-    }
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const int64_t slot = (int64_t)shape->batch * selection_rows(shape) * k;
-    const int32_t *rho = nullptr;
-    int n_sel = 0;
-    for (int i = 0; i < num_layers; ++i) {
-        td_status st;
-        if (schedule[i] == TD_LAYER_DENSE) {
-            st = attend(ctx, shape, kDense, q_layers[i], K_layers[i], V_layers[i], nullptr, 0, nullptr, 0,
-                        out_layers[i], stream);
-        } else if (schedule[i] == TD_LAYER_SELECT) {
-            int32_t *dst = positions + slot * n_sel++;
-            st = select_tokens(ctx, shape, q_layers[i], K_layers[i], V_layers[i], k, out_layers[i], dst, nullptr, stream);
-            rho = dst;
-        } else {
-            st = attend(ctx, shape, kSparse, q_layers[i], K_layers[i], V_layers[i], rho, k, nullptr, 0,
-                        out_layers[i], stream);
-        }
-        if (st != TD_OK) return st;
-    }
-    return TD_OK;
+    if (!k_new_layers || !v_new_layers) return fail(ctx, TD_ERR_INVALID_ARG, "%s", "k_new_layers or v_new_layers is NULL");
+    return decode_step(ctx, shape, num_layers, schedule, q_layers, k_new_layers, v_new_layers,
+                       const_cast<const void *const *>(K_layers), const_cast<const void *const *>(V_layers), k,
+                       out_layers, positions, hip_stream);
 }
 
 td_status td_probe_stream(td_ctx *ctx, void *dst, const void *src, size_t bytes, void *hip_stream) {

@@ -188,6 +188,23 @@ void attend_split_kernel(const AttendParams p) {
     const char *Kb = (const char *)p.K + head_off;
     const char *Vb = (const char *)p.V + head_off;
 
+    // Fused C.append(k, v) of Alg. 1: the current token's row (index N - 1) comes from k_new /
+    // v_new.  Whoever needs that row reads it there instead of from the cache, so nobody depends
+    // on the one workgroup per KV head that stores it into the cache.
+    const bool append = p.k_new != nullptr;
+    const int last = N - 1;
+    const int64_t new_off = (((int64_t)b * (p.num_kv_heads / p.kv_div) + g / p.kv_div) * D) * E::kBytes + c * 16;
+    const char *Knew = (const char *)p.k_new + new_off, *Vnew = (const char *)p.v_new + new_off;
+    if (append && split == 0 && g % p.kv_div == 0 && threadIdx.x < LPR) {
+        int64_t dst = (int64_t)last * row_bytes;
+        if constexpr (PAGED) {
+            const int page = p.block_table[(int64_t)b * p.bt_stride + (last >> p.page_shift)];
+            dst = (int64_t)min(max(page, 0), p.num_pages - 1) * page_bytes + (int64_t)(last & slot_mask) * row_bytes;
+        }
+        *(uint4 *)(const_cast<char *>(Kb) + dst) = *(const uint4 *)Knew;
+        *(uint4 *)(const_cast<char *>(Vb) + dst) = *(const uint4 *)Vnew;
+    }
+
     float m[G], l[G], acc[G][EPL];
 #pragma unroll
     for (int i = 0; i < G; ++i) {
@@ -200,7 +217,7 @@ void attend_split_kernel(const AttendParams p) {
 
     for (int base = t0 + wave * STEP; base < t1; base += TILE) {
         uint4 kraw[kUnroll], vraw[kUnroll];
-        bool valid[kUnroll];
+        bool valid[kUnroll], fresh[kUnroll];
         int64_t off[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
@@ -224,10 +241,11 @@ void attend_split_kernel(const AttendParams p) {
                 off[u] = (int64_t)min(max(page, 0), p.num_pages - 1) * page_bytes + (int64_t)(row & slot_mask) * row_bytes;
             else
                 off[u] = (int64_t)row * row_bytes;
-            kraw[u] = stream_load16(Kb + off[u]);
+            fresh[u] = append && row == last;
+            kraw[u] = stream_load16(fresh[u] ? Knew : Kb + off[u]);
         }
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) vraw[u] = stream_load16(Vb + off[u]);
+        for (int u = 0; u < kUnroll; ++u) vraw[u] = stream_load16(fresh[u] ? Vnew : Vb + off[u]);
         __builtin_amdgcn_sched_barrier(0);  // every load is issued before the first one is consumed
 
         float s2[kUnroll][G], gsum[kUnroll];

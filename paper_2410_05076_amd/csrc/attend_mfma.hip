@@ -151,6 +151,25 @@ void attend_mfma_kernel(const AttendParams p) {
 
     // Where the row for slot t of the chunk lives (byte offset inside the head's cache); lanes
     // beyond the chunk, and positions that are no token, read a row that exists and are masked.
+    // Fused C.append(k, v) of Alg. 1: the current token's row (index N - 1) comes from k_new /
+    // v_new.  Whoever needs that row reads it there instead of from the cache, so nobody depends
+    // on the one workgroup per KV head that stores it into the cache.
+    const bool append = p.k_new != nullptr;
+    const int last = N - 1;
+    const int64_t new_off = (((int64_t)b * (p.num_kv_heads / p.kv_div) + g / p.kv_div) * kD) * 2;
+    const char *Knew = static_cast<const char *>(p.k_new) + new_off + kb * 16;
+    const char *Vnew = static_cast<const char *>(p.v_new) + new_off + n16 * 16;
+    if (append && split == 0 && g % p.kv_div == 0 && threadIdx.x < 16) {
+        int64_t dst = (int64_t)last * row_bytes;
+        if constexpr (PAGED) {
+            const int page = p.block_table[(int64_t)b * p.bt_stride + (last >> p.page_shift)];
+            dst = (int64_t)min(max(page, 0), p.num_pages - 1) * page_bytes + (int64_t)(last & slot_mask) * row_bytes;
+        }
+        *reinterpret_cast<uint4 *>(const_cast<char *>(Vb) + dst) = *reinterpret_cast<const uint4 *>(Vnew);
+        *reinterpret_cast<uint4 *>(static_cast<char *>(const_cast<void *>(p.K)) + head_off + n16 * 16 + dst) =
+            *reinterpret_cast<const uint4 *>(static_cast<const char *>(p.k_new) + new_off + n16 * 16);
+    }
+
     auto locate = [&](int t, bool &ok, int &row) -> int64_t {
         ok = t < t1;
         int page = 0;
@@ -186,13 +205,16 @@ void attend_mfma_kernel(const AttendParams p) {
             // K: token base + 16x + n16
             bool okk;
             int rowk;
-            const char *kp = Kb + locate(base + kWaveTokens * x + n16, okk, rowk);
+            const int64_t koff = locate(base + kWaveTokens * x + n16, okk, rowk);
+            const char *kp = append && rowk == last ? Knew : Kb + koff;
 #pragma unroll
             for (int s = 0; s < 4; ++s) kraw[x][s] = stream_load16(kp + 64 * s);
             // V: tokens base + 16x + 4kb + u; their validity is also the validity of this lane's logits
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
-                vraw[x][u] = stream_load16(Vb + locate(base + kWaveTokens * x + 4 * kb + u, valid[x][u], tok[x][u]));
+            for (int u = 0; u < 4; ++u) {
+                const int64_t voff = locate(base + kWaveTokens * x + 4 * kb + u, valid[x][u], tok[x][u]);
+                vraw[x][u] = stream_load16(append && tok[x][u] == last ? Vnew : Vb + voff);
+            }
         }
         __builtin_amdgcn_sched_barrier(0);  // every load is issued before the first one is consumed
 

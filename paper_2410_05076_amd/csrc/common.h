@@ -35,6 +35,7 @@ enum AttendMode { kDense = 0, kSelect = 1, kSparse = 2 };
 
 struct AttendParams {
     const void *q, *K, *V;
+    const void *k_new, *v_new;  // fused C.append: [B][Hkv][D] rows for token seq_lens[b] - 1, or nullptr
     const int32_t *seq_lens;
     const int32_t *positions;  // sparse: [B][Hkv][k]
     float *scores;             // select: [B][Hkv][score_stride]

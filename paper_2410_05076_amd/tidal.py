@@ -18,7 +18,8 @@ BF16, F32 = 0, 1
 LAYER_DENSE, LAYER_SELECT, LAYER_SPARSE = 0, 1, 2
 
 EXPORTS = ("td_validate", "td_workspace_bytes", "td_topk_workspace_bytes", "td_create", "td_destroy", "td_full_attend",
-           "td_select_tokens", "td_sparse_attend", "td_topk", "td_decode_step", "td_set_tuning", "td_probe_stream",
+           "td_select_tokens", "td_sparse_attend", "td_topk", "td_decode_step", "td_decode_step_append",
+           "td_set_tuning", "td_probe_stream",
            "td_status_string", "td_last_error")
 
 
@@ -71,6 +72,9 @@ def lib():
     L.td_decode_step.argtypes = [vp, shp, i32, ctypes.POINTER(i32), ctypes.POINTER(vp), ctypes.POINTER(vp),
                                  ctypes.POINTER(vp), i32, ctypes.POINTER(vp), vp, vp]
     L.td_decode_step.restype = ctypes.c_int
+    pv = ctypes.POINTER(vp)
+    L.td_decode_step_append.argtypes = [vp, shp, i32, ctypes.POINTER(i32), pv, pv, pv, pv, pv, i32, pv, vp, vp]
+    L.td_decode_step_append.restype = ctypes.c_int
     L.td_set_tuning.argtypes, L.td_set_tuning.restype = [vp, i32, i32, i32, i32, i32], ctypes.c_int
     L.td_probe_stream.argtypes, L.td_probe_stream.restype = [vp, vp, vp, sz, vp], ctypes.c_int
     L.td_status_string.argtypes, L.td_status_string.restype = [ctypes.c_int], ctypes.c_char_p
@@ -186,6 +190,18 @@ class Tidal:
         sched = (ctypes.c_int32 * n)(*[int(x) for x in schedule])
         self._check(lib().td_decode_step(
             self._ctx, ctypes.byref(shape), n, sched, arr(*[t.data_ptr() for t in qs]),
+            arr(*[t.data_ptr() for t in Ks]), arr(*[t.data_ptr() for t in Vs]), k,
+            arr(*[t.data_ptr() for t in outs]), positions.data_ptr(), _stream()))
+        return outs, positions
+
+    def decode_step_append(self, shape, schedule, qs, k_news, v_news, Ks, Vs, k, outs, positions):
+        """td_decode_step_append: every layer appends k_news[i], v_news[i] [B][Hkv][d] to its cache first."""
+        n = len(schedule)
+        arr = ctypes.c_void_p * n
+        sched = (ctypes.c_int32 * n)(*[int(x) for x in schedule])
+        self._check(lib().td_decode_step_append(
+            self._ctx, ctypes.byref(shape), n, sched, arr(*[t.data_ptr() for t in qs]),
+            arr(*[t.data_ptr() for t in k_news]), arr(*[t.data_ptr() for t in v_news]),
             arr(*[t.data_ptr() for t in Ks]), arr(*[t.data_ptr() for t in Vs]), k,
             arr(*[t.data_ptr() for t in outs]), positions.data_ptr(), _stream()))
         return outs, positions
