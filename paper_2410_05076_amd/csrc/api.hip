@@ -82,6 +82,9 @@ const char *shape_problem(const td_shape *s, int32_t k, td_status *code) {
     if (g != 1 && g != 2 && g != 4 && g != 8) return "group size must be 1, 2, 4 or 8";
     if (s->batch > 65535 || s->num_kv_heads > 65535 || (int64_t)s->batch * selection_rows(s) > 65535)
         return "batch * num_kv_heads (num_q_heads with per-head selection) above 65535";
+    // a selection chunk stages its scores in LDS; kSplitsMax chunks must cover the context
+    if (k > 0 && (int64_t)s->max_seq_len > (int64_t)kSplitsMax * 4 * kScoreStagePerWave)
+        return "max_seq_len is too long for a selection layer (above 1048576)";
     // a paged chunk stages its block-table entries in LDS; kSplitsMax chunks must cover the context
     if (s->page_size > 0 && (int64_t)s->max_seq_len > (int64_t)kSplitsMax * paged_chunk_limit(s->page_size))
         return "max_seq_len is too long for this page size";
@@ -121,8 +124,9 @@ bool ragged_batch(const td_shape *s) {
     return s->total_seq_len > 0 && s->total_seq_len * 10 < dense_tokens * 9;
 }
 
-void plan_chunks(const td_ctx *ctx, const td_shape *s, bool sparse, int32_t waves, int32_t tokens,
+void plan_chunks(const td_ctx *ctx, const td_shape *s, int mode, int32_t waves, int32_t tokens,
                  int32_t *chunk, int32_t *splits) {
+    const bool sparse = mode == kSparse;
     // sparse launches are latency-bound: fewer, fatter workgroups shorten the ticket and merge tail
     int32_t target = (ctx->target_workgroups > 0 ? ctx->target_workgroups : kDefaultTargetWorkgroups) / (sparse ? 2 : 1);
     // a ragged batch leaves many chunks of the grid empty and the rest unevenly spread over
@@ -143,6 +147,7 @@ void plan_chunks(const td_ctx *ctx, const td_shape *s, bool sparse, int32_t wave
     c = (int32_t)align_up((size_t)c, kChunkGranule);
     if (sparse) c = std::min(c, kSparseChunkMax);
     if (!sparse && s->page_size > 0) c = (int32_t)std::min<int64_t>(c, paged_chunk_limit(s->page_size));
+    if (mode == kSelect) c = std::min(c, waves * kScoreStagePerWave);  // the chunk's scores are staged in LDS
     *chunk = c;
     *splits = ceil_div(tokens, c);
 }
@@ -205,7 +210,7 @@ td_status attend(td_ctx *ctx, const td_shape *s, int mode, const void *q, const 
     if (kv == 2 || kv == 4) waves = 4;
     if (kv == 3 || kv == 5) waves = 8;
     if (!attend_supports_waves(group, waves)) waves = 4;
-    plan_chunks(ctx, s, mode == kSparse, waves, mode == kSparse ? k : s->max_seq_len, &p.chunk, &p.num_splits);
+    plan_chunks(ctx, s, mode, waves, mode == kSparse ? k : s->max_seq_len, &p.chunk, &p.num_splits);
     const hipError_t e = mfma ? launch_attend_mfma(group, waves, mode, p, stream)
                               : launch_attend(s->dtype, s->head_dim, group, waves, mode, p, stream);
     if (e != hipSuccess) return fail(ctx, TD_ERR_HIP, "attention launch failed: %s", hipGetErrorString(e));

@@ -215,6 +215,20 @@ void attend_split_kernel(const AttendParams p) {
     }
     const float scale2 = p.scale * kLog2e;
 
+    // Selection layers with one score row per KV head collect the chunk's scores in LDS and write
+    // them with one contiguous burst after the loop: writes that trickle out between the
+    // streaming reads make HBM switch direction and row all the time (34 us per 16 MiB of
+    // scores, measured).  The launch plan keeps such chunks within W * kScoreStagePerWave tokens.
+    // The stage shares its LDS with the tail's state buffers, which are used only after it has
+    // been written out.
+    constexpr int RG = W * TPW;          // row groups per workgroup
+    constexpr int GC = G < 4 ? G : 4;    // heads per pass of the tail
+    using Tail = TailShared<D, GC, RG, T>;
+    constexpr size_t kStageBytes = MODE == kSelect ? W * kScoreStagePerWave * sizeof(float) : 0;
+    __shared__ __align__(16) char lds_tail[sizeof(Tail) > kStageBytes ? sizeof(Tail) : kStageBytes];
+    float *s_scores = reinterpret_cast<float *>(lds_tail);
+    const bool per_head = MODE == kSelect && p.select_rule == TD_SELECT_PER_HEAD;
+
     for (int base = t0 + wave * STEP; base < t1; base += TILE) {
         uint4 kraw[kUnroll], vraw[kUnroll];
         bool valid[kUnroll], fresh[kUnroll];
@@ -272,12 +286,11 @@ void attend_split_kernel(const AttendParams p) {
             // so the wave stores its kUnroll * TPW consecutive scores with one instruction
             static_assert(kUnroll <= LPR, "one writing lane per load");
             const int t = base + c * TPW + r;
-            if (p.select_rule != TD_SELECT_PER_HEAD) {
+            if (!per_head) {
                 float mine = gsum[0];
 #pragma unroll
                 for (int u = 1; u < kUnroll; ++u) mine = c == u ? gsum[u] : mine;
-                if (c < kUnroll && t < t1)
-                    p.scores[((int64_t)b * p.num_kv_heads + g) * p.score_stride + t] = mine;
+                if (c < kUnroll && t < t1) s_scores[t - t0] = mine;
             } else {  // one score row per query head: the head's own scaled logits
 #pragma unroll
                 for (int i = 0; i < G; ++i) {
@@ -318,11 +331,16 @@ void attend_split_kernel(const AttendParams p) {
         }
     }
 
+    if constexpr (MODE == kSelect) {
+        if (!per_head) {
+            write_staged_scores<T>(s_scores, t1 - t0, p.scores + ((int64_t)b * p.num_kv_heads + g) * p.score_stride + t0);
+            __syncthreads();  // the stage has been read; its LDS now takes the states
+        }
+    }
+
     // ---- merge the online-softmax states of the workgroup's row groups through LDS,
     // at most four heads at a time to bound the LDS footprint
-    constexpr int RG = W * TPW;  // row groups per workgroup
-    constexpr int GC = G < 4 ? G : 4;         // heads per pass
-    __shared__ TailShared<D, GC, RG, T> sm;
+    Tail &sm = *reinterpret_cast<Tail *>(lds_tail);
     const int rg = wave * TPW + r;
 #pragma unroll
     for (int h0 = 0; h0 < G; h0 += GC) {

@@ -196,6 +196,13 @@ void attend_mfma_kernel(const AttendParams p) {
     for (int e = 0; e < 8; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
     const float scale2 = p.scale * kLog2e;
 
+    // Selection layers with one score row per KV head collect the chunk's scores in LDS and write
+    // them with one contiguous burst after the loop: writes that trickle out between the
+    // streaming reads make HBM switch direction and row all the time (34 us per 16 MiB of
+    // scores, measured).  The launch plan keeps such chunks within W * kScoreStagePerWave tokens.
+    __shared__ float s_scores[MODE == kSelect ? W * kScoreStagePerWave : 1];
+    const bool per_head = MODE == kSelect && p.select_rule == TD_SELECT_PER_HEAD;
+
     for (int base = t0 + wave * STEP; base < t1; base += W * STEP) {
         uint4 kraw[kTiles][4], vraw[kTiles][4];
         bool valid[kTiles][4];
@@ -229,7 +236,6 @@ void attend_mfma_kernel(const AttendParams p) {
                 // per token, the group's scaled logits sit in lanes n16 = 0..G-1 of a 16-lane row
                 // (lanes >= G hold zeros): their sum, their maximum, or each head's own value
                 float gs[4];
-                const bool per_head = p.select_rule == TD_SELECT_PER_HEAD;
                 if (p.select_rule == TD_SELECT_GROUP_MAX) {
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
@@ -249,10 +255,19 @@ void attend_mfma_kernel(const AttendParams p) {
                         }
                     }
                 }
-                // lane (head, kb) holds the values of the four consecutive tokens base + 4kb ..: one
-                // 16-byte store where the row allows it, so a tile's 16 scores are one 64-byte write
-                if (per_head ? n16 < G : n16 == 0) {
-                    float *dst = score_row + (per_head ? (int64_t)n16 * p.score_stride : 0) + tok[x][0];
+                // lane (head, kb) holds the values of the four consecutive tokens base + 4kb ..
+                if (!per_head) {
+                    if (n16 == 0 && valid[x][0]) {  // a lane's valid tokens are a prefix of its four
+                        if (valid[x][3]) {
+                            *reinterpret_cast<float4 *>(&s_scores[tok[x][0] - t0]) = make_float4(gs[0], gs[1], gs[2], gs[3]);
+                        } else {
+#pragma unroll
+                            for (int i = 0; i < 4; ++i)
+                                if (valid[x][i]) s_scores[tok[x][i] - t0] = gs[i];
+                        }
+                    }
+                } else if (n16 < G) {  // one 16-byte store per head where the row allows it
+                    float *dst = score_row + (int64_t)n16 * p.score_stride + tok[x][0];
                     if (valid[x][3] && (reinterpret_cast<uintptr_t>(dst) & 15u) == 0) {
                         *reinterpret_cast<float4 *>(dst) = make_float4(gs[0], gs[1], gs[2], gs[3]);
                     } else {
@@ -306,6 +321,10 @@ void attend_mfma_kernel(const AttendParams p) {
                 acc[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_lo, vf, acc[e], 0, 0, 0);
             }
         }
+    }
+
+    if constexpr (MODE == kSelect) {
+        if (!per_head) write_staged_scores<T>(s_scores, t1 - t0, score_row + t0);
     }
 
     // ---- one state per wave into LDS, then the common tail

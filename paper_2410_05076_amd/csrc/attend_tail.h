@@ -61,6 +61,21 @@ __device__ __forceinline__ u32x2_t coherent_load8(__amdgpu_buffer_rsrc_t r, uint
     return __builtin_amdgcn_raw_buffer_load_b64(r, byte_offset, 0, kCachePolicySc1);
 }
 
+// Writes the n scores that the workgroup's waves have put into LDS to dst, 16 bytes per lane
+// where dst allows it.  Every thread of the workgroup calls it.
+template <int T>
+__device__ __forceinline__ void write_staged_scores(const float *staged, int n, float *dst) {
+    __syncthreads();
+    if ((reinterpret_cast<uintptr_t>(dst) & 15u) == 0) {
+        const int n4 = n & ~3;
+        for (int i = threadIdx.x * 4; i < n4; i += T * 4)
+            *reinterpret_cast<float4 *>(dst + i) = *reinterpret_cast<const float4 *>(staged + i);
+        for (int i = n4 + threadIdx.x; i < n; i += T) dst[i] = staged[i];
+    } else {
+        for (int i = threadIdx.x; i < n; i += T) dst[i] = staged[i];
+    }
+}
+
 // LDS needed by fold_states / finish_chunks for RG states of GC heads each, in a workgroup
 // of T threads.
 template <int D, int GC, int RG, int T>

@@ -9,6 +9,8 @@ namespace tidal {
 
 constexpr int kWave = 64;
 constexpr int kSplitsMax = 256;        // upper bound on token chunks per (sequence, KV head)
+// group scores of one chunk are staged in LDS (selection layers): tokens per wave of the workgroup
+constexpr int kScoreStagePerWave = 1024;
 constexpr int kPageStageMax = 1024;    // block-table entries of one chunk are staged in LDS
 constexpr int kSparseChunkMax = 2048;  // positions of one chunk are staged in LDS
 constexpr float kLog2e = 1.4426950408889634f;
