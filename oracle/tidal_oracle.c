@@ -221,18 +221,22 @@ int tdo_select(const tdo_shape *s, const void *q, const void *K, const void *V, 
  * query heads that share a KV head agree on one token set; tdo_select above
  * takes the sum of the group's scaled logits.  The alternatives:
  *   TDO_REDUCE_MAX  r_g[j] = max_{h in g} s_h[j], one rho per KV head;
+ *   TDO_REDUCE_MEAN_PROB  r_g[j] = (1/G) sum_{h in g} softmax(s_h)[j]: the mean of the heads'
+ *                   attention probabilities over the whole cache (the selection by "highest
+ *                   attention scores" of Sec. 3.1 read on probabilities), one rho per KV head;
  *   TDO_PER_HEAD    no reduction: rho_h = argTopK(s_h, k) for every query head,
  *                   the paper's literal rule; positions are [B][Hq][k] and a
  *                   sparse layer gathers each head's own rows (tdo_sparse_per_head).
  * scores (optional): fp32 [B][Hkv][max_seq_len] for the reductions,
  * [B][Hq][max_seq_len] for TDO_PER_HEAD.
  */
-enum { TDO_REDUCE_SUM = 0, TDO_REDUCE_MAX = 1, TDO_PER_HEAD = 2 };
+enum { TDO_REDUCE_SUM = 0, TDO_REDUCE_MAX = 1, TDO_PER_HEAD = 2, TDO_REDUCE_MEAN_PROB = 3 };
 
 int tdo_select_variant(const tdo_shape *s, int variant, const void *q, const void *K, const void *V,
                        int32_t k, float *out, int32_t *positions, float *scores) {
     if (variant == TDO_REDUCE_SUM) return tdo_select(s, q, K, V, k, out, positions, scores);
-    if (!shape_ok(s) || !positions || k < 1 || (variant != TDO_REDUCE_MAX && variant != TDO_PER_HEAD))
+    if (!shape_ok(s) || !positions || k < 1 ||
+        (variant != TDO_REDUCE_MAX && variant != TDO_PER_HEAD && variant != TDO_REDUCE_MEAN_PROB))
         return TDO_BAD_ARG;
     const int G = s->num_q_heads / s->num_kv_heads;
     const int64_t maxN = s->max_seq_len;
@@ -246,7 +250,18 @@ int tdo_select_variant(const tdo_shape *s, int variant, const void *q, const voi
             int N = s->seq_lens[b];
             float *r = (float *)malloc((size_t)N * sizeof(float));
             if (!r) { err = TDO_NO_MEM; continue; }
-            for (int j = 0; j < N; ++j) {
+            if (variant == TDO_REDUCE_MEAN_PROB) {
+                for (int j = 0; j < N; ++j) r[j] = 0.0f;
+                for (int i = 0; i < G; ++i) {
+                    const float *sl = logits + ((int64_t)b * s->num_q_heads + x * G + i) * maxN;
+                    float m = sl[0], l = 0.0f;
+                    for (int j = 1; j < N; ++j) if (sl[j] > m) m = sl[j];
+                    for (int j = 0; j < N; ++j) l += expf(sl[j] - m);
+                    for (int j = 0; j < N; ++j) r[j] += expf(sl[j] - m) / l;
+                }
+                for (int j = 0; j < N; ++j) r[j] /= (float)G;
+            }
+            for (int j = 0; j < N && variant != TDO_REDUCE_MEAN_PROB; ++j) {
                 if (variant == TDO_PER_HEAD) {
                     r[j] = logits[((int64_t)b * s->num_q_heads + x) * maxN + j];
                 } else {

@@ -110,12 +110,13 @@ def sparse(q, K, V, seq_lens, positions, sm_scale=0.0):
     return out
 
 
-REDUCE_SUM, REDUCE_MAX, PER_HEAD = 0, 1, 2
+REDUCE_SUM, REDUCE_MAX, PER_HEAD, REDUCE_MEAN_PROB = 0, 1, 2, 3
 
 
 def select_variant(q, K, V, seq_lens, k, variant, sm_scale=0.0):
     """Selection layer with another grouped-query rule: REDUCE_MAX (max of the group's logits, one
-    rho per KV head) or PER_HEAD (the paper's per-head rule: positions and scores per query head).
+    rho per KV head), REDUCE_MEAN_PROB (mean of the heads' softmax probabilities, one rho per KV head)
+    or PER_HEAD (the paper's per-head rule: positions and scores per query head).
     Returns (out, positions, scores)."""
     s, lens = _shape(q, K, V, seq_lens, sm_scale)
     rows = q.shape[1] if variant == PER_HEAD else K.shape[1]

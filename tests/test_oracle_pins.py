@@ -456,3 +456,27 @@ def test_append_then_attend_equals_attention_over_the_concatenated_cache():
     want = O.full(q, torch.cat([K[:, :, :9], kn[:, :, None]], 2), torch.cat([V[:, :, :9], vn[:, :, None]], 2), [10])
     O.append(K, V, kn, vn, [10])
     assert torch.equal(O.full(q, K, V, [10]), want)
+
+
+def test_mean_probability_reduction_against_float64_softmax():
+    q, K, V, lens = _small_gqa(8)
+    G = q.shape[1] // K.shape[1]
+    out, pos, sc = O.select_variant(q, K, V, lens, 5, O.REDUCE_MEAN_PROB)
+    assert torch.equal(out, O.full(q, K, V, lens))
+    for b, n in enumerate(lens):
+        for g in range(K.shape[1]):
+            p64 = torch.stack([torch.softmax((K[b, g, :n].double() @ q[b, g * G + i].double()) / math.sqrt(q.shape[2]), 0)
+                               for i in range(G)]).mean(0)
+            assert torch.allclose(sc[b, g, :n].double(), p64, atol=1e-6)
+            assert abs(sc[b, g, :n].sum().item() - 1.0) < 1e-5         # a mean of distributions is a distribution
+            assert pos[b, g].tolist() == sorted(torch.topk(p64, 5).indices.tolist())
+
+
+def test_mean_probability_equals_the_logit_rule_for_a_single_head():
+    # softmax preserves order (the paper's footnote to Sec. 3.1): same rho as top-k of the logits
+    g = torch.Generator().manual_seed(9)
+    q = torch.randn((1, 3, 8), generator=g)
+    K = torch.randn((1, 3, 30, 8), generator=g)
+    V = torch.randn((1, 3, 30, 8), generator=g)
+    _, pos, _ = O.select_variant(q, K, V, [30], 6, O.REDUCE_MEAN_PROB)
+    assert torch.equal(pos, O.select(q, K, V, [30], 6)[1])
