@@ -55,7 +55,7 @@ def main():
                     help="inside a page: [KV head][slot][d] or [slot][KV head][d]")
     ap.add_argument("--append", action="store_true",
                     help="time td_decode_step_append: every layer also appends the current token's k, v to its cache")
-    ap.add_argument("--selection", default="sum", choices=["sum", "max", "per_head"],
+    ap.add_argument("--selection", default="sum", choices=["sum", "max", "per_head", "mean_prob"],
                     help="grouped-query selection rule (td_shape.selection)")
     ap.add_argument("--tune", default="", help="target_workgroups,min_chunk_dense,min_chunk_sparse,max_splits,kernel_variant (0 = default)")
     args = ap.parse_args()
@@ -83,7 +83,8 @@ def main():
 
     lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=dev)
     n_sel = sum(1 for x in w.schedule if x == W.SELECT)
-    selection = {"sum": tidal.SELECT_GROUP_SUM, "max": tidal.SELECT_GROUP_MAX, "per_head": tidal.SELECT_PER_HEAD}[args.selection]
+    selection = {"sum": tidal.SELECT_GROUP_SUM, "max": tidal.SELECT_GROUP_MAX, "per_head": tidal.SELECT_PER_HEAD,
+                 "mean_prob": tidal.SELECT_GROUP_MEAN_PROB}[args.selection]
     sel_rows = w.num_q_heads if args.selection == "per_head" else w.num_kv_heads
     sets, all_news = [], []
     for c in range(copies):

@@ -85,12 +85,21 @@ typedef enum { TD_BF16 = 0, TD_F32 = 1 } td_dtype;
  * attention head, Sec. 3.1, and is silent on grouped-query attention):
  *   TD_SELECT_GROUP_SUM  top-k over the per-token sum of the group's scaled logits (default);
  *   TD_SELECT_GROUP_MAX  top-k over their per-token maximum;
+ *   TD_SELECT_GROUP_MEAN_PROB  top-k over the mean of the heads' attention probabilities
+ *                        softmax(s_h)[j] over the whole cache; needs the final softmax
+ *                        statistics, so the scores are formed in a second small pass over the
+ *                        per-head logits (group_scores then holds probabilities);
  *   TD_SELECT_PER_HEAD   no agreement: every query head selects by its own logits, the
  *                        paper's literal rule.  positions (and group_scores) then have one
  *                        row per QUERY head, [batch][num_q_heads][k], and a sparse layer
  *                        gathers each head's own rows: group-size times the gather traffic.
- * All three coincide when num_q_heads == num_kv_heads. */
-typedef enum { TD_SELECT_GROUP_SUM = 0, TD_SELECT_GROUP_MAX = 1, TD_SELECT_PER_HEAD = 2 } td_selection;
+ * All of them select the same tokens when num_q_heads == num_kv_heads. */
+typedef enum {
+    TD_SELECT_GROUP_SUM = 0,
+    TD_SELECT_GROUP_MAX = 1,
+    TD_SELECT_PER_HEAD = 2,
+    TD_SELECT_GROUP_MEAN_PROB = 3
+} td_selection;
 
 /* Layer kinds of Alg. 1. */
 typedef enum { TD_LAYER_DENSE = 0, TD_LAYER_SELECT = 1, TD_LAYER_SPARSE = 2 } td_layer_kind;

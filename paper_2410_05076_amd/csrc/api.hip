@@ -67,7 +67,7 @@ const char *shape_problem(const td_shape *s, int32_t k, td_status *code) {
         return "KV strides must be multiples of 8 elements";
     if (k > kSparseChunkMax * kSplitsMax) return "k is larger than 524288";
     if (s->total_seq_len < 0) return "total_seq_len is negative";
-    if (s->selection < TD_SELECT_GROUP_SUM || s->selection > TD_SELECT_PER_HEAD) return "selection is not a td_selection";
+    if (s->selection < TD_SELECT_GROUP_SUM || s->selection > TD_SELECT_GROUP_MEAN_PROB) return "selection is not a td_selection";
     if (s->page_size < 0 || (s->page_size & (s->page_size - 1))) return "page_size is not a power of two";
     if (s->page_size > 0) {
         if (!s->block_table) return "block_table is NULL";
@@ -97,7 +97,7 @@ bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) !
 // Workspace: [ticket counters, fixed size][top-k scratch][chunk partials][group scores].
 // Only the counters carry state from one call to the next (they are zero between launches).
 struct Workspace {
-    size_t counters, topk, part_acc, part_ml, scores, total;
+    size_t counters, topk, part_acc, part_ml, scores, head_logits, ml_final, total;
     int64_t score_stride;
 };
 
@@ -114,7 +114,11 @@ Workspace workspace_layout(const td_shape *s, int32_t k) {
     w.part_ml = align_up(w.part_acc + heads * kSplitsMax * s->head_dim * sizeof(float), 256);
     w.scores = align_up(w.part_ml + heads * kSplitsMax * 2 * sizeof(float), 256);
     const size_t score_bytes = k > 0 ? (size_t)rows * w.score_stride * sizeof(float) : 0;
-    w.total = align_up(w.scores + score_bytes, 256);
+    // the mean-of-probabilities rule also keeps every head's logits and final softmax statistics
+    const bool two_pass = k > 0 && s->selection == TD_SELECT_GROUP_MEAN_PROB;
+    w.head_logits = align_up(w.scores + score_bytes, 256);
+    w.ml_final = align_up(w.head_logits + (two_pass ? heads * w.score_stride * sizeof(float) : 0), 256);
+    w.total = align_up(w.ml_final + (two_pass ? heads * 2 * sizeof(float) : 0), 256);
     return w;
 }
 
@@ -154,7 +158,8 @@ void plan_chunks(const td_ctx *ctx, const td_shape *s, int mode, int32_t waves, 
 
 td_status attend(td_ctx *ctx, const td_shape *s, int mode, const void *q, const void *K, const void *V,
                  const int32_t *positions, int32_t k, float *scores, int64_t score_stride, void *out,
-                 hipStream_t stream, const void *k_new = nullptr, const void *v_new = nullptr) {
+                 hipStream_t stream, const void *k_new = nullptr, const void *v_new = nullptr,
+                 int32_t score_rule = -1, float *ml_out = nullptr) {
     const Workspace w = workspace_layout(s, mode == kDense ? 0 : k);
     AttendParams p;
     memset(&p, 0, sizeof p);
@@ -180,7 +185,8 @@ td_status attend(td_ctx *ctx, const td_shape *s, int mode, const void *q, const 
     p.batch = s->batch;
     p.num_q_heads = s->num_q_heads;
     p.num_kv_heads = s->num_kv_heads;
-    p.select_rule = s->selection;
+    p.select_rule = score_rule >= 0 ? score_rule : s->selection;  // what the selection mode writes to `scores`
+    p.ml_out = ml_out;
     p.kv_div = 1;
     p.max_seq_len = s->max_seq_len;
     p.k = k;
@@ -238,12 +244,31 @@ td_status select_tokens(td_ctx *ctx, const td_shape *s, const void *q, const voi
     const Workspace w = workspace_layout(s, k);
     float *scores = group_scores ? group_scores : reinterpret_cast<float *>(ctx->workspace + w.scores);
     const int64_t stride = group_scores ? (int64_t)s->max_seq_len : w.score_stride;
-    td_status st = attend(ctx, s, kSelect, q, K, V, nullptr, k, scores, stride, out, stream, k_new, v_new);
-    if (st != TD_OK) return st;
+    int64_t stride_for_topk = stride;
+    td_status st;
+    if (s->selection == TD_SELECT_GROUP_MEAN_PROB) {
+        // pass 1 writes every head's logits and final (max, sum); pass 2 forms the group's mean probability
+        float *logits = reinterpret_cast<float *>(ctx->workspace + w.head_logits);
+        float *ml = reinterpret_cast<float *>(ctx->workspace + w.ml_final);
+        st = attend(ctx, s, kSelect, q, K, V, nullptr, k, logits, w.score_stride, out, stream, k_new, v_new,
+                    TD_SELECT_PER_HEAD, ml);
+        if (st != TD_OK) return st;
+        // top-k ranks log2 of the probabilities, kept in the workspace; the caller's buffer gets the probabilities
+        float *rank = reinterpret_cast<float *>(ctx->workspace + w.scores);
+        const hipError_t pe = launch_mean_prob(logits, w.score_stride, ml, s->seq_lens, s->batch, s->num_kv_heads,
+                                               s->num_q_heads / s->num_kv_heads, s->max_seq_len, rank, w.score_stride,
+                                               group_scores, s->max_seq_len, stream);
+        if (pe != hipSuccess) return fail(ctx, TD_ERR_HIP, "mean-probability launch failed: %s", hipGetErrorString(pe));
+        scores = rank;
+        stride_for_topk = w.score_stride;
+    } else {
+        st = attend(ctx, s, kSelect, q, K, V, nullptr, k, scores, stride, out, stream, k_new, v_new);
+        if (st != TD_OK) return st;
+    }
     // the selection kernel clears the top-k state of its KV head's row on the way; with one row
     // per query head the state is cleared by top-k's own reset instead
     const int32_t rows = selection_rows(s);
-    const hipError_t e = launch_topk(scores, stride, s->batch * rows, s->seq_lens, rows, s->max_seq_len, k, positions,
+    const hipError_t e = launch_topk(scores, stride_for_topk, s->batch * rows, s->seq_lens, rows, s->max_seq_len, k, positions,
                                      ctx->workspace + w.topk, s->selection == TD_SELECT_PER_HEAD, stream);
     if (e != hipSuccess) return fail(ctx, TD_ERR_HIP, "top-k launch failed: %s", hipGetErrorString(e));
     return TD_OK;

@@ -108,6 +108,10 @@ __device__ __forceinline__ void fold_states(const AttendParams &p, TailShared<D,
         const int64_t head = (int64_t)b * p.num_q_heads + g * G + h0 + i;
         if (ns == 1) {  // the only chunk: finish here, no partials
             store_out<DT>(p.out, head * D + ch, ls > 0.f ? as / ls : 0.f);
+            if (p.ml_out && ch == 0) {
+                p.ml_out[head * 2] = mx;
+                p.ml_out[head * 2 + 1] = ls;
+            }
         } else {
             const int64_t slot = head * p.num_splits + split;
             publish(&p.part_acc[slot * D + ch], as);
@@ -208,6 +212,10 @@ __device__ __forceinline__ void finish_chunks(const AttendParams &p, TailShared<
         }
     }
     if (sg == 0) {
+        if (p.ml_out && c4 == 0) {
+            p.ml_out[head * 2] = mm;
+            p.ml_out[head * 2 + 1] = ll;
+        }
         const float inv = ll > 0.f ? 1.f / ll : 0.f;
         const int64_t oi = head * D + c4 * 4;
         store_out<DT>(p.out, oi, aa.x * inv);

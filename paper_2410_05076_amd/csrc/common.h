@@ -46,6 +46,7 @@ struct AttendParams {
     int32_t *counters;         // [B][Hkv] chunks finished so far; zero between launches
     void *topk_scratch;        // select: TopkRow [B][Hkv], histogram and candidate count cleared here
     void *out;                 // [B][Hq][D]
+    float *ml_out;             // optional [B][Hq][2]: final softmax maximum (log2 units) and sum per head
     int64_t stride_batch, stride_head, stride_tok;  // elements; paged: stride_batch is the page stride
     const int32_t *block_table;  // paged cache: [B][bt_stride] page ids, else nullptr
     int64_t bt_stride;
@@ -71,6 +72,14 @@ bool attend_supports_waves(int group, int waves);
 hipError_t launch_attend(int dtype, int head_dim, int group, int waves, int mode, const AttendParams &p,
                          hipStream_t stream);
 hipError_t launch_attend_mfma(int group, int waves, int mode, const AttendParams &p, hipStream_t stream);
+
+// Mean-of-probabilities rule: prob[b][g][j] = mean over the group's heads of
+// exp2(logit[b][h][j] * log2(e) - m_h) / l_h, from the per-head scaled logits and the final
+// (m_h, l_h) that a selection launch leaves in ml.  rank receives log2(prob), which top-k ranks;
+// prob (optional) receives the probabilities.
+hipError_t launch_mean_prob(const float *head_logits, int64_t logit_stride, const float *ml, const int32_t *seq_lens,
+                            int32_t batch, int32_t num_kv_heads, int32_t group, int32_t max_seq_len, float *rank,
+                            int64_t rank_stride, float *prob, int64_t prob_stride, hipStream_t stream);
 
 // argTopK over rows of fp32 scores.  scratch: topk_scratch_bytes(rows, max_len) bytes; reset
 // clears the per-row state first (not needed right after a selection attention launch).

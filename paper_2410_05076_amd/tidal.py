@@ -91,7 +91,7 @@ def _dtype_code(t):
     raise TypeError("q, K, V must be bfloat16 or float32, got %s" % t)
 
 
-SELECT_GROUP_SUM, SELECT_GROUP_MAX, SELECT_PER_HEAD = 0, 1, 2
+SELECT_GROUP_SUM, SELECT_GROUP_MAX, SELECT_PER_HEAD, SELECT_GROUP_MEAN_PROB = 0, 1, 2, 3
 
 
 def make_shape(q, K, seq_lens, sm_scale=0.0, total_seq_len=0, selection=0):

@@ -38,8 +38,11 @@ def check_output(gpu_out, oracle_out, what=""):
     return max_abs, rel
 
 
-def check_positions(gpu_pos, oracle_scores, seq_lens, k, what=""):
-    """gpu_pos [B][Hkv][k] int32, oracle_scores [B][Hkv][N_max] fp32 (oracle's group sums)."""
+def check_positions(gpu_pos, oracle_scores, seq_lens, k, what="", relative_band=False):
+    """gpu_pos [B][Hkv][k] int32, oracle_scores [B][Hkv][N_max] fp32 (oracle's group scores).
+
+    relative_band: tau = 1e-4 * |s*| without the floor of 1, for scores that are probabilities
+    (far below 1, where the floor would make the band wider than the scores themselves)."""
     gp = gpu_pos.detach().cpu()
     B, H, _ = gp.shape
     exact = 0
@@ -54,7 +57,7 @@ def check_positions(gpu_pos, oracle_scores, seq_lens, k, what=""):
             assert (sel[1:] > sel[:-1]).all(), "%s: not strictly ascending at (%d,%d)" % (what, b, h)
             r = oracle_scores[b, h, :n]
             kth = torch.topk(r, ke).values[-1]
-            tau = BAND * max(abs(kth.item()), 1.0)
+            tau = BAND * (abs(kth.item()) if relative_band else max(abs(kth.item()), 1.0))
             chosen = torch.zeros(n, dtype=torch.bool)
             chosen[sel] = True
             must = r > kth + tau

@@ -79,7 +79,7 @@ def test_validate_rejects_paged(over, code):
     (dict(kv_stride_tok=64), 1, tidal.ERR_INVALID_ARG),
     (dict(kv_stride_tok=132), 1, tidal.ERR_INVALID_ARG),
     (dict(total_seq_len=-5), 1, tidal.ERR_INVALID_ARG),
-    (dict(selection=3), 1, tidal.ERR_INVALID_ARG),
+    (dict(selection=4), 1, tidal.ERR_INVALID_ARG),
     (dict(selection=-1), 1, tidal.ERR_INVALID_ARG),
     (dict(), 600000, tidal.ERR_INVALID_ARG),
     (dict(head_dim=96, kv_stride_tok=96), 1, tidal.ERR_UNSUPPORTED),

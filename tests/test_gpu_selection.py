@@ -11,7 +11,8 @@ from parity_util import check_output, check_positions, same_positions
 from test_gpu_parity import DEV, device_layers, host, say
 
 pytestmark = pytest.mark.gpu
-RULES = {"max": (tidal.SELECT_GROUP_MAX, O.REDUCE_MAX), "per_head": (tidal.SELECT_PER_HEAD, O.PER_HEAD)}
+RULES = {"max": (tidal.SELECT_GROUP_MAX, O.REDUCE_MAX), "per_head": (tidal.SELECT_PER_HEAD, O.PER_HEAD),
+         "mean_prob": (tidal.SELECT_GROUP_MEAN_PROB, O.REDUCE_MEAN_PROB)}
 
 
 def run_rule(w, rule, kernel_variant=0, page_size=0):
@@ -40,11 +41,17 @@ def run_rule(w, rule, kernel_variant=0, page_size=0):
     torch.cuda.synchronize()
     o_out, o_pos, o_scores = O.select_variant(host(q1), host(K1), host(V1), w.seq_lens, w.k, o_rule)
     check_output(out, o_out, tag + " select")
+    prob = rule == "mean_prob"      # scores are probabilities: compare relative to the row's largest
     for b, n in enumerate(w.seq_lens):
-        d = (host(scores)[b, :, :n] - o_scores[b, :, :n]).abs().max().item()
-        assert d <= 1e-4 * max(1.0, o_scores[b, :, :n].abs().max().item()), "%s scores %g" % (tag, d)
+        gs, os_ = host(scores)[b, :, :n], o_scores[b, :, :n]
+        if prob:
+            d = ((gs - os_).abs().max(dim=-1).values / os_.max(dim=-1).values).max().item()
+            assert d <= 1e-4, "%s probabilities off by %g of the row maximum" % (tag, d)
+        else:
+            d = (gs - os_).abs().max().item()
+            assert d <= 1e-4 * max(1.0, os_.abs().max().item()), "%s scores %g" % (tag, d)
         assert torch.isnan(host(scores)[b, :, n:]).all()
-    check_positions(pos, o_scores, w.seq_lens, w.k, tag)
+    check_positions(pos, o_scores, w.seq_lens, w.k, tag, relative_band=prob)
     say("%s: positions identical to oracle: %s" % (tag, same_positions(pos, o_pos)))
     pos2, out2 = torch.full_like(pos, -7), torch.full_like(q1, float("nan"))
     td.select_tokens(shape, q1, dK1, dV1, w.k, out2, pos2)      # scores in the workspace
@@ -59,7 +66,7 @@ def run_rule(w, rule, kernel_variant=0, page_size=0):
     td.close()
 
 
-@pytest.mark.parametrize("rule", ["max", "per_head"])
+@pytest.mark.parametrize("rule", ["max", "per_head", "mean_prob"])
 @pytest.mark.parametrize("name,over", [
     ("c2", dict(context=4099, k=300)),                                  # G = 4, matrix-core kernel
     ("c6", dict(context=3000, k=200)),                                  # G = 8
@@ -72,13 +79,13 @@ def test_selection_rules(name, over, rule):
     run_rule(W.workload(name, **over), rule)
 
 
-@pytest.mark.parametrize("rule", ["max", "per_head"])
+@pytest.mark.parametrize("rule", ["max", "per_head", "mean_prob"])
 @pytest.mark.parametrize("variant", [2, 3, 4])
 def test_selection_rules_on_each_kernel(rule, variant):
     run_rule(W.workload("c2", context=4500, k=300), rule, kernel_variant=variant)
 
 
-@pytest.mark.parametrize("rule", ["max", "per_head"])
+@pytest.mark.parametrize("rule", ["max", "per_head", "mean_prob"])
 def test_selection_rules_paged(rule):
     run_rule(W.workload("c2", context=4099, k=300), rule, page_size=16)
     run_rule(W.workload("c1", context=1500, k=128), rule, page_size=8)
