@@ -43,6 +43,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=6)
     ap.add_argument("--workload", default="c2", choices=sorted(DESCRIPTIONS))
     ap.add_argument("--k", type=int, default=0, help="token budget override (c5 sweep)")
+    ap.add_argument("--num-q-heads", type=int, default=0, help="override the workload's query head count")
+    ap.add_argument("--num-kv-heads", type=int, default=0, help="override the workload's KV head count")
+    ap.add_argument("--context", type=int, default=0, help="override the context length of every sequence")
     ap.add_argument("--copies", type=int, default=0, help="independent input copies to rotate over")
     ap.add_argument("--no-graph", action="store_true", help="enqueue eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -74,6 +77,12 @@ def main():
         print(json.dumps({"hbm_probe": hbm_probe(torch, tidal, dev)}), flush=True)
         return
     over = {"k": args.k} if args.k else {}
+    if args.num_q_heads:
+        over["num_q_heads"] = args.num_q_heads
+    if args.num_kv_heads:
+        over["num_kv_heads"] = args.num_kv_heads
+    if args.context:
+        over["context"] = args.context
     w = W.workload(args.workload, **over)
     step_bytes = w.algorithmic_bytes_per_step()
     cache_bytes = w.num_layers * 2 * w.batch * w.num_kv_heads * w.max_seq_len * w.head_dim * w.elem_bytes
@@ -241,7 +250,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": DESCRIPTIONS[w.name] + (", cache in pages of %d tokens (%s) behind a shuffled block table"
+        "config": {"workload": DESCRIPTIONS[w.name] + ("".join(", %s overridden to %s" % (a, b) for a, b in sorted(over.items()) if a != "k")) + (", cache in pages of %d tokens (%s) behind a shuffled block table"
                                                        % (args.page_size, args.page_layout) if args.page_size else ""),
                    "k": w.k, "selection": args.selection, "input_copies_rotated": copies,
                    "launch": ("hip graph replay of " if use_graph else "eager ") +

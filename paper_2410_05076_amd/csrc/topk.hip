@@ -161,6 +161,10 @@ __global__ __launch_bounds__(kTopkThreads) void topk_hist_kernel(const float *sc
         lo = fminf(lo, s_lo[w]);
         hi = fmaxf(hi, s_hi[w]);
     }
+    // The k largest live in the upper tail, which 256 samples do not reach (their maximum is
+    // about the row's 99.6th percentile): the binned range extends above the sampled maximum
+    // by the sampled width, so that the tail is resolved instead of piling up in the last bin.
+    hi += hi - lo;
     const float inv = hi > lo ? (float)kBins / (hi - lo) : 0.f;
     if (blockIdx.x == 0 && tid == 0) {
         s.state->lo = lo;
