@@ -135,3 +135,41 @@ def test_append_paged(page_size, layout):
 def test_append_with_per_head_selection():
     run_append(W.workload("c3", context=3000, k=200, tau=64.0, num_kv_heads=8), (S, P, P),
                selection=tidal.SELECT_PER_HEAD)
+
+
+def test_append_step_as_a_hip_graph():
+    # the fused append rewrites the same cache row on every replay: replays reproduce the eager result
+    w = W.workload("c3", context=3000, k=200, tau=64.0, num_kv_heads=8)
+    schedule = (D, S, P, P)
+    layers = device_layers(w, range(len(schedule)))
+    qs = [q for q, _, _ in layers]
+    news = [split_last_row(w, K, V) for _, K, V in layers]
+    Ks, Vs = [K for _, K, _ in layers], [V for _, _, V in layers]
+    lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=DEV)
+    shape = tidal.make_shape(qs[0], Ks[0], lens)
+    td = tidal.Tidal(shape, w.k)
+    outs = [torch.full_like(q, float("nan")) for q in qs]
+    pos = torch.full((1, w.batch, w.num_kv_heads, w.k), -7, dtype=torch.int32, device=DEV)
+    args = (shape, schedule, qs, [a for a, _ in news], [b for _, b in news], Ks, Vs, w.k, outs, pos)
+    td.decode_step_append(*args)
+    torch.cuda.synchronize()
+    eager_outs, eager_pos = [o.clone() for o in outs], pos.clone()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        td.decode_step_append(*args)
+    for rep in range(3):
+        for o in outs:
+            o.fill_(float("nan"))
+        pos.fill_(-7)
+        for K, V in zip(Ks, Vs):            # forget the appended row: the replay must write it again
+            K[0, :, w.seq_lens[0] - 1] = float("nan")
+            V[0, :, w.seq_lens[0] - 1] = float("nan")
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(pos, eager_pos), "replay %d" % rep
+        for a, b in zip(outs, eager_outs):
+            assert torch.equal(a, b), "replay %d" % rep
+        for (kn, vn), K, V in zip(news, Ks, Vs):
+            assert torch.equal(K[0, :, w.seq_lens[0] - 1], kn[0]) and torch.equal(V[0, :, w.seq_lens[0] - 1], vn[0])
+    td.close()
