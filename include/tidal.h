@@ -197,6 +197,20 @@ td_status td_decode_step_append(td_ctx *ctx, const td_shape *shape, int32_t num_
                                 void *const *K_layers, void *const *V_layers, int32_t k,
                                 void *const *out_layers, int32_t *positions, void *hip_stream);
 
+/* Host-only: how a layer of kind `layer_kind` (td_layer_kind) would be launched for this shape
+ * and budget - nothing is enqueued.  ctx may be NULL (default tuning).  For sizing, logging
+ * and tests of the launch planning. */
+typedef struct td_launch_plan {
+    int32_t chunk_tokens;        /* tokens (or selected positions) per workgroup */
+    int32_t chunks_per_row;      /* workgroups per (sequence, KV head) */
+    int32_t waves_per_workgroup; /* 4 or 8 wave64s */
+    int32_t matrix_core;         /* 1: the MFMA kernel, 0: the vector-ALU kernel */
+    int32_t grid_rows;           /* batch * KV heads (query heads for a per-head sparse layer) */
+    int64_t workgroups;          /* grid_rows * chunks_per_row, empty chunks of short sequences included */
+} td_launch_plan;
+td_status td_plan_launch(const td_ctx *ctx, const td_shape *shape, int32_t layer_kind, int32_t k,
+                         td_launch_plan *plan);
+
 /* Tuning knobs for measurement sweeps (0 keeps the default): target number of
  * workgroups per attention launch, the smallest token chunk per workgroup for
  * full and for sparse attention, the largest number of chunks per

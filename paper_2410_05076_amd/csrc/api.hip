@@ -132,6 +132,8 @@ void plan_chunks(const td_ctx *ctx, const td_shape *s, int mode, int32_t waves, 
                  int32_t *chunk, int32_t *splits) {
     const bool sparse = mode == kSparse;
     // sparse launches are latency-bound: fewer, fatter workgroups shorten the ticket and merge tail
+    const td_ctx defaults;
+    if (!ctx) ctx = &defaults;
     int32_t target = (ctx->target_workgroups > 0 ? ctx->target_workgroups : kDefaultTargetWorkgroups) / (sparse ? 2 : 1);
     // a ragged batch leaves many chunks of the grid empty and the rest unevenly spread over
     // the CUs: smaller chunks balance it
@@ -154,6 +156,45 @@ void plan_chunks(const td_ctx *ctx, const td_shape *s, int mode, int32_t waves, 
     if (mode == kSelect) c = std::min(c, waves * kScoreStagePerWave);  // the chunk's scores are staged in LDS
     *chunk = c;
     *splits = ceil_div(tokens, c);
+}
+
+// What one attention launch will look like: decided on the host from the shape alone.
+struct LaunchPlan {
+    int32_t chunk, splits;       // tokens per workgroup, workgroups per grid row
+    int32_t waves;               // wave64s per workgroup
+    int32_t group;               // query heads served by a grid row
+    int32_t grid_rows_per_seq;   // KV heads, or query heads when a sparse layer follows the per-head rule
+    bool matrix_core;
+};
+
+LaunchPlan plan_launch(const td_ctx *ctx, const td_shape *s, int mode, int32_t k) {
+    LaunchPlan plan;
+    plan.group = s->num_q_heads / s->num_kv_heads;
+    plan.grid_rows_per_seq = s->num_kv_heads;
+    if (mode == kSparse && s->selection == TD_SELECT_PER_HEAD) {
+        plan.grid_rows_per_seq = s->num_q_heads;
+        plan.group = 1;
+    }
+    // The matrix-core kernel (bf16, head_dim 128) serves up to 16 query heads from one K/V tile
+    // for the same instruction count.  Measured per launch against the vector-ALU kernel: groups
+    // of eight 28.6 vs 43.3 us (full) and 11.2 vs 15.1 us (sparse); groups of four 26.6 vs 28.0 us
+    // and 9.5 vs 10.0 us at 32K tokens, 328 vs 351 us at 4 x 128K; a single head per KV head
+    // 319-327 vs 334 us for a full layer, but 20.0 vs 18.6 us for a sparse one, where most of the
+    // 16-row tile is empty.  Hence: every layer kind for groups of four and more, full layers
+    // only for smaller groups.
+    const bool mfma_ok = s->dtype == TD_BF16 && s->head_dim == 128;
+    const int32_t kv = ctx ? ctx->kernel_variant : 0;
+    plan.matrix_core = mfma_ok && (kv == 1 || kv == 4 || kv == 5 || (kv == 0 && (plan.group >= 4 || mode == kDense)));
+    // Workgroup size.  Full and selection layers use eight waves (half as many partials to merge
+    // across workgroups; measured 3 to 9 % faster per launch on the uniform workloads) unless the
+    // batch is ragged, where many small chunks balance better; sparse layers are one short burst
+    // per wave and finish sooner with four.
+    plan.waves = mode != kSparse && !ragged_batch(s) ? 8 : 4;
+    if (kv == 2 || kv == 4) plan.waves = 4;
+    if (kv == 3 || kv == 5) plan.waves = 8;
+    if (!attend_supports_waves(plan.group, plan.waves)) plan.waves = 4;
+    plan_chunks(ctx, s, mode, plan.waves, mode == kSparse ? k : s->max_seq_len, &plan.chunk, &plan.splits);
+    return plan;
 }
 
 td_status attend(td_ctx *ctx, const td_shape *s, int mode, const void *q, const void *K, const void *V,
@@ -191,32 +232,16 @@ td_status attend(td_ctx *ctx, const td_shape *s, int mode, const void *q, const 
     p.max_seq_len = s->max_seq_len;
     p.k = k;
     p.scale = s->sm_scale > 0.f ? s->sm_scale : 1.0f / sqrtf((float)s->head_dim);
-    int group = s->num_q_heads / s->num_kv_heads;
-    if (mode == kSparse && s->selection == TD_SELECT_PER_HEAD) {
+    const LaunchPlan plan = plan_launch(ctx, s, mode, k);
+    if (plan.grid_rows_per_seq != s->num_kv_heads) {
         // one grid row per query head, each gathering its own rho from KV head (row / group)
-        p.kv_div = group;
+        p.kv_div = s->num_q_heads / s->num_kv_heads;
         p.num_kv_heads = s->num_q_heads;
-        group = 1;
     }
-    // The matrix-core kernel (bf16, head_dim 128) serves up to 16 query heads from one K/V tile
-    // for the same instruction count.  Measured per launch against the vector-ALU kernel: groups
-    // of eight 28.6 vs 43.3 us (full) and 11.2 vs 15.1 us (sparse); groups of four 26.6 vs 28.0 us
-    // and 9.5 vs 10.0 us at 32K tokens, 328 vs 351 us at 4 x 128K; a single head per KV head
-    // 319-327 vs 334 us for a full layer, but 20.0 vs 18.6 us for a sparse one, where most of the
-    // 16-row tile is empty.  Hence: every layer kind for groups of four and more, full layers
-    // only for smaller groups.
-    const bool mfma_ok = s->dtype == TD_BF16 && s->head_dim == 128;
-    const int32_t kv = ctx->kernel_variant;
-    const bool mfma = mfma_ok && (kv == 1 || kv == 4 || kv == 5 || (kv == 0 && (group >= 4 || mode == kDense)));
-    // Workgroup size of the vector-ALU kernel.  Full and selection layers use eight waves (half
-    // as many partials to merge across workgroups; measured 3 to 9 % faster per launch on the
-    // uniform workloads) unless the batch is ragged, where many small chunks balance better;
-    // sparse layers are one short burst per wave and finish sooner with four.
-    int waves = mode != kSparse && !ragged_batch(s) ? 8 : 4;
-    if (kv == 2 || kv == 4) waves = 4;
-    if (kv == 3 || kv == 5) waves = 8;
-    if (!attend_supports_waves(group, waves)) waves = 4;
-    plan_chunks(ctx, s, mode, waves, mode == kSparse ? k : s->max_seq_len, &p.chunk, &p.num_splits);
+    p.chunk = plan.chunk;
+    p.num_splits = plan.splits;
+    const int group = plan.group, waves = plan.waves;
+    const bool mfma = plan.matrix_core;
     const hipError_t e = mfma ? launch_attend_mfma(group, waves, mode, p, stream)
                               : launch_attend(s->dtype, s->head_dim, group, waves, mode, p, stream);
     if (e != hipSuccess) return fail(ctx, TD_ERR_HIP, "attention launch failed: %s", hipGetErrorString(e));
@@ -367,6 +392,21 @@ td_status td_destroy(td_ctx *ctx) {
     if (ctx->workspace) e = hipFree(ctx->workspace);
     delete ctx;
     return e == hipSuccess ? TD_OK : TD_ERR_HIP;
+}
+
+td_status td_plan_launch(const td_ctx *ctx, const td_shape *shape, int32_t layer_kind, int32_t k, td_launch_plan *plan) {
+    if (!plan || layer_kind < TD_LAYER_DENSE || layer_kind > TD_LAYER_SPARSE) return TD_ERR_INVALID_ARG;
+    td_status code;
+    if (shape_problem(shape, k, &code)) return code;
+    if (layer_kind != TD_LAYER_DENSE && k < 1) return TD_ERR_INVALID_ARG;
+    const LaunchPlan lp = plan_launch(ctx, shape, layer_kind, k);
+    plan->chunk_tokens = lp.chunk;
+    plan->chunks_per_row = lp.splits;
+    plan->waves_per_workgroup = lp.waves;
+    plan->matrix_core = lp.matrix_core ? 1 : 0;
+    plan->grid_rows = shape->batch * lp.grid_rows_per_seq;
+    plan->workgroups = (int64_t)plan->grid_rows * lp.splits;
+    return TD_OK;
 }
 
 td_status td_set_tuning(td_ctx *ctx, int32_t target_workgroups, int32_t min_chunk_dense,

@@ -19,7 +19,7 @@ LAYER_DENSE, LAYER_SELECT, LAYER_SPARSE = 0, 1, 2
 
 EXPORTS = ("td_validate", "td_workspace_bytes", "td_topk_workspace_bytes", "td_create", "td_destroy", "td_full_attend",
            "td_select_tokens", "td_sparse_attend", "td_topk", "td_decode_step", "td_decode_step_append",
-           "td_set_tuning", "td_probe_stream",
+           "td_plan_launch", "td_set_tuning", "td_probe_stream",
            "td_status_string", "td_last_error")
 
 
@@ -35,6 +35,22 @@ class Shape(ctypes.Structure):
                 ("page_size", ctypes.c_int32), ("num_pages", ctypes.c_int32),
                 ("block_table", ctypes.c_void_p), ("block_table_stride", ctypes.c_int64),
                 ("selection", ctypes.c_int32)]
+
+
+class LaunchPlan(ctypes.Structure):
+    """td_launch_plan of include/tidal.h."""
+    _fields_ = [("chunk_tokens", ctypes.c_int32), ("chunks_per_row", ctypes.c_int32),
+                ("waves_per_workgroup", ctypes.c_int32), ("matrix_core", ctypes.c_int32),
+                ("grid_rows", ctypes.c_int32), ("workgroups", ctypes.c_int64)]
+
+
+def plan_launch(shape, layer_kind, k, ctx=None):
+    """td_plan_launch: the launch plan of one layer (host only, nothing is enqueued)."""
+    plan = LaunchPlan()
+    st = lib().td_plan_launch(ctx, ctypes.byref(shape), int(layer_kind), int(k), ctypes.byref(plan))
+    if st != OK:
+        raise TidalError(st, "td_plan_launch")
+    return plan
 
 
 class TidalError(RuntimeError):
@@ -75,6 +91,8 @@ def lib():
     pv = ctypes.POINTER(vp)
     L.td_decode_step_append.argtypes = [vp, shp, i32, ctypes.POINTER(i32), pv, pv, pv, pv, pv, i32, pv, vp, vp]
     L.td_decode_step_append.restype = ctypes.c_int
+    L.td_plan_launch.argtypes = [vp, shp, i32, i32, ctypes.POINTER(LaunchPlan)]
+    L.td_plan_launch.restype = ctypes.c_int
     L.td_set_tuning.argtypes, L.td_set_tuning.restype = [vp, i32, i32, i32, i32, i32], ctypes.c_int
     L.td_probe_stream.argtypes, L.td_probe_stream.restype = [vp, vp, vp, sz, vp], ctypes.c_int
     L.td_status_string.argtypes, L.td_status_string.restype = [ctypes.c_int], ctypes.c_char_p
