@@ -273,3 +273,26 @@ def test_repeated_launches_with_alternating_inputs_are_stable():
     check_output(ref["a"][0], O.full(host(qa), host(Ka), host(Va), w.seq_lens), "input a")
     check_output(ref["b"][0], O.full(host(qb), host(Kb), host(Vb), w.seq_lens), "input b")
     c.td.close()
+
+
+def test_correction_prefill_as_pseudo_sequences_sharing_one_cache():
+    # Sec. 3.2's cache correction re-runs full attention for the last P ("polluted") tokens: token
+    # N - P + j attends causally over positions 0 .. N - P + j.  That is td_full_attend over P
+    # pseudo-sequences that share one cache (kv_stride_batch = 0) with lengths N - P + 1 .. N.
+    w = W.workload("c2", context=3000, k=64)
+    (q1, K, V), = device_layers(w, [0])
+    P_tok = 8
+    g = torch.Generator(device=DEV).manual_seed(5)
+    q = torch.randn((P_tok, w.num_q_heads, w.head_dim), generator=g, device=DEV).to(torch.bfloat16)
+    lens_list = [w.max_seq_len - P_tok + 1 + j for j in range(P_tok)]
+    lens = torch.tensor(lens_list, dtype=torch.int32, device=DEV)
+    Kx, Vx = K.expand(P_tok, -1, -1, -1), V.expand(P_tok, -1, -1, -1)      # batch stride 0
+    assert Kx.stride(0) == 0
+    shape = tidal.make_shape(q, Kx, lens)
+    td = tidal.Tidal(shape, 0)
+    out = torch.full_like(q, float("nan"))
+    td.full_attend(shape, q, K, V, out)
+    torch.cuda.synchronize()
+    ref = O.full(host(q), host(K).expand(P_tok, -1, -1, -1), host(V).expand(P_tok, -1, -1, -1), lens_list)
+    check_output(out, ref, "correction prefill")
+    td.close()
