@@ -127,6 +127,13 @@ def test_c4_full_size_ragged_batch():
     run_step(w, {3, 12, 14, 31}, tag="c4")
 
 
+def test_c6_sixty_four_layers_eight_heads_per_group():
+    # the 64-layer schedule with the 70B head shape; a shorter schedule with the same kinds and the
+    # re-selection keeps the oracle's share to a few layers
+    w = W.workload("c6", schedule=(W.DENSE, W.DENSE, W.SELECT, W.SPARSE, W.SPARSE, W.SELECT, W.SPARSE, W.SPARSE))
+    run_step(w, {3, 4, 6, 7}, graph=True, tag="c6")
+
+
 @pytest.mark.parametrize("k", [256, 1024, 4096, 16384])
 def test_c5_budget_sweep(k):
     # the cache does not depend on k; a shorter schedule keeps one full, both kinds of
