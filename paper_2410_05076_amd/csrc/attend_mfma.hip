@@ -50,13 +50,13 @@ constexpr uint32_t kLowHalves = 0x05040100u;   // (x1.lo16 << 16) | x0.lo16
 constexpr uint32_t kHighHalves = 0x07060302u;  // (x1.hi16 << 16) | x0.hi16
 
 // W wave64s per workgroup (4 or 8) and PAGED as in attend.hip.  A sparse layer is one short
-// burst per wave, so there a wave takes two 16-token tiles per iteration (all 16 row loads in
-// flight at once); full and selection layers take one.
+// burst per wave, so with four waves a wave takes two 16-token tiles per iteration (all 16 row
+// loads in flight at once); full and selection layers, and eight-wave sparse layers, take one.
 template <int G, int MODE, int W, bool PAGED>
 __global__ __launch_bounds__(W *kWave) __attribute__((amdgpu_waves_per_eu(MODE != kSparse ? 4 : 1)))
 void attend_mfma_kernel(const AttendParams p) {
     constexpr int T = W * kWave;
-    constexpr int kTiles = MODE == kSparse ? 2 : 1;
+    constexpr int kTiles = MODE == kSparse && W == 4 ? 2 : 1;
     constexpr int STEP = kTiles * kWaveTokens;  // tokens per wave per iteration
     const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
