@@ -22,7 +22,7 @@ namespace {
 
 constexpr int32_t kDefaultTargetWorkgroups = 1024;
 constexpr int32_t kRaggedTargetWorkgroups = 8192;
-constexpr int32_t kDefaultMinChunkDense = 256;
+constexpr int32_t kDefaultMinChunkDense = 128;
 constexpr int32_t kDefaultMinChunkSparse = 128;
 constexpr int32_t kChunkGranule = 128;
 // chunks per (sequence, KV head): every chunk takes a ticket on one counter and the last one
