@@ -17,6 +17,8 @@
  *   sparse : Eq. 1 restricted to the persisted positions rho
  *            (Alg. 1, "SparseAttention(q, C[rho])")
  *   step   : Alg. 1's layer loop, attention part only
+ *   prefill: full attention for the last P tokens of a sequence with the causal rule (the
+ *            attention of the cache-correction step, Sec. 3.2)
  *   paged  : the same results for a cache stored in pages behind a block
  *            table (tdo_gather_pages states the mapping)
  *
@@ -437,6 +439,35 @@ int tdo_append(const tdo_shape *s, void *K, void *V, const void *k_new, const vo
             memcpy((char *)V + dst * eb, (const char *)v_new + src * eb, row);
         }
     return TDO_OK;
+}
+
+/*
+ * Attention of the cache-correction step (Sec. 3.2): a prefill over the last P tokens of every
+ * sequence, whose keys and values are already in the cache.  Token j (0 <= j < P) of sequence b
+ * sits at position N_b - P + j and attends, with full attention (Eq. 1), to the positions up to
+ * and including its own - the usual causal rule of a prefill.  q, out: [B][P][Hq][d].
+ * Requires P <= N_b for every sequence.
+ */
+int tdo_prefill(const tdo_shape *s, int32_t num_new, const void *q, const void *K, const void *V, float *out) {
+    if (!shape_ok(s) || !q || !K || !V || !out || num_new < 1) return TDO_BAD_ARG;
+    for (int b = 0; b < s->batch; ++b)
+        if (s->seq_lens[b] < num_new) return TDO_BAD_ARG;
+    const int G = s->num_q_heads / s->num_kv_heads, d = s->head_dim;
+    const float scale = scale_of(s);
+    int err = TDO_OK;
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int b = 0; b < s->batch; ++b)
+        for (int x = 0; x < num_new * s->num_q_heads; ++x) {
+            const int j = x / s->num_q_heads, h = x % s->num_q_heads, g = h / G;
+            const int visible = s->seq_lens[b] - num_new + j + 1;
+            float *work = (float *)malloc((size_t)visible * sizeof(float));
+            if (!work) { err = TDO_NO_MEM; continue; }
+            const int64_t qo = (((int64_t)b * num_new + j) * s->num_q_heads + h) * d;
+            const int64_t kvo = b * s->kv_stride_batch + g * s->kv_stride_head;
+            attend_one(q, qo, K, V, kvo, s->kv_stride_tok, d, s->dtype, scale, NULL, visible, out + qo, NULL, work);
+            free(work);
+        }
+    return err;
 }
 
 int tdo_num_threads(void) {

@@ -45,7 +45,7 @@ def lib():
             _build.build()
         _lib = ctypes.CDLL(path)
         for name in ("tdo_full", "tdo_select", "tdo_sparse", "tdo_step", "tdo_topk_row", "tdo_gather_pages",
-                     "tdo_select_variant", "tdo_sparse_per_head", "tdo_append"):
+                     "tdo_select_variant", "tdo_sparse_per_head", "tdo_append", "tdo_prefill"):
             getattr(_lib, name).restype = ctypes.c_int
         _lib.tdo_num_threads.restype = ctypes.c_int
     return _lib
@@ -198,3 +198,14 @@ def append(K, V, k_new, v_new, seq_lens):
     s, lens = _shape(q_like, K, V, seq_lens, 0.0)
     assert k_new.shape == q_like.shape
     _check(lib().tdo_append(ctypes.byref(s), _ptr(K), _ptr(V), _ptr(k_new), _ptr(v_new)))
+
+
+def prefill(q, K, V, seq_lens, sm_scale=0.0):
+    """Attention of a prefill over the last P tokens (cache correction, Sec. 3.2): q [B][P][Hq][d];
+    token j of sequence b sits at position seq_lens[b] - P + j and sees positions up to its own."""
+    assert q.dim() == 4 and q.is_contiguous()
+    B, P_new, Hq, d = q.shape
+    s, lens = _shape(q.view(B * P_new, Hq, d)[:B], K, V, seq_lens, sm_scale)
+    out = torch.zeros(q.shape, dtype=torch.float32)
+    _check(lib().tdo_prefill(ctypes.byref(s), ctypes.c_int32(P_new), _ptr(q), _ptr(K), _ptr(V), _ptr(out)))
+    return out

@@ -480,3 +480,40 @@ def test_mean_probability_equals_the_logit_rule_for_a_single_head():
     V = torch.randn((1, 3, 30, 8), generator=g)
     _, pos, _ = O.select_variant(q, K, V, [30], 6, O.REDUCE_MEAN_PROB)
     assert torch.equal(pos, O.select(q, K, V, [30], 6)[1])
+
+
+# ---- prefill over the last P tokens (attention of the cache-correction step, Sec. 3.2)
+
+
+def test_prefill_against_float64_causal_attention():
+    g = torch.Generator().manual_seed(21)
+    B, P_new, Hq, Hkv, N, d = 2, 5, 4, 2, 19, 8
+    lens = [19, 7]
+    q = torch.randn((B, P_new, Hq, d), generator=g)
+    K = torch.randn((B, Hkv, N, d), generator=g)
+    V = torch.randn((B, Hkv, N, d), generator=g)
+    out = O.prefill(q, K, V, lens)
+    for b, n in enumerate(lens):
+        for j in range(P_new):
+            vis = n - P_new + j + 1
+            for h in range(Hq):
+                kv = h // (Hq // Hkv)
+                p = torch.softmax((K[b, kv, :vis].double() @ q[b, j, h].double()) / math.sqrt(d), 0)
+                assert torch.allclose(out[b, j, h].double(), p @ V[b, kv, :vis].double(), atol=1e-5), (b, j, h)
+
+
+def test_prefill_is_causal_and_reduces_to_full_attention_for_one_token():
+    g = torch.Generator().manual_seed(22)
+    q = torch.randn((1, 3, 2, 8), generator=g)
+    K = torch.randn((1, 2, 12, 8), generator=g)
+    V = torch.randn((1, 2, 12, 8), generator=g)
+    base = O.prefill(q, K, V, [12])
+    K2, V2 = K.clone(), V.clone()
+    K2[0, :, 11] += 3.0
+    V2[0, :, 11] -= 2.0                      # only the last token may notice its own row
+    moved = O.prefill(q, K2, V2, [12])
+    assert torch.equal(moved[0, :2], base[0, :2]) and not torch.equal(moved[0, 2], base[0, 2])
+    assert torch.equal(O.prefill(q[:, 2:], K, V, [12])[0, 0], O.full(q[0, 2][None], K, V, [12])[0])
+    # token j is the decode step of a sequence that ends at its position
+    for j in range(3):
+        assert torch.equal(base[0, j], O.full(q[0, j][None], K, V, [12 - 2 + j])[0])
