@@ -181,6 +181,16 @@ td_status td_decode_step(td_ctx *ctx, const td_shape *shape, int32_t num_layers,
                          const void *const *K_layers, const void *const *V_layers, int32_t k,
                          void *const *out_layers, int32_t *positions, void *hip_stream);
 
+/* Attention of a prefill over the last `num_new` tokens of every sequence - the attention of the
+ * cache-correction step (Sec. 3.2), which re-runs full attention for the tokens that were decoded
+ * sparsely.  q, out: [batch][num_new][num_q_heads][head_dim]; token j of sequence b sits at
+ * position seq_lens[b] - num_new + j (its key and value are already in the cache) and attends,
+ * with Eq. 1, to the positions up to and including its own; a token that would sit before the
+ * start of the cache (num_new > seq_lens[b]) yields zeros.  Needs no workspace.  Supported: bf16,
+ * head_dim 128, contiguous cache (TD_ERR_UNSUPPORTED otherwise). */
+td_status td_prefill_attend(td_ctx *ctx, const td_shape *shape, int32_t num_new, const void *q,
+                            const void *K, const void *V, void *out, void *hip_stream);
+
 /* The same with C.append(k, v) of Alg. 1 fused into each layer's launch: layer
  * i first appends the current token's key and value, k_new_layers[i] and
  * v_new_layers[i] ([batch][num_kv_heads][head_dim], element type `dtype`,

@@ -444,6 +444,32 @@ td_status td_select_tokens(td_ctx *ctx, const td_shape *shape, const void *q, co
     return select_tokens(ctx, shape, q, K, V, k, out, positions, group_scores, static_cast<hipStream_t>(hip_stream));
 }
 
+td_status td_prefill_attend(td_ctx *ctx, const td_shape *shape, int32_t num_new, const void *q, const void *K,
+                            const void *V, void *out, void *hip_stream) {
+    td_status st = check_call(ctx, shape, 0, false, q, K, V, out);
+    if (st != TD_OK) return st;
+    if (num_new < 1 || num_new > shape->max_seq_len)
+        return fail(ctx, TD_ERR_INVALID_ARG, "%s", "num_new outside [1, max_seq_len]");
+    if (shape->dtype != TD_BF16 || shape->head_dim != 128 || shape->page_size != 0)
+        return fail(ctx, TD_ERR_UNSUPPORTED, "%s", "prefill attention needs bf16, head_dim 128 and a contiguous cache");
+    PrefillParams p;
+    memset(&p, 0, sizeof p);
+    p.q = q; p.K = K; p.V = V; p.out = out;
+    p.seq_lens = shape->seq_lens;
+    p.stride_batch = shape->kv_stride_batch;
+    p.stride_head = shape->kv_stride_head;
+    p.stride_tok = shape->kv_stride_tok;
+    p.batch = shape->batch;
+    p.num_q_heads = shape->num_q_heads;
+    p.num_kv_heads = shape->num_kv_heads;
+    p.max_seq_len = shape->max_seq_len;
+    p.num_new = num_new;
+    p.scale = shape->sm_scale > 0.f ? shape->sm_scale : 1.0f / sqrtf((float)shape->head_dim);
+    const hipError_t e = launch_prefill(shape->num_q_heads / shape->num_kv_heads, p, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail(ctx, TD_ERR_HIP, "prefill launch failed: %s", hipGetErrorString(e));
+    return TD_OK;
+}
+
 td_status td_sparse_attend(td_ctx *ctx, const td_shape *shape, const void *q, const void *K, const void *V,
                            const int32_t *positions, int32_t k, void *out, void *hip_stream) {
     td_status st = check_call(ctx, shape, k, true, q, K, V, out);

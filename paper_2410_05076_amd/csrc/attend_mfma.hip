@@ -24,30 +24,13 @@
 //                 {8 c + e}, which the matrix core does not care about.  No LDS in the loop.
 //   The accumulators of head 4kb + i, channel 8 n16 + e live in lane (n16, kb), acc[e][i].
 #include "attend_tail.h"
+#include "mfma_util.h"
 
 namespace tidal {
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
 constexpr int kD = 128;
 constexpr int kWaveTokens = 16;  // tokens per wave per iteration
-
-template <int CTRL>
-__device__ __forceinline__ float dpp_f(float v) {
-    return __builtin_bit_cast(
-        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
-}
-
-__device__ __forceinline__ s16x4 pack_pairs(uint32_t a1, uint32_t a0, uint32_t b1, uint32_t b0, uint32_t sel) {
-    const uint32_t d0 = __builtin_amdgcn_perm(a1, a0, sel), d1 = __builtin_amdgcn_perm(b1, b0, sel);
-    return __builtin_bit_cast(s16x4, make_uint2(d0, d1));
-}
-
-constexpr uint32_t kLowHalves = 0x05040100u;   // (x1.lo16 << 16) | x0.lo16
-constexpr uint32_t kHighHalves = 0x07060302u;  // (x1.hi16 << 16) | x0.hi16
 
 // W wave64s per workgroup (4 or 8) and PAGED as in attend.hip.  A sparse layer is one short
 // burst per wave, so with four waves a wave takes two 16-token tiles per iteration (all 16 row

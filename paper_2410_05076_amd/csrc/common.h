@@ -73,6 +73,17 @@ hipError_t launch_attend(int dtype, int head_dim, int group, int waves, int mode
                          hipStream_t stream);
 hipError_t launch_attend_mfma(int group, int waves, int mode, const AttendParams &p, hipStream_t stream);
 
+// Prefill attention over the last num_new tokens of every sequence (bf16, head_dim 128, contiguous cache).
+struct PrefillParams {
+    const void *q, *K, *V;  // q: [B][num_new][Hq][128]
+    void *out;              // like q
+    const int32_t *seq_lens;
+    int64_t stride_batch, stride_head, stride_tok;  // elements
+    int32_t batch, num_q_heads, num_kv_heads, max_seq_len, num_new;
+    float scale;
+};
+hipError_t launch_prefill(int group, const PrefillParams &p, hipStream_t stream);
+
 // Mean-of-probabilities rule: prob[b][g][j] = mean over the group's heads of
 // exp2(logit[b][h][j] * log2(e) - m_h) / l_h, from the per-head scaled logits and the final
 // (m_h, l_h) that a selection launch leaves in ml.  rank receives log2(prob), which top-k ranks;

@@ -18,7 +18,7 @@ BF16, F32 = 0, 1
 LAYER_DENSE, LAYER_SELECT, LAYER_SPARSE = 0, 1, 2
 
 EXPORTS = ("td_validate", "td_workspace_bytes", "td_topk_workspace_bytes", "td_create", "td_destroy", "td_full_attend",
-           "td_select_tokens", "td_sparse_attend", "td_topk", "td_decode_step", "td_decode_step_append",
+           "td_select_tokens", "td_sparse_attend", "td_prefill_attend", "td_topk", "td_decode_step", "td_decode_step_append",
            "td_plan_launch", "td_set_tuning", "td_probe_stream",
            "td_status_string", "td_last_error")
 
@@ -83,6 +83,8 @@ def lib():
     L.td_select_tokens.restype = ctypes.c_int
     L.td_sparse_attend.argtypes = [vp, shp, vp, vp, vp, vp, i32, vp, vp]
     L.td_sparse_attend.restype = ctypes.c_int
+    L.td_prefill_attend.argtypes = [vp, shp, i32, vp, vp, vp, vp, vp]
+    L.td_prefill_attend.restype = ctypes.c_int
     L.td_topk.argtypes = [vp, vp, i64, i32, vp, i32, i32, i32, vp, vp]
     L.td_topk.restype = ctypes.c_int
     L.td_decode_step.argtypes = [vp, shp, i32, ctypes.POINTER(i32), ctypes.POINTER(vp), ctypes.POINTER(vp),
@@ -201,6 +203,13 @@ class Tidal:
         nbytes = src.numel() * src.element_size()
         self._check(lib().td_probe_stream(self._ctx, dst.data_ptr() if dst is not None else None,
                                           src.data_ptr(), nbytes, _stream()))
+
+    def prefill_attend(self, shape, q, K, V, out):
+        """td_prefill_attend: q, out [B][num_new][Hq][d]; causal attention of the last num_new tokens."""
+        assert q.dim() == 4 and q.is_contiguous() and out.is_contiguous() and out.shape == q.shape
+        self._check(lib().td_prefill_attend(self._ctx, ctypes.byref(shape), q.shape[1], q.data_ptr(), K.data_ptr(),
+                                            V.data_ptr(), out.data_ptr(), _stream()))
+        return out
 
     def decode_step(self, shape, schedule, qs, Ks, Vs, k, outs, positions):
         n = len(schedule)

@@ -1,0 +1,73 @@
+"""GPU parity for td_prefill_attend (the attention of the cache-correction step, Sec. 3.2): causal
+full attention of the last P tokens of every sequence, against the oracle's tdo_prefill."""
+import pytest
+import torch
+
+from oracle import tidal_oracle as O
+from paper_2410_05076_amd import tidal
+from paper_2410_05076_amd import workloads as W
+from parity_util import check_output
+from test_gpu_parity import DEV, device_layers, host, say
+
+pytestmark = pytest.mark.gpu
+
+
+def run_prefill(w, num_new, seed=3):
+    (_, K, V), = device_layers(w, [0])
+    g = torch.Generator(device=DEV).manual_seed(seed)
+    q = torch.randn((w.batch, num_new, w.num_q_heads, w.head_dim), generator=g, device=DEV).to(torch.bfloat16)
+    lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=DEV)
+    shape = tidal.make_shape(q[:, 0].contiguous(), K, lens)
+    td = tidal.Tidal(shape, 0)
+    out = torch.full_like(q, float("nan"))
+    say("prefill %s P=%d" % (w.name, num_new))
+    td.prefill_attend(shape, q, K, V, out)
+    torch.cuda.synchronize()
+    check_output(out, O.prefill(host(q), host(K), host(V), w.seq_lens), "prefill %s P=%d" % (w.name, num_new))
+    td.close()
+
+
+@pytest.mark.parametrize("name,over,num_new", [
+    ("c2", dict(context=3000, k=64), 1),                                   # one token: the decode step
+    ("c2", dict(context=3000, k=64), 16),                                  # G = 4: exactly one row block
+    ("c2", dict(context=3000, k=64), 37),                                  # ragged last row block
+    ("c2", dict(context=777, k=64), 300),                                  # many row blocks, short prefix
+    ("c3", dict(context=2500, k=64, tau=512.0), 100),                      # G = 1: 64 tokens per block
+    ("c6", dict(context=2000, k=64), 21),                                  # G = 8
+    ("c2", dict(context=1000, k=64, num_q_heads=16), 50),                  # G = 2
+    ("c4", dict(seq_lens=(900, 33, 64, 2048), k=64), 33),                  # ragged batch, P = N for one
+    ("c2", dict(context=40, k=8), 40),                                     # the whole sequence is new
+])
+def test_prefill_attend(name, over, num_new):
+    run_prefill(W.workload(name, **over), num_new)
+
+
+def test_prefill_longer_than_a_sequence_yields_zeros_for_the_missing_tokens():
+    w = W.workload("c4", seq_lens=(50, 10), k=8)
+    (_, K, V), = device_layers(w, [0])
+    g = torch.Generator(device=DEV).manual_seed(1)
+    q = torch.randn((2, 16, w.num_q_heads, w.head_dim), generator=g, device=DEV).to(torch.bfloat16)
+    lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=DEV)
+    shape = tidal.make_shape(q[:, 0].contiguous(), K, lens)
+    td = tidal.Tidal(shape, 0)
+    out = torch.full_like(q, float("nan"))
+    td.prefill_attend(shape, q, K, V, out)
+    torch.cuda.synchronize()
+    assert (out[1, :6] == 0).all()                     # tokens at positions -6 .. -1 do not exist
+    ref = O.prefill(host(q[1:, 6:]).contiguous(), host(K[1:]), host(V[1:]), [10])
+    check_output(out[1:, 6:], ref, "tail of the short sequence")
+    check_output(out[:1], O.prefill(host(q[:1]), host(K[:1]), host(V[:1]), [50]), "long sequence")
+    td.close()
+
+
+def test_prefill_rejects_unsupported_shapes():
+    w = W.workload("c1", context=100, k=8)               # fp32, head_dim 64
+    (q1, K, V), = device_layers(w, [0])
+    lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=DEV)
+    shape = tidal.make_shape(q1, K, lens)
+    td = tidal.Tidal(shape, 0)
+    q = q1[:, None].contiguous()
+    with pytest.raises(tidal.TidalError) as e:
+        td.prefill_attend(shape, q, K, V, torch.empty_like(q))
+    assert e.value.status == tidal.ERR_UNSUPPORTED
+    td.close()
