@@ -56,6 +56,9 @@ def main():
                     help="hold the cache in pages of this many tokens behind a shuffled block table (0: contiguous)")
     ap.add_argument("--page-layout", default="HND", choices=["HND", "NHD"],
                     help="inside a page: [KV head][slot][d] or [slot][KV head][d]")
+    ap.add_argument("--prefill", type=int, default=0,
+                    help="instead of the decode step, time td_prefill_attend over this many new tokens per sequence "
+                         "(the attention of the cache-correction step) on one layer of the workload")
     ap.add_argument("--append", action="store_true",
                     help="time td_decode_step_append: every layer also appends the current token's k, v to its cache")
     ap.add_argument("--selection", default="sum", choices=["sum", "max", "per_head", "mean_prob"],
@@ -75,6 +78,9 @@ def main():
     dev = "cuda:0"
     if args.probe_only:
         print(json.dumps({"hbm_probe": hbm_probe(torch, tidal, dev)}), flush=True)
+        return
+    if args.prefill:
+        print(json.dumps(prefill_bench(args, torch, tidal, W, dev)), flush=True)
         return
     over = {"k": args.k} if args.k else {}
     if args.num_q_heads:
@@ -265,6 +271,51 @@ def main():
     }
     td.close()
     print(json.dumps(out), flush=True)
+
+
+def prefill_bench(args, torch, tidal, W, dev):
+    """Time of td_prefill_attend for P new tokens per sequence on one layer's cache, against the dense MFMA peak.
+
+    flop = 4 * d * sum over tokens and heads of the positions each token sees (two products, multiply-add)."""
+    over = {}
+    if args.num_q_heads:
+        over["num_q_heads"] = args.num_q_heads
+    if args.num_kv_heads:
+        over["num_kv_heads"] = args.num_kv_heads
+    if args.context:
+        over["context"] = args.context
+    w = W.workload(args.workload, **over)
+    P = args.prefill
+    q1, K, V = W.make_layer(w, 0, dev, heavy=W.heavy_positions(w), ranks=W.zipf_ranks(w) if w.structure == "zipf" else None)
+    q = torch.randn((w.batch, P, w.num_q_heads, w.head_dim), device=dev).to(w.torch_dtype)
+    out = torch.empty_like(q)
+    lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=dev)
+    shape = tidal.make_shape(q1, K, lens)
+    td = tidal.Tidal(shape, 0)
+    for _ in range(max(1, args.warmup)):
+        td.prefill_attend(shape, q, K, V, out)
+    torch.cuda.synchronize()
+    evs = []
+    for _ in range(args.steps):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        td.prefill_attend(shape, q, K, V, out)
+        b.record()
+        evs.append((a, b))
+    torch.cuda.synchronize()
+    ts = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
+    us = sum(ts) / len(ts)
+    seen = sum(sum(max(n - P + j + 1, 0) for j in range(P)) for n in w.seq_lens)
+    flop = 4.0 * w.head_dim * w.num_q_heads * seen
+    tflops = flop / (us * 1e-6) / 1e12
+    td.close()
+    return {"metric": "prefill_attention_us", "value": round(us, 2), "unit": "us", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": round(us / 1e3, 5), "higher_is_better": False, "scaling": "weak",
+            "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+            "config": {"workload": DESCRIPTIONS[w.name] + ", one layer, prefill attention over the last %d tokens" % P},
+            "median_us": round(ts[len(ts) // 2], 2),
+            "roofline": {"kernel": "prefill_mfma_kernel", "bound": "mfma", "achieved": round(tflops, 1), "peak": 2500.0,
+                         "unit": "TFLOP/s", "frac": round(tflops / 2500.0, 4), "traffic": None, "flop_per_launch": flop}}
 
 
 def hbm_probe(torch, tidal, dev, td=None, nbytes=2**30, reps=6):

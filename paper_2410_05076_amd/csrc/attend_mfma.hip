@@ -265,8 +265,7 @@ void attend_mfma_kernel(const AttendParams p) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) s2[i] = valid[x][i] ? st[i] * scale2 : -INFINITY;
             float tm = fmaxf(fmaxf(s2[0], s2[1]), fmaxf(s2[2], s2[3]));
-            tm = fmaxf(tm, __shfl_xor(tm, 16));
-            tm = fmaxf(tm, __shfl_xor(tm, 32));
+            tm = cross_rows_max(tm);
             const float m_new = fmaxf(m_run, tm);
             const float alpha = fast_exp2(m_run - m_new);
             float pr[4];
@@ -311,8 +310,7 @@ void attend_mfma_kernel(const AttendParams p) {
     }
 
     // ---- one state per wave into LDS, then the common tail
-    l_run += __shfl_xor(l_run, 16);
-    l_run += __shfl_xor(l_run, 32);
+    l_run = cross_rows_sum(l_run);
     constexpr int RG = W;
     __shared__ TailShared<kD, G, RG, T> sm;
     if (kb == 0 && n16 < G) {

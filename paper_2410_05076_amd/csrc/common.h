@@ -80,6 +80,7 @@ struct PrefillParams {
     const int32_t *seq_lens;
     int64_t stride_batch, stride_head, stride_tok;  // elements
     int32_t batch, num_q_heads, num_kv_heads, max_seq_len, num_new;
+    int32_t row_blocks;  // set by the launcher: workgroups per (sequence, KV head)
     float scale;
 };
 hipError_t launch_prefill(int group, const PrefillParams &p, hipStream_t stream);

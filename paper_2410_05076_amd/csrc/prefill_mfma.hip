@@ -29,7 +29,20 @@ constexpr int kPThreads = kPWaves * kWave;
 
 template <int G, int R>
 __global__ __launch_bounds__(kPThreads) void prefill_mfma_kernel(const PrefillParams p) {
-    const int rb = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+    // Workgroups are handed to the eight XCDs round-robin by their linear index.  The row blocks of
+    // one (sequence, KV head) stream the same keys and values at about the same pace, so they
+    // should share an L2: with a multiple of eight (sequence, KV head) pairs, the linear index is
+    // unpacked pair-first, and all row blocks of a pair land on XCD (pair % 8).
+    const int pairs = p.num_kv_heads * p.batch;
+    int rb, pair;
+    if (pairs % 8 == 0) {
+        pair = blockIdx.x % pairs;
+        rb = blockIdx.x / pairs;
+    } else {
+        rb = blockIdx.x % p.row_blocks;
+        pair = blockIdx.x / p.row_blocks;
+    }
+    const int g = pair % p.num_kv_heads, b = pair / p.num_kv_heads;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
     const int n16 = lane & 15, kb = lane >> 4;
     const int P = p.num_new, rows_total = P * G, row0 = rb * (16 * R);
@@ -79,16 +92,23 @@ __global__ __launch_bounds__(kPThreads) void prefill_mfma_kernel(const PrefillPa
     }
     const float scale2 = p.scale * kLog2e;
 
-    for (int base = wave * 16; base < t_end; base += kPWaves * 16) {
-        // K: token base + n16; V: tokens base + 4kb + u.  Lanes beyond the streamed range read its
-        // last row and are masked by the rows' limits.
+    // K: token base + n16; V: tokens base + 4kb + u.  Lanes beyond the streamed range read its last
+    // row and are masked by the rows' limits.  The next tile's loads are issued before the current
+    // tile is consumed (one wave per SIMD fits the registers, so nothing else hides the latency).
+    auto load_tile = [&](int base, uint4 (&kr)[4], uint4 (&vr)[4]) {
         const char *kp = Kb + (int64_t)min(base + n16, t_end - 1) * row_bytes;
-        uint4 kraw[4], vraw[4];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) kraw[s] = stream_load16(kp + 64 * s);
+        for (int s = 0; s < 4; ++s) kr[s] = stream_load16(kp + 64 * s);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) vraw[u] = stream_load16(Vb + (int64_t)min(base + 4 * kb + u, t_end - 1) * row_bytes);
-        __builtin_amdgcn_sched_barrier(0);  // every load is issued before the first one is consumed
+        for (int u = 0; u < 4; ++u) vr[u] = stream_load16(Vb + (int64_t)min(base + 4 * kb + u, t_end - 1) * row_bytes);
+    };
+    uint4 kraw[4], vraw[4];
+    if (wave * 16 < t_end) load_tile(wave * 16, kraw, vraw);
+    for (int base = wave * 16; base < t_end; base += kPWaves * 16) {
+        uint4 knext[4], vnext[4];
+        const bool more = base + kPWaves * 16 < t_end;
+        if (more) load_tile(base + kPWaves * 16, knext, vnext);
+        __builtin_amdgcn_sched_barrier(0);  // the next tile's loads are issued before this tile is consumed
 
         // V as B operand: for channel group e the 4-token column of channels {8 c + e}
         s16x4 vf[8];
@@ -113,8 +133,7 @@ __global__ __launch_bounds__(kPThreads) void prefill_mfma_kernel(const PrefillPa
 #pragma unroll
             for (int i = 0; i < 4; ++i) s2[i] = t_lane + i < limit[r] ? st[i] * scale2 : -INFINITY;
             float tm = fmaxf(fmaxf(s2[0], s2[1]), fmaxf(s2[2], s2[3]));
-            tm = fmaxf(tm, __shfl_xor(tm, 16));
-            tm = fmaxf(tm, __shfl_xor(tm, 32));
+            tm = cross_rows_max(tm);
             const float m_new = fmaxf(m_run[r], tm);
             const float alpha = fast_exp2(m_run[r] - m_new);
             float pr[4];
@@ -138,6 +157,13 @@ __global__ __launch_bounds__(kPThreads) void prefill_mfma_kernel(const PrefillPa
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc[r][e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, vf[e], acc[r][e], 0, 0, 0);
         }
+        if (more) {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                kraw[s] = knext[s];
+                vraw[s] = vnext[s];
+            }
+        }
     }
 
     // ---- fold the four waves' states of one row tile at a time through LDS and write the rows
@@ -145,9 +171,7 @@ __global__ __launch_bounds__(kPThreads) void prefill_mfma_kernel(const PrefillPa
     __shared__ __align__(16) float s_acc[kPWaves][16][kPD];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        float lr = l_run[r];
-        lr += __shfl_xor(lr, 16);
-        lr += __shfl_xor(lr, 32);
+        const float lr = cross_rows_sum(l_run[r]);
         if (r) __syncthreads();
         if (kb == 0) {
             s_m[wave][n16] = m_run[r];
@@ -181,12 +205,22 @@ __global__ __launch_bounds__(kPThreads) void prefill_mfma_kernel(const PrefillPa
     }
 }
 
-template <int G>
-hipError_t launch_prefill_group(const PrefillParams &p, hipStream_t stream) {
-    constexpr int R = 4;
-    const dim3 grid((p.num_new * G + 16 * R - 1) / (16 * R), p.num_kv_heads, p.batch), block(kPThreads);
+template <int G, int R>
+hipError_t launch_prefill_rows(PrefillParams p, hipStream_t stream) {
+    p.row_blocks = (p.num_new * G + 16 * R - 1) / (16 * R);
+    const dim3 grid(p.row_blocks * p.num_kv_heads * p.batch), block(kPThreads);
     hipLaunchKernelGGL((prefill_mfma_kernel<G, R>), grid, block, 0, stream, p);
     return hipGetLastError();
+}
+
+// Rows per workgroup: 64 when that still gives every CU a workgroup, else 32 or 16 (more
+// workgroups, each streaming the keys and values for fewer rows).
+template <int G>
+hipError_t launch_prefill_group(const PrefillParams &p, hipStream_t stream) {
+    const int64_t rows = (int64_t)p.num_new * G, pairs = (int64_t)p.num_kv_heads * p.batch;
+    if ((rows + 63) / 64 * pairs >= 256) return launch_prefill_rows<G, 4>(p, stream);
+    if ((rows + 31) / 32 * pairs >= 256) return launch_prefill_rows<G, 2>(p, stream);
+    return launch_prefill_rows<G, 1>(p, stream);
 }
 
 }  // namespace
