@@ -7,18 +7,28 @@
 // of four wave64s takes R * 16 consecutive rows and streams the cache once for all of them, up to
 // the last position any of its rows may see; the waves split the tokens (16-token tiles,
 // interleaved) and every wave keeps an online-softmax state for all R * 16 rows, so a K or V tile
-// is loaded once per wave and used by R row tiles.  The tile arithmetic is that of
-// attend_mfma.hip: S^T = K Q^T with v_mfma_f32_16x16x32_bf16 (K from memory straight into the A
-// operand), O += P V with v_mfma_f32_16x16x16_bf16 - here with P rounded to bf16 once, as prefill
-// kernels commonly do - and per-row causal masks on the logits.  The four waves' states are
-// folded through LDS, one row tile at a time, and the rows are written out; there is no split
-// across workgroups, so no partials and no workspace.
+// is loaded once per wave and used by R row tiles.  Per tile: S^T = K Q^T with
+// v_mfma_f32_16x16x32_bf16 (K from memory straight into the A operand; a lane then holds four
+// tokens of one query row), P = exp2(S^T scale log2(e) - m) rounded to bf16 once
+// (v_cvt_pk_bf16_f32), and O^T += V^T P^T with v_mfma_f32_16x16x16_bf16, so that a lane's
+// accumulators all belong to its own query row and the row's state (m, l) needs no shuffle.
 //
-// Per 16-token tile and wave: 8 loads of 16 bytes per lane, R * 12 MFMAs (R * 98304 flop) and
-// about 60 + R * 45 vector instructions, so for R = 4 the vector ALU, not the matrix core, sets
-// the pace: at best ~40 % of the MFMA peak.
+// The reference maximum m of a row is lazy: it is raised (and the row's accumulators rescaled)
+// only when a logit exceeds it by more than kLazyMax in log2 units, so p <= 2^kLazyMax, far
+// inside the range of fp32 sums and bf16 operands, and the check is one compare per lane with no
+// cross-lane step; after the first tile the rescale branch is practically never taken.  Tiles
+// that every row of the workgroup sees in full run without masks and with wave-uniform load
+// addresses; only the last tiles (the causal diagonal and the ragged end) take the masked path.
+// The four waves' states are folded through LDS, one row tile at a time, and the rows are written
+// out; there is no split across workgroups, so no partials and no workspace.
+//
+// Per 16-token tile and wave: 8 loads of 16 bytes per lane, R * 12 MFMAs (R * 98304 flop, 128
+// matrix-core cycles per row tile) and about 20 + R * 22 vector instructions, four of them
+// quarter-rate exponentials per row tile: the vector ALU and the matrix core are about balanced.
 #include "attend_tail.h"
 #include "mfma_util.h"
+
+#include <type_traits>
 
 namespace tidal {
 namespace {
@@ -26,6 +36,15 @@ namespace {
 constexpr int kPD = 128;
 constexpr int kPWaves = 4;
 constexpr int kPThreads = kPWaves * kWave;
+constexpr int kPStep = kPWaves * 16;  // tokens between two tiles of one wave
+constexpr float kLazyMax = 8.f;       // a row's reference maximum may trail its true one by this (log2 units)
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t bf16_pair(float lo, float hi) {
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){lo, hi}, bf16x2));
+}
 
 template <int G, int R>
 __global__ __launch_bounds__(kPThreads) void prefill_mfma_kernel(const PrefillParams p) {
@@ -43,7 +62,8 @@ __global__ __launch_bounds__(kPThreads) void prefill_mfma_kernel(const PrefillPa
         pair = blockIdx.x / p.row_blocks;
     }
     const int g = pair % p.num_kv_heads, b = pair / p.num_kv_heads;
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n16 = lane & 15, kb = lane >> 4;
     const int P = p.num_new, rows_total = P * G, row0 = rb * (16 * R);
 
@@ -74,89 +94,127 @@ __global__ __launch_bounds__(kPThreads) void prefill_mfma_kernel(const PrefillPa
 #pragma unroll
     for (int r = 0; r < R; ++r) limit[r] = row0 + 16 * r + n16 < rows_total ? max(N - P + tkn[r] + 1, 0) : 0;
     const int last_tkn = min(P - 1, (row0 + 16 * R - 1) / G);
-    const int t_end = max(N - P + last_tkn + 1, 0);  // tokens this workgroup streams
+    const int t_end = max(N - P + last_tkn + 1, 0);   // tokens this workgroup streams
+    const int t_full = max(N - P + row0 / G + 1, 0);  // tokens below this one are seen by every row
 
     const int64_t row_bytes = p.stride_tok * 2;
     const int64_t head_off = ((int64_t)b * p.stride_batch + (int64_t)g * p.stride_head) * 2;
-    const char *Kb = static_cast<const char *>(p.K) + head_off + kb * 16;  // + 64 s per step
-    const char *Vb = static_cast<const char *>(p.V) + head_off + n16 * 16;
+    const char *Kh = static_cast<const char *>(p.K) + head_off;  // wave-uniform
+    const char *Vh = static_cast<const char *>(p.V) + head_off;
 
-    float m_run[R], l_run[R];
-    f32x4 acc[R][8];
+    // The softmax denominator is accumulated on the matrix core as well, as one more "channel" of
+    // ones: it then sums the same bf16-rounded probabilities as the numerator, which keeps a row
+    // that one token dominates exact, and costs no vector instruction.
+    float m_use[R];   // reference maximum of row n16 (the same in its four lanes)
+    f32x4 acc[R][8];  // acc[r][e][i]: row n16 of tile r, channel 8 (4 kb + i) + e
+    f32x4 lacc[R];    // every element: l of row n16
+    const s16x4 ones = {0x3f80, 0x3f80, 0x3f80, 0x3f80};
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        m_run[r] = kEmptyMax;
-        l_run[r] = 0.f;
+        m_use[r] = kEmptyMax;
+        lacc[r] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[r][e] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
     const float scale2 = p.scale * kLog2e;
 
-    // K: token base + n16; V: tokens base + 4kb + u.  Lanes beyond the streamed range read its last
-    // row and are masked by the rows' limits.  The next tile's loads are issued before the current
-    // tile is consumed (one wave per SIMD fits the registers, so nothing else hides the latency).
+    // K: token base + n16, d-octets kb + 4 s; V: tokens base + 4 kb + u, channels 8 n16 .. + 7.
+    // A tile whose 16 tokens all exist is addressed as a wave-uniform base plus a constant lane
+    // offset; the last, partial tile clamps its tokens to the last one streamed (masked below).
+    const uint32_t k_lane = (uint32_t)(n16 * row_bytes) + kb * 16, v_lane = (uint32_t)(4 * kb * row_bytes) + n16 * 16;
     auto load_tile = [&](int base, uint4 (&kr)[4], uint4 (&vr)[4]) {
-        const char *kp = Kb + (int64_t)min(base + n16, t_end - 1) * row_bytes;
+        if (base + 16 <= t_end) {
+            const char *kt = Kh + (int64_t)base * row_bytes, *vt = Vh + (int64_t)base * row_bytes;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) kr[s] = stream_load16(kp + 64 * s);
+            for (int s = 0; s < 4; ++s) kr[s] = *reinterpret_cast<const uint4 *>(kt + k_lane + 64 * s);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) vr[u] = stream_load16(Vb + (int64_t)min(base + 4 * kb + u, t_end - 1) * row_bytes);
+            for (int u = 0; u < 4; ++u) vr[u] = *reinterpret_cast<const uint4 *>(vt + u * row_bytes + v_lane);
+        } else {
+            const char *kp = Kh + (int64_t)min(base + n16, t_end - 1) * row_bytes + kb * 16;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) kr[s] = *reinterpret_cast<const uint4 *>(kp + 64 * s);
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                vr[u] = *reinterpret_cast<const uint4 *>(Vh + (int64_t)min(base + 4 * kb + u, t_end - 1) * row_bytes +
+                                                         n16 * 16);
+        }
     };
-    uint4 kraw[4], vraw[4];
-    if (wave * 16 < t_end) load_tile(wave * 16, kraw, vraw);
-    for (int base = wave * 16; base < t_end; base += kPWaves * 16) {
-        uint4 knext[4], vnext[4];
-        const bool more = base + kPWaves * 16 < t_end;
-        if (more) load_tile(base + kPWaves * 16, knext, vnext);
-        __builtin_amdgcn_sched_barrier(0);  // the next tile's loads are issued before this tile is consumed
 
-        // V as B operand: for channel group e the 4-token column of channels {8 c + e}
+    // One 16-token tile against the R row tiles.  kMasked: per-row causal limits apply.  Returns
+    // false, with nothing accumulated, when some reference maximum has to be raised first.
+    float top[R];  // largest scaled logit of this lane in the tile, per row tile
+    auto consume = [&](auto masked, int base, const uint4 (&kr)[4], const uint4 (&vr)[4]) -> bool {
+        constexpr bool kMasked = decltype(masked)::value;
+        // V^T as A operand: for channel group e, tokens 4kb .. 4kb+3 of channel 8 n16 + e
         s16x4 vf[8];
         {
-            const uint32_t vw[4][4] = {{vraw[0].x, vraw[0].y, vraw[0].z, vraw[0].w},
-                                       {vraw[1].x, vraw[1].y, vraw[1].z, vraw[1].w},
-                                       {vraw[2].x, vraw[2].y, vraw[2].z, vraw[2].w},
-                                       {vraw[3].x, vraw[3].y, vraw[3].z, vraw[3].w}};
+            const uint32_t vw[4][4] = {{vr[0].x, vr[0].y, vr[0].z, vr[0].w},
+                                       {vr[1].x, vr[1].y, vr[1].z, vr[1].w},
+                                       {vr[2].x, vr[2].y, vr[2].z, vr[2].w},
+                                       {vr[3].x, vr[3].y, vr[3].z, vr[3].w}};
 #pragma unroll
             for (int e = 0; e < 8; ++e)
                 vf[e] = pack_pairs(vw[1][e >> 1], vw[0][e >> 1], vw[3][e >> 1], vw[2][e >> 1],
                                    (e & 1) ? kHighHalves : kLowHalves);
         }
         const int t_lane = base + 4 * kb;  // this lane's logits are for tokens t_lane .. t_lane + 3
+        f32x4 st[R];
+        bool grow = false;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            f32x4 st = {0.f, 0.f, 0.f, 0.f};
+            st[r] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int s = 0; s < 4; ++s)
-                st = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kraw[s]), qfrag[r][s], st, 0, 0, 0);
-            float s2[4];
+                st[r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kr[s]), qfrag[r][s], st[r], 0, 0, 0);
+            if (kMasked) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) s2[i] = t_lane + i < limit[r] ? st[i] * scale2 : -INFINITY;
-            float tm = fmaxf(fmaxf(s2[0], s2[1]), fmaxf(s2[2], s2[3]));
-            tm = cross_rows_max(tm);
-            const float m_new = fmaxf(m_run[r], tm);
-            const float alpha = fast_exp2(m_run[r] - m_new);
+                for (int i = 0; i < 4; ++i) st[r][i] = t_lane + i < limit[r] ? st[r][i] : -INFINITY;
+            }
+            top[r] = fmaxf(fmaxf(st[r][0], st[r][1]), fmaxf(st[r][2], st[r][3])) * scale2;  // scale2 > 0
+            grow |= top[r] > m_use[r] + kLazyMax;
+        }
+        if (__builtin_expect(__any(grow), 0)) return false;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
             float pr[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) pr[i] = fast_exp2(s2[i] - m_new);
-            l_run[r] = l_run[r] * alpha + ((pr[0] + pr[1]) + (pr[2] + pr[3]));
-            if (__any(m_new != m_run[r])) {  // some row's maximum moved: rescale its accumulators
+            for (int i = 0; i < 4; ++i) pr[i] = fast_exp2(fmaf(st[r][i], scale2, -m_use[r]));
+            // P^T as B operand: tokens 4kb .. 4kb+3 of row n16, rounded to bf16
+            const s16x4 pa = __builtin_bit_cast(s16x4, make_uint2(bf16_pair(pr[0], pr[1]), bf16_pair(pr[2], pr[3])));
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const float a = __shfl(alpha, 4 * kb + i);  // row 4kb + i keeps its state in lane 4kb + i
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) acc[r][e][i] *= a;
-                }
-            }
-            m_run[r] = m_new;
-            // P (tokens 4kb .. 4kb+3 of row n16), rounded to bf16 (half up on the magnitude)
-            uint32_t ph[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) ph[i] = __float_as_uint(pr[i]) + 0x8000u;
-            const s16x4 pa = pack_pairs(ph[1], ph[0], ph[3], ph[2], kHighHalves);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[r][e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, vf[e], acc[r][e], 0, 0, 0);
+            for (int e = 0; e < 8; ++e) acc[r][e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vf[e], pa, acc[r][e], 0, 0, 0);
+            lacc[r] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ones, pa, lacc[r], 0, 0, 0);
         }
+        return true;
+    };
+    // Rare (after a row's first tile practically never): bring every row's reference maximum up
+    // to date and rescale its state.  Kept outside the tile loops so that the accumulators stay in
+    // their matrix-core registers there.
+    auto raise = [&]() {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const float m_new = fmaxf(m_use[r], cross_rows_max(top[r]));
+            const float alpha = fast_exp2(m_use[r] - m_new);
+            m_use[r] = m_new;
+            lacc[r] *= alpha;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[r][e] *= alpha;
+        }
+    };
+
+    // The next tile's loads are issued before the current tile is consumed (one wave per SIMD fits
+    // the registers, so nothing else hides the latency).  Unmasked tiles first, then the masked
+    // ones; a tile that needs a higher reference maximum leaves the loops, and is taken again
+    // after the rescale.
+    uint4 kraw[4], vraw[4];
+    int base = wave * 16;
+    if (base < t_end) load_tile(base, kraw, vraw);
+    auto step = [&](auto masked) -> bool {
+        uint4 knext[4], vnext[4];
+        const bool more = base + kPStep < t_end;
+        if (more) load_tile(base + kPStep, knext, vnext);
+        __builtin_amdgcn_sched_barrier(0);
+        if (!consume(masked, base, kraw, vraw)) return false;
         if (more) {
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
@@ -164,22 +222,31 @@ __global__ __launch_bounds__(kPThreads) void prefill_mfma_kernel(const PrefillPa
                 vraw[s] = vnext[s];
             }
         }
+        base += kPStep;
+        return true;
+    };
+    for (;;) {
+        bool done = true;
+        while (done && base + 16 <= t_full) done = step(std::false_type{});
+        while (done && base < t_end) done = step(std::true_type{});
+        if (done) break;
+        raise();
     }
 
     // ---- fold the four waves' states of one row tile at a time through LDS and write the rows
+    constexpr int kPitch = kPD + 4;  // rows of one wave's tile start in different banks
     __shared__ float s_m[kPWaves][16], s_l[kPWaves][16];
-    __shared__ __align__(16) float s_acc[kPWaves][16][kPD];
+    __shared__ __align__(16) float s_acc[kPWaves][16][kPitch];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        const float lr = cross_rows_sum(l_run[r]);
         if (r) __syncthreads();
         if (kb == 0) {
-            s_m[wave][n16] = m_run[r];
-            s_l[wave][n16] = lr;
+            s_m[wave][n16] = m_use[r];
+            s_l[wave][n16] = lacc[r][0];
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {  // row 4kb + i, channels 8 n16 + e
-            float *dst = &s_acc[wave][4 * kb + i][8 * n16];
+        for (int i = 0; i < 4; ++i) {  // row n16, channels 8 (4 kb + i) + e
+            float *dst = &s_acc[wave][n16][8 * (4 * kb + i)];
             *reinterpret_cast<float4 *>(dst) = make_float4(acc[r][0][i], acc[r][1][i], acc[r][2][i], acc[r][3][i]);
             *reinterpret_cast<float4 *>(dst + 4) = make_float4(acc[r][4][i], acc[r][5][i], acc[r][6][i], acc[r][7][i]);
         }
