@@ -291,7 +291,7 @@ def prefill_bench(args, torch, tidal, W, dev):
     out = torch.empty_like(q)
     lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=dev)
     shape = tidal.make_shape(q1, K, lens)
-    td = tidal.Tidal(shape, 0)
+    td = tidal.Tidal(shape, 0, prefill_new=P)
     for _ in range(max(1, args.warmup)):
         td.prefill_attend(shape, q, K, V, out)
     torch.cuda.synchronize()

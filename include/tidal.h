@@ -186,8 +186,14 @@ td_status td_decode_step(td_ctx *ctx, const td_shape *shape, int32_t num_layers,
  * sparsely.  q, out: [batch][num_new][num_q_heads][head_dim]; token j of sequence b sits at
  * position seq_lens[b] - num_new + j (its key and value are already in the cache) and attends,
  * with Eq. 1, to the positions up to and including its own; a token that would sit before the
- * start of the cache (num_new > seq_lens[b]) yields zeros.  Needs no workspace.  Supported: bf16,
- * head_dim 128, contiguous cache (TD_ERR_UNSUPPORTED otherwise). */
+ * start of the cache (num_new > seq_lens[b]) yields zeros.  Supported: bf16, head_dim 128,
+ * contiguous cache (TD_ERR_UNSUPPORTED otherwise).
+ * A prefill over few tokens is bound by the stream of the cache, as a decode step is: the tokens
+ * are then cut into chunks whose partial states go through the context's workspace.
+ * td_prefill_workspace_bytes is the size that allows every chunk the launch plan would like (0
+ * when it wants none); with a smaller workspace the call uses fewer chunks, down to one (correct,
+ * slower when num_new * num_q_heads / num_kv_heads rows are too few to fill the GPU). */
+size_t td_prefill_workspace_bytes(const td_shape *shape, int32_t num_new);
 td_status td_prefill_attend(td_ctx *ctx, const td_shape *shape, int32_t num_new, const void *q,
                             const void *K, const void *V, void *out, void *hip_stream);
 

@@ -254,7 +254,7 @@ td_status attend(td_ctx *ctx, const td_shape *s, int mode, const void *q, const 
 
 // Checks common to every attention call; `k` <= 0 when the call has no budget.
 td_status check_call(td_ctx *ctx, const td_shape *s, int32_t k, bool needs_k, const void *q, const void *K,
-                     const void *V, const void *out) {
+                     const void *V, const void *out, bool needs_workspace = true) {
     if (!ctx) return TD_ERR_INVALID_ARG;
     td_status code;
     if (const char *why = shape_problem(s, k, &code)) return fail(ctx, code, "%s", why);
@@ -262,7 +262,7 @@ td_status check_call(td_ctx *ctx, const td_shape *s, int32_t k, bool needs_k, co
     if (!q || !K || !V || !out) return fail(ctx, TD_ERR_INVALID_ARG, "%s", "q, K, V or out is NULL");
     if (misaligned(q) || misaligned(K) || misaligned(V) || misaligned(out))
         return fail(ctx, TD_ERR_INVALID_ARG, "%s", "q, K, V and out must be 16-byte aligned");
-    if (workspace_layout(s, needs_k ? k : 0).total > ctx->workspace_bytes)
+    if (needs_workspace && workspace_layout(s, needs_k ? k : 0).total > ctx->workspace_bytes)
         return fail(ctx, TD_ERR_WORKSPACE, "%s", "workspace is smaller than td_workspace_bytes(shape, k)");
     return TD_OK;
 }
@@ -444,9 +444,30 @@ td_status td_select_tokens(td_ctx *ctx, const td_shape *shape, const void *q, co
     return select_tokens(ctx, shape, q, K, V, k, out, positions, group_scores, static_cast<hipStream_t>(hip_stream));
 }
 
+namespace {
+PrefillPlan prefill_plan_for(const td_shape *s, int32_t num_new, size_t avail) {
+    const int64_t pairs = (int64_t)s->batch * s->num_kv_heads;
+    // the maxima and denominators come first, rounded up to 256 bytes; the rest holds the numerators
+    const size_t slack = 256;
+    return plan_prefill((int64_t)num_new * (s->num_q_heads / s->num_kv_heads), pairs, s->max_seq_len,
+                        avail > slack ? avail - slack : 0);
+}
+size_t prefill_ml_bytes(const PrefillPlan &pl, const td_shape *s) {
+    const size_t slots = (size_t)pl.row_blocks * s->batch * s->num_kv_heads * pl.chunks * pl.rows_per_wg;
+    return align_up(slots * 2 * sizeof(float), 256);
+}
+}  // namespace
+
+size_t td_prefill_workspace_bytes(const td_shape *shape, int32_t num_new) {
+    td_status code;
+    if (shape_problem(shape, 0, &code) || num_new < 1 || num_new > shape->max_seq_len) return 0;
+    const PrefillPlan pl = prefill_plan_for(shape, num_new, ~(size_t)0);
+    return pl.chunks > 1 ? align_up(kCountersBytes + 256 + pl.part_bytes, 256) : 0;
+}
+
 td_status td_prefill_attend(td_ctx *ctx, const td_shape *shape, int32_t num_new, const void *q, const void *K,
                             const void *V, void *out, void *hip_stream) {
-    td_status st = check_call(ctx, shape, 0, false, q, K, V, out);
+    td_status st = check_call(ctx, shape, 0, false, q, K, V, out, false);
     if (st != TD_OK) return st;
     if (num_new < 1 || num_new > shape->max_seq_len)
         return fail(ctx, TD_ERR_INVALID_ARG, "%s", "num_new outside [1, max_seq_len]");
@@ -465,6 +486,17 @@ td_status td_prefill_attend(td_ctx *ctx, const td_shape *shape, int32_t num_new,
     p.max_seq_len = shape->max_seq_len;
     p.num_new = num_new;
     p.scale = shape->sm_scale > 0.f ? shape->sm_scale : 1.0f / sqrtf((float)shape->head_dim);
+    // token chunks as far as the workspace holds their partial states
+    const size_t avail = ctx->workspace_bytes > kCountersBytes ? ctx->workspace_bytes - kCountersBytes : 0;
+    const PrefillPlan pl = prefill_plan_for(shape, num_new, avail);
+    p.rows_per_wg = pl.rows_per_wg;
+    p.row_blocks = pl.row_blocks;
+    p.chunk = pl.chunk;
+    p.chunks = pl.chunks;
+    if (pl.chunks > 1) {
+        p.part_ml = reinterpret_cast<float *>(ctx->workspace + kCountersBytes);
+        p.part_acc = reinterpret_cast<float *>(ctx->workspace + kCountersBytes + prefill_ml_bytes(pl, shape));
+    }
     const hipError_t e = launch_prefill(shape->num_q_heads / shape->num_kv_heads, p, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return fail(ctx, TD_ERR_HIP, "prefill launch failed: %s", hipGetErrorString(e));
     return TD_OK;

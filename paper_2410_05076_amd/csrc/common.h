@@ -74,15 +74,30 @@ hipError_t launch_attend(int dtype, int head_dim, int group, int waves, int mode
 hipError_t launch_attend_mfma(int group, int waves, int mode, const AttendParams &p, hipStream_t stream);
 
 // Prefill attention over the last num_new tokens of every sequence (bf16, head_dim 128, contiguous cache).
+// The query rows of a KV head are the (token, head) pairs; a workgroup takes rows_per_wg of them and one
+// chunk of the tokens.  With more than one chunk the workgroups leave partial states
+//   part_ml [wg][chunk][rows_per_wg][2], part_acc [wg][chunk][rows_per_wg][128]   (wg = pair * row_blocks + row block)
+// and a second kernel merges them.
 struct PrefillParams {
     const void *q, *K, *V;  // q: [B][num_new][Hq][128]
     void *out;              // like q
     const int32_t *seq_lens;
+    float *part_acc, *part_ml;
     int64_t stride_batch, stride_head, stride_tok;  // elements
     int32_t batch, num_q_heads, num_kv_heads, max_seq_len, num_new;
-    int32_t row_blocks;  // set by the launcher: workgroups per (sequence, KV head)
+    int32_t rows_per_wg;  // 16, 32 or 64
+    int32_t row_blocks;   // workgroups per (sequence, KV head) and chunk
+    int32_t chunk;        // tokens per chunk, a multiple of 64
+    int32_t chunks;       // grid.y
     float scale;
 };
+struct PrefillPlan {
+    int32_t rows_per_wg, row_blocks, chunk, chunks;
+    size_t part_bytes;  // workspace for the partial states (0 with one chunk)
+};
+// Launch shape for `rows` = num_new * group query rows per (sequence, KV head), `pairs` such pairs and
+// up to `part_avail` bytes for partial states.
+PrefillPlan plan_prefill(int64_t rows, int64_t pairs, int32_t max_seq_len, size_t part_avail);
 hipError_t launch_prefill(int group, const PrefillParams &p, hipStream_t stream);
 
 // Mean-of-probabilities rule: prob[b][g][j] = mean over the group's heads of

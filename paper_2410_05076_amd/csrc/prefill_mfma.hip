@@ -28,6 +28,7 @@
 #include "attend_tail.h"
 #include "mfma_util.h"
 
+#include <algorithm>
 #include <type_traits>
 
 namespace tidal {
@@ -94,8 +95,11 @@ __global__ __launch_bounds__(kPThreads) void prefill_mfma_kernel(const PrefillPa
 #pragma unroll
     for (int r = 0; r < R; ++r) limit[r] = row0 + 16 * r + n16 < rows_total ? max(N - P + tkn[r] + 1, 0) : 0;
     const int last_tkn = min(P - 1, (row0 + 16 * R - 1) / G);
-    const int t_end = max(N - P + last_tkn + 1, 0);   // tokens this workgroup streams
+    const int t_end = max(N - P + last_tkn + 1, 0);   // tokens the rows of this block may see
     const int t_full = max(N - P + row0 / G + 1, 0);  // tokens below this one are seen by every row
+    // this workgroup's chunk of them
+    const int c0 = blockIdx.y * p.chunk, c1 = min(c0 + p.chunk, t_end);
+    if (p.chunks > 1 && c0 >= t_end) return;  // the merge kernel knows that this chunk is empty
 
     const int64_t row_bytes = p.stride_tok * 2;
     const int64_t head_off = ((int64_t)b * p.stride_batch + (int64_t)g * p.stride_head) * 2;
@@ -207,11 +211,11 @@ __global__ __launch_bounds__(kPThreads) void prefill_mfma_kernel(const PrefillPa
     // ones; a tile that needs a higher reference maximum leaves the loops, and is taken again
     // after the rescale.
     uint4 kraw[4], vraw[4];
-    int base = wave * 16;
-    if (base < t_end) load_tile(base, kraw, vraw);
+    int base = c0 + wave * 16;
+    if (base < c1) load_tile(base, kraw, vraw);
     auto step = [&](auto masked) -> bool {
         uint4 knext[4], vnext[4];
-        const bool more = base + kPStep < t_end;
+        const bool more = base + kPStep < c1;
         if (more) load_tile(base + kPStep, knext, vnext);
         __builtin_amdgcn_sched_barrier(0);
         if (!consume(masked, base, kraw, vraw)) return false;
@@ -227,8 +231,8 @@ __global__ __launch_bounds__(kPThreads) void prefill_mfma_kernel(const PrefillPa
     };
     for (;;) {
         bool done = true;
-        while (done && base + 16 <= t_full) done = step(std::false_type{});
-        while (done && base < t_end) done = step(std::true_type{});
+        while (done && base + 16 <= min(t_full, c1)) done = step(std::false_type{});
+        while (done && base < c1) done = step(std::true_type{});
         if (done) break;
         raise();
     }
@@ -265,32 +269,102 @@ __global__ __launch_bounds__(kPThreads) void prefill_mfma_kernel(const PrefillPa
                 ls = fmaf(s_l[w][i], wgt, ls);
                 as = fmaf(s_acc[w][i][ch], wgt, as);
             }
-            const int t = row / G, head = row - t * G;
-            store_out<TD_BF16>(p.out, ((((int64_t)b * P + t) * p.num_q_heads + g * G + head) * kPD + ch),
-                               ls > 0.f ? as / ls : 0.f);
+            if (p.chunks > 1) {  // partial state of (row, chunk): maximum, denominator, numerators
+                const int64_t slot = (((int64_t)pair * p.row_blocks + rb) * p.chunks + blockIdx.y) * (16 * R) + 16 * r + i;
+                p.part_acc[slot * kPD + ch] = as;
+                if (ch == 0) *reinterpret_cast<float2 *>(p.part_ml + slot * 2) = make_float2(mx, ls);
+            } else {
+                const int t = row / G, head = row - t * G;
+                store_out<TD_BF16>(p.out, ((((int64_t)b * P + t) * p.num_q_heads + g * G + head) * kPD + ch),
+                                   ls > 0.f ? as / ls : 0.f);
+            }
         }
     }
 }
 
+// Merge of the chunks' partial states: one thread per (row, channel), two rows per workgroup.
+template <int G>
+__global__ __launch_bounds__(2 * kPD) void prefill_merge_kernel(const PrefillParams p) {
+    const int rpw = p.rows_per_wg, P = p.num_new;
+    const int64_t rid = (int64_t)blockIdx.x * 2 + threadIdx.x / kPD;  // over (pair, row block, row in block)
+    const int ch = threadIdx.x % kPD;
+    const int64_t wg = rid / rpw;
+    const int i = (int)(rid - wg * rpw);
+    if (wg >= (int64_t)p.row_blocks * p.num_kv_heads * p.batch) return;
+    const int pair = (int)(wg / p.row_blocks), rb = (int)(wg - (int64_t)pair * p.row_blocks);
+    const int row = rb * rpw + i;
+    if (row >= P * G) return;
+    const int g = pair % p.num_kv_heads, b = pair / p.num_kv_heads;
+    const int N = min(max(p.seq_lens[b], 0), p.max_seq_len);
+    const int last_tkn = min(P - 1, (rb * rpw + rpw - 1) / G);
+    const int t_end = max(N - P + last_tkn + 1, 0);
+    const int nch = min(p.chunks, (t_end + p.chunk - 1) / p.chunk);  // chunks that hold tokens for this row block
+    const float *ml = p.part_ml + (wg * p.chunks * rpw + i) * 2;
+    const float *pa = p.part_acc + (wg * p.chunks * rpw + i) * kPD + ch;
+    float mx = kEmptyMax;
+    for (int c = 0; c < nch; ++c) mx = fmaxf(mx, ml[(int64_t)c * rpw * 2]);
+    float ls = 0.f, as = 0.f;
+#pragma unroll 4
+    for (int c = 0; c < nch; ++c) {
+        const float2 s = *reinterpret_cast<const float2 *>(ml + (int64_t)c * rpw * 2);
+        const float wgt = fast_exp2(s.x - mx);
+        ls = fmaf(s.y, wgt, ls);
+        as = fmaf(pa[(int64_t)c * rpw * kPD], wgt, as);
+    }
+    const int t = row / G, head = row - t * G;
+    store_out<TD_BF16>(p.out, ((((int64_t)b * P + t) * p.num_q_heads + g * G + head) * kPD + ch), ls > 0.f ? as / ls : 0.f);
+}
+
 template <int G, int R>
-hipError_t launch_prefill_rows(PrefillParams p, hipStream_t stream) {
-    p.row_blocks = (p.num_new * G + 16 * R - 1) / (16 * R);
-    const dim3 grid(p.row_blocks * p.num_kv_heads * p.batch), block(kPThreads);
+hipError_t launch_prefill_rows(const PrefillParams &p, hipStream_t stream) {
+    const int pairs = p.num_kv_heads * p.batch;
+    const dim3 grid(p.row_blocks * pairs, p.chunks), block(kPThreads);
     hipLaunchKernelGGL((prefill_mfma_kernel<G, R>), grid, block, 0, stream, p);
+    if (p.chunks > 1) {
+        const int64_t rows = (int64_t)p.row_blocks * pairs * p.rows_per_wg;
+        hipLaunchKernelGGL((prefill_merge_kernel<G>), dim3((unsigned)((rows + 1) / 2)), dim3(2 * kPD), 0, stream, p);
+    }
     return hipGetLastError();
 }
 
-// Rows per workgroup: 64 when that still gives every CU a workgroup, else 32 or 16 (more
-// workgroups, each streaming the keys and values for fewer rows).
 template <int G>
 hipError_t launch_prefill_group(const PrefillParams &p, hipStream_t stream) {
-    const int64_t rows = (int64_t)p.num_new * G, pairs = (int64_t)p.num_kv_heads * p.batch;
-    if ((rows + 63) / 64 * pairs >= 256) return launch_prefill_rows<G, 4>(p, stream);
-    if ((rows + 31) / 32 * pairs >= 256) return launch_prefill_rows<G, 2>(p, stream);
-    return launch_prefill_rows<G, 1>(p, stream);
+    switch (p.rows_per_wg) {
+    case 64: return launch_prefill_rows<G, 4>(p, stream);
+    case 32: return launch_prefill_rows<G, 2>(p, stream);
+    case 16: return launch_prefill_rows<G, 1>(p, stream);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace
+
+// Rows per workgroup: as many of a pair's rows as there are, up to 64 (the keys and values are
+// streamed once per row block).  Few row blocks leave most of the chip idle - and a prefill over
+// few tokens is bound by the stream of the cache, like a decode step - so the tokens are cut into
+// chunks until about two workgroups per CU exist; a chunk is at least 512 tokens (its partial
+// state is rows_per_wg * 520 bytes, written and read once).
+PrefillPlan plan_prefill(int64_t rows, int64_t pairs, int32_t max_seq_len, size_t part_avail) {
+    PrefillPlan pl;
+    pl.rows_per_wg = rows <= 16 ? 16 : rows <= 32 ? 32 : 64;
+    pl.row_blocks = (int32_t)((rows + pl.rows_per_wg - 1) / pl.rows_per_wg);
+    const int64_t wgs = (int64_t)pl.row_blocks * pairs;
+    constexpr int64_t kTargetWgs = 512, kMinChunk = 512;
+    int64_t chunks = (kTargetWgs + wgs - 1) / wgs;
+    chunks = std::min<int64_t>(chunks, std::max<int64_t>(1, max_seq_len / kMinChunk));
+    const size_t per_chunk = (size_t)wgs * pl.rows_per_wg * (kPD + 2) * sizeof(float);
+    if (chunks > 1 && per_chunk * chunks > part_avail) chunks = (int64_t)(part_avail / per_chunk);
+    if (chunks <= 1) {
+        pl.chunks = 1;
+        pl.chunk = (max_seq_len + kPStep - 1) / kPStep * kPStep;
+        pl.part_bytes = 0;
+        return pl;
+    }
+    pl.chunk = (int32_t)(((max_seq_len + chunks - 1) / chunks + kPStep - 1) / kPStep * kPStep);
+    pl.chunks = (max_seq_len + pl.chunk - 1) / pl.chunk;
+    pl.part_bytes = per_chunk * pl.chunks;
+    return pl;
+}
 
 hipError_t launch_prefill(int group, const PrefillParams &p, hipStream_t stream) {
     switch (group) {

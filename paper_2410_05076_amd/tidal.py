@@ -18,7 +18,7 @@ BF16, F32 = 0, 1
 LAYER_DENSE, LAYER_SELECT, LAYER_SPARSE = 0, 1, 2
 
 EXPORTS = ("td_validate", "td_workspace_bytes", "td_topk_workspace_bytes", "td_create", "td_destroy", "td_full_attend",
-           "td_select_tokens", "td_sparse_attend", "td_prefill_attend", "td_topk", "td_decode_step", "td_decode_step_append",
+           "td_select_tokens", "td_sparse_attend", "td_prefill_attend", "td_prefill_workspace_bytes", "td_topk", "td_decode_step", "td_decode_step_append",
            "td_plan_launch", "td_set_tuning", "td_probe_stream",
            "td_status_string", "td_last_error")
 
@@ -85,6 +85,7 @@ def lib():
     L.td_sparse_attend.restype = ctypes.c_int
     L.td_prefill_attend.argtypes = [vp, shp, i32, vp, vp, vp, vp, vp]
     L.td_prefill_attend.restype = ctypes.c_int
+    L.td_prefill_workspace_bytes.argtypes, L.td_prefill_workspace_bytes.restype = [shp, i32], sz
     L.td_topk.argtypes = [vp, vp, i64, i32, vp, i32, i32, i32, vp, vp]
     L.td_topk.restype = ctypes.c_int
     L.td_decode_step.argtypes = [vp, shp, i32, ctypes.POINTER(i32), ctypes.POINTER(vp), ctypes.POINTER(vp),
@@ -145,7 +146,7 @@ def _stream():
 class Tidal:
     """A td_ctx with a workspace sized for one shape and budget."""
 
-    def __init__(self, shape, k, device=None, topk_rows=0, topk_max_len=0):
+    def __init__(self, shape, k, device=None, topk_rows=0, topk_max_len=0, prefill_new=0, workspace_bytes=None):
         L = lib()
         self.device = torch.cuda.current_device() if device is None else device
         need = L.td_workspace_bytes(ctypes.byref(shape), k)
@@ -153,6 +154,10 @@ class Tidal:
             raise TidalError(L.td_validate(ctypes.byref(shape), k), "invalid or unsupported shape")
         if topk_rows:       # also room for stand-alone td_topk calls of this size
             need = max(need, L.td_topk_workspace_bytes(topk_rows, topk_max_len))
+        if prefill_new:     # also room for the token chunks of prefill_attend over this many new tokens
+            need = max(need, L.td_prefill_workspace_bytes(ctypes.byref(shape), prefill_new))
+        if workspace_bytes is not None:   # the caller's own size (td_create's argument as it is)
+            need = workspace_bytes
         self.workspace_bytes = need
         self._ctx = ctypes.c_void_p()
         st = L.td_create(ctypes.byref(self._ctx), self.device, need)

@@ -12,15 +12,16 @@ from test_gpu_parity import DEV, device_layers, host, say
 pytestmark = pytest.mark.gpu
 
 
-def run_prefill(w, num_new, seed=3):
+def run_prefill(w, num_new, seed=3, chunked=True):
     (_, K, V), = device_layers(w, [0])
     g = torch.Generator(device=DEV).manual_seed(seed)
     q = torch.randn((w.batch, num_new, w.num_q_heads, w.head_dim), generator=g, device=DEV).to(torch.bfloat16)
     lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=DEV)
     shape = tidal.make_shape(q[:, 0].contiguous(), K, lens)
-    td = tidal.Tidal(shape, 0)
+    # chunked: a workspace for every token chunk the plan wants; else none, so one chunk
+    td = tidal.Tidal(shape, 0, prefill_new=num_new) if chunked else tidal.Tidal(shape, 0, workspace_bytes=0)
     out = torch.full_like(q, float("nan"))
-    say("prefill %s P=%d" % (w.name, num_new))
+    say("prefill %s P=%d chunked=%s" % (w.name, num_new, chunked))
     td.prefill_attend(shape, q, K, V, out)
     torch.cuda.synchronize()
     check_output(out, O.prefill(host(q), host(K), host(V), w.seq_lens), "prefill %s P=%d" % (w.name, num_new),
@@ -39,8 +40,33 @@ def run_prefill(w, num_new, seed=3):
     ("c4", dict(seq_lens=(900, 33, 64, 2048), k=64), 33),                  # ragged batch, P = N for one
     ("c2", dict(context=40, k=8), 40),                                     # the whole sequence is new
 ])
-def test_prefill_attend(name, over, num_new):
-    run_prefill(W.workload(name, **over), num_new)
+@pytest.mark.parametrize("chunked", [True, False])
+def test_prefill_attend(name, over, num_new, chunked):
+    run_prefill(W.workload(name, **over), num_new, chunked=chunked)
+
+
+def test_prefill_over_many_token_chunks():
+    run_prefill(W.workload("c2", context=20000, k=64), 16)            # 39 chunks of 576 tokens
+
+
+def test_prefill_with_a_workspace_for_some_of_the_chunks():
+    w = W.workload("c2", context=6000, k=64)
+    (_, K, V), = device_layers(w, [0])
+    g = torch.Generator(device=DEV).manual_seed(5)
+    q = torch.randn((1, 16, w.num_q_heads, w.head_dim), generator=g, device=DEV).to(torch.bfloat16)
+    lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=DEV)
+    shape = tidal.make_shape(q[:, 0].contiguous(), K, lens)
+    full = tidal.lib().td_prefill_workspace_bytes(shape, 16)
+    assert full > 0
+    ref = O.prefill(host(q), host(K), host(V), w.seq_lens)
+    for ws in (full, full // 2, full // 4):
+        td = tidal.Tidal(shape, 0, workspace_bytes=ws)
+        out = torch.full_like(q, float("nan"))
+        say("prefill with %d workspace bytes" % ws)
+        td.prefill_attend(shape, q, K, V, out)
+        torch.cuda.synchronize()
+        check_output(out, ref, "workspace %d" % ws, single_bf16_p=True)
+        td.close()
 
 
 def test_prefill_longer_than_a_sequence_yields_zeros_for_the_missing_tokens():

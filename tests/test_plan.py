@@ -87,3 +87,20 @@ def test_plan_rejects_bad_arguments():
     assert L.td_plan_launch(None, ctypes.byref(shape(head_dim=96, kv_stride_tok=96)), DENSE, 0,
                             ctypes.byref(plan)) == tidal.ERR_UNSUPPORTED
     assert L.td_plan_launch(None, ctypes.byref(shape()), DENSE, 0, None) == tidal.ERR_INVALID_ARG
+
+
+def test_prefill_workspace_covers_token_chunks_only_when_rows_are_few():
+    L = tidal.lib()
+    c2 = shape()
+    # 16 new tokens x 4 heads per KV head = one row block per (sequence, KV head): 8 workgroups, so
+    # the tokens are cut into 64 chunks of 512 and every chunk leaves 64 rows x 130 floats per pair
+    need = L.td_prefill_workspace_bytes(ctypes.byref(c2), 16)
+    parts = 8 * 64 * 64 * 130 * 4
+    assert parts <= need <= parts + 65536 * 4 + 1024
+    # 4096 new tokens fill the GPU with row blocks alone: no chunks, no workspace
+    assert L.td_prefill_workspace_bytes(ctypes.byref(c2), 4096) == 0
+    # a short cache cannot be cut below 512 tokens per chunk
+    assert L.td_prefill_workspace_bytes(ctypes.byref(shape(n=600)), 16) == 0
+    # invalid arguments
+    assert L.td_prefill_workspace_bytes(ctypes.byref(c2), 0) == 0
+    assert L.td_prefill_workspace_bytes(ctypes.byref(c2), 40000) == 0
