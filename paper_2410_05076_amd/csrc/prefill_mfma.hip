@@ -282,15 +282,18 @@ __global__ __launch_bounds__(kPThreads) void prefill_mfma_kernel(const PrefillPa
     }
 }
 
-// Merge of the chunks' partial states: one thread per (row, channel), two rows per workgroup.
+// Merge of the chunks' partial states: one workgroup per row, thread = (channel, one of four
+// interleaved sets of chunks), so that every thread's loads are independent and few.
+constexpr int kMergeSets = 4;
+constexpr int kPrefillChunksMax = 512;
 template <int G>
-__global__ __launch_bounds__(2 * kPD) void prefill_merge_kernel(const PrefillParams p) {
+__global__ __launch_bounds__(kMergeSets * kPD) void prefill_merge_kernel(const PrefillParams p) {
+    __shared__ float s_m[kPrefillChunksMax], s_l[kPrefillChunksMax], s_part[kMergeSets][kPD];
     const int rpw = p.rows_per_wg, P = p.num_new;
-    const int64_t rid = (int64_t)blockIdx.x * 2 + threadIdx.x / kPD;  // over (pair, row block, row in block)
-    const int ch = threadIdx.x % kPD;
+    const int64_t rid = blockIdx.x;  // over (pair, row block, row in block)
+    const int ch = threadIdx.x % kPD, set = threadIdx.x / kPD;
     const int64_t wg = rid / rpw;
     const int i = (int)(rid - wg * rpw);
-    if (wg >= (int64_t)p.row_blocks * p.num_kv_heads * p.batch) return;
     const int pair = (int)(wg / p.row_blocks), rb = (int)(wg - (int64_t)pair * p.row_blocks);
     const int row = rb * rpw + i;
     if (row >= P * G) return;
@@ -301,16 +304,24 @@ __global__ __launch_bounds__(2 * kPD) void prefill_merge_kernel(const PrefillPar
     const int nch = min(p.chunks, (t_end + p.chunk - 1) / p.chunk);  // chunks that hold tokens for this row block
     const float *ml = p.part_ml + (wg * p.chunks * rpw + i) * 2;
     const float *pa = p.part_acc + (wg * p.chunks * rpw + i) * kPD + ch;
-    float mx = kEmptyMax;
-    for (int c = 0; c < nch; ++c) mx = fmaxf(mx, ml[(int64_t)c * rpw * 2]);
-    float ls = 0.f, as = 0.f;
-#pragma unroll 4
-    for (int c = 0; c < nch; ++c) {
+    for (int c = threadIdx.x; c < nch; c += kMergeSets * kPD) {
         const float2 s = *reinterpret_cast<const float2 *>(ml + (int64_t)c * rpw * 2);
-        const float wgt = fast_exp2(s.x - mx);
-        ls = fmaf(s.y, wgt, ls);
-        as = fmaf(pa[(int64_t)c * rpw * kPD], wgt, as);
+        s_m[c] = s.x;
+        s_l[c] = s.y;
     }
+    __syncthreads();
+    float mx = kEmptyMax;
+    for (int c = 0; c < nch; ++c) mx = fmaxf(mx, s_m[c]);
+    float as = 0.f;
+#pragma unroll 8
+    for (int c = set; c < nch; c += kMergeSets) as = fmaf(pa[(int64_t)c * rpw * kPD], fast_exp2(s_m[c] - mx), as);
+    s_part[set][ch] = as;
+    __syncthreads();
+    if (set) return;
+    float ls = 0.f;
+    for (int c = 0; c < nch; ++c) ls = fmaf(s_l[c], fast_exp2(s_m[c] - mx), ls);
+#pragma unroll
+    for (int s = 1; s < kMergeSets; ++s) as += s_part[s][ch];
     const int t = row / G, head = row - t * G;
     store_out<TD_BF16>(p.out, ((((int64_t)b * P + t) * p.num_q_heads + g * G + head) * kPD + ch), ls > 0.f ? as / ls : 0.f);
 }
@@ -322,7 +333,7 @@ hipError_t launch_prefill_rows(const PrefillParams &p, hipStream_t stream) {
     hipLaunchKernelGGL((prefill_mfma_kernel<G, R>), grid, block, 0, stream, p);
     if (p.chunks > 1) {
         const int64_t rows = (int64_t)p.row_blocks * pairs * p.rows_per_wg;
-        hipLaunchKernelGGL((prefill_merge_kernel<G>), dim3((unsigned)((rows + 1) / 2)), dim3(2 * kPD), 0, stream, p);
+        hipLaunchKernelGGL((prefill_merge_kernel<G>), dim3((unsigned)rows), dim3(kMergeSets * kPD), 0, stream, p);
     }
     return hipGetLastError();
 }
@@ -339,19 +350,21 @@ hipError_t launch_prefill_group(const PrefillParams &p, hipStream_t stream) {
 
 }  // namespace
 
-// Rows per workgroup: as many of a pair's rows as there are, up to 64 (the keys and values are
-// streamed once per row block).  Few row blocks leave most of the chip idle - and a prefill over
-// few tokens is bound by the stream of the cache, like a decode step - so the tokens are cut into
-// chunks until about two workgroups per CU exist; a chunk is at least 512 tokens (its partial
-// state is rows_per_wg * 520 bytes, written and read once).
+// Rows per workgroup: 64 (the keys and values are streamed once per row block, and the R = 4
+// kernel does the most arithmetic per byte loaded), but 32 at most for a pair with no more than
+// 64 rows: such a prefill is bound by the stream of the cache, like a decode step, and the
+// smaller kernel keeps two waves per SIMD with their loads in flight.  Few row blocks leave most
+// of the chip idle, so the tokens are cut into chunks until every CU has a workgroup; more
+// chunks than that measured slower at every size (each adds a partial state of rows_per_wg * 520
+// bytes, an epilogue and merge work).  A chunk is at least 512 tokens.
 PrefillPlan plan_prefill(int64_t rows, int64_t pairs, int32_t max_seq_len, size_t part_avail) {
     PrefillPlan pl;
-    pl.rows_per_wg = rows <= 16 ? 16 : rows <= 32 ? 32 : 64;
+    pl.rows_per_wg = rows <= 16 ? 16 : rows <= 64 ? 32 : 64;
     pl.row_blocks = (int32_t)((rows + pl.rows_per_wg - 1) / pl.rows_per_wg);
     const int64_t wgs = (int64_t)pl.row_blocks * pairs;
-    constexpr int64_t kTargetWgs = 512, kMinChunk = 512;
+    constexpr int64_t kTargetWgs = 256, kMinChunk = 512;
     int64_t chunks = (kTargetWgs + wgs - 1) / wgs;
-    chunks = std::min<int64_t>(chunks, std::max<int64_t>(1, max_seq_len / kMinChunk));
+    chunks = std::min<int64_t>({chunks, std::max<int64_t>(1, max_seq_len / kMinChunk), (int64_t)kPrefillChunksMax});
     const size_t per_chunk = (size_t)wgs * pl.rows_per_wg * (kPD + 2) * sizeof(float);
     if (chunks > 1 && per_chunk * chunks > part_avail) chunks = (int64_t)(part_avail / per_chunk);
     if (chunks <= 1) {

@@ -92,10 +92,10 @@ def test_plan_rejects_bad_arguments():
 def test_prefill_workspace_covers_token_chunks_only_when_rows_are_few():
     L = tidal.lib()
     c2 = shape()
-    # 16 new tokens x 4 heads per KV head = one row block per (sequence, KV head): 8 workgroups, so
-    # the tokens are cut into 64 chunks of 512 and every chunk leaves 64 rows x 130 floats per pair
+    # 16 new tokens x 4 heads per KV head = 64 rows = two row blocks of 32 per (sequence, KV head): 16
+    # workgroups, so the tokens are cut into 16 chunks of 2048 and every chunk leaves 32 rows x 130 floats
     need = L.td_prefill_workspace_bytes(ctypes.byref(c2), 16)
-    parts = 8 * 64 * 64 * 130 * 4
+    parts = 16 * 16 * 32 * 130 * 4
     assert parts <= need <= parts + 65536 * 4 + 1024
     # 4096 new tokens fill the GPU with row blocks alone: no chunks, no workspace
     assert L.td_prefill_workspace_bytes(ctypes.byref(c2), 4096) == 0
