@@ -85,7 +85,7 @@ struct PrefillParams {
     float *part_acc, *part_ml;
     int64_t stride_batch, stride_head, stride_tok;  // elements
     int32_t batch, num_q_heads, num_kv_heads, max_seq_len, num_new;
-    int32_t rows_per_wg;  // 16, 32 or 64
+    int32_t rows_per_wg;  // 32 or 64
     int32_t row_blocks;   // workgroups per (sequence, KV head) and chunk
     int32_t chunk;        // tokens per chunk, a multiple of 64
     int32_t chunks;       // grid.y

@@ -4,14 +4,15 @@
 // contiguous cache.
 //
 // The query rows of a KV head are the (token, head) pairs, row = token * G + head.  A workgroup
-// of four wave64s takes R * 16 consecutive rows and streams the cache once for all of them, up to
-// the last position any of its rows may see; the waves split the tokens (16-token tiles,
-// interleaved) and every wave keeps an online-softmax state for all R * 16 rows, so a K or V tile
-// is loaded once per wave and used by R row tiles.  Per tile: S^T = K Q^T with
+// of four wave64s takes R * 16 consecutive rows (R = 4 or 2) and one chunk of the tokens, up to
+// the last position any of its rows may see; the waves split the chunk's 32-token tiles
+// (interleaved) and every wave keeps an online-softmax state for all R * 16 rows, so a K or V tile
+// is loaded once per wave and used by R row tiles.  Per tile half: S^T = K Q^T with
 // v_mfma_f32_16x16x32_bf16 (K from memory straight into the A operand; a lane then holds four
-// tokens of one query row), P = exp2(S^T scale log2(e) - m) rounded to bf16 once
-// (v_cvt_pk_bf16_f32), and O^T += V^T P^T with v_mfma_f32_16x16x16_bf16, so that a lane's
-// accumulators all belong to its own query row and the row's state (m, l) needs no shuffle.
+// tokens of one query row); then P = exp2(S^T scale log2(e) - m) rounded to bf16 once
+// (v_cvt_pk_bf16_f32), and O^T += V^T P^T over the tile's 32 tokens, again with
+// v_mfma_f32_16x16x32_bf16 (twice the rate of the 16-deep form), so that a lane's accumulators
+// all belong to its own query row and the row's state (m, l) needs no shuffle.
 //
 // The reference maximum m of a row is lazy: it is raised (and the row's accumulators rescaled)
 // only when a logit exceeds it by more than kLazyMax in log2 units, so p <= 2^kLazyMax, far
@@ -19,12 +20,14 @@
 // cross-lane step; after the first tile the rescale branch is practically never taken.  Tiles
 // that every row of the workgroup sees in full run without masks and with wave-uniform load
 // addresses; only the last tiles (the causal diagonal and the ragged end) take the masked path.
-// The four waves' states are folded through LDS, one row tile at a time, and the rows are written
-// out; there is no split across workgroups, so no partials and no workspace.
+// The four waves' states are folded through LDS, one row tile at a time.  With one chunk the rows
+// are written out; with more, the folded state goes to the workspace and prefill_merge_kernel
+// combines the chunks.
 //
-// Per 16-token tile and wave: 8 loads of 16 bytes per lane, R * 12 MFMAs (R * 98304 flop, 128
-// matrix-core cycles per row tile) and about 20 + R * 22 vector instructions, four of them
-// quarter-rate exponentials per row tile: the vector ALU and the matrix core are about balanced.
+// Per 32-token tile and wave: 16 loads of 16 bytes per lane, R * 17 MFMAs (R * 196608 flop, 272
+// matrix-core cycles per row tile) and about 40 + R * 45 vector instructions, eight of them
+// quarter-rate exponentials per row tile: the vector ALU and the matrix core are about balanced,
+// and with one wave per SIMD they overlap only as far as the instruction order lets them.
 #include "attend_tail.h"
 #include "mfma_util.h"
 
@@ -37,7 +40,8 @@ namespace {
 constexpr int kPD = 128;
 constexpr int kPWaves = 4;
 constexpr int kPThreads = kPWaves * kWave;
-constexpr int kPStep = kPWaves * 16;  // tokens between two tiles of one wave
+constexpr int kPTile = 32;                // tokens per tile
+constexpr int kPStep = kPWaves * kPTile;  // tokens between two tiles of one wave
 constexpr float kLazyMax = 8.f;       // a row's reference maximum may trail its true one by this (log2 units)
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -48,7 +52,8 @@ __device__ __forceinline__ uint32_t bf16_pair(float lo, float hi) {
 }
 
 template <int G, int R>
-__global__ __launch_bounds__(kPThreads) void prefill_mfma_kernel(const PrefillParams p) {
+__global__ __launch_bounds__(kPThreads)
+void prefill_mfma_kernel(const PrefillParams p) {
     // Workgroups are handed to the eight XCDs round-robin by their linear index.  The row blocks of
     // one (sequence, KV head) stream the same keys and values at about the same pace, so they
     // should share an L2: with a multiple of eight (sequence, KV head) pairs, the linear index is
@@ -112,7 +117,8 @@ __global__ __launch_bounds__(kPThreads) void prefill_mfma_kernel(const PrefillPa
     float m_use[R];   // reference maximum of row n16 (the same in its four lanes)
     f32x4 acc[R][8];  // acc[r][e][i]: row n16 of tile r, channel 8 (4 kb + i) + e
     f32x4 lacc[R];    // every element: l of row n16
-    const s16x4 ones = {0x3f80, 0x3f80, 0x3f80, 0x3f80};
+    const uint32_t one2 = 0x3f803f80u;  // bf16 (1, 1)
+    const bf16x8 ones = __builtin_bit_cast(bf16x8, make_uint4(one2, one2, one2, one2));
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         m_use[r] = kEmptyMax;
@@ -122,73 +128,129 @@ __global__ __launch_bounds__(kPThreads) void prefill_mfma_kernel(const PrefillPa
     }
     const float scale2 = p.scale * kLog2e;
 
-    // K: token base + n16, d-octets kb + 4 s; V: tokens base + 4 kb + u, channels 8 n16 .. + 7.
-    // A tile whose 16 tokens all exist is addressed as a wave-uniform base plus a constant lane
-    // offset; the last, partial tile clamps its tokens to the last one streamed (masked below).
+    // A tile is 32 tokens, two halves h of 16.  K: token base + 16 h + n16, d-octets kb + 4 s;
+    // V: tokens base + 16 h + 4 kb + u, channels 8 n16 .. + 7.  A tile whose tokens all exist is
+    // addressed as a wave-uniform base plus a constant lane offset; the last, partial tile clamps
+    // its tokens to the last one streamed (masked below).
     const uint32_t k_lane = (uint32_t)(n16 * row_bytes) + kb * 16, v_lane = (uint32_t)(4 * kb * row_bytes) + n16 * 16;
-    auto load_tile = [&](int base, uint4 (&kr)[4], uint4 (&vr)[4]) {
-        if (base + 16 <= t_end) {
-            const char *kt = Kh + (int64_t)base * row_bytes, *vt = Vh + (int64_t)base * row_bytes;
+    uint4 kr[2][4], vr[2][4];
+    auto load_tile = [&](int base, uint4 (&kr)[2][4], uint4 (&vr)[2][4]) {
+        if (base + kPTile <= t_end) {
 #pragma unroll
-            for (int s = 0; s < 4; ++s) kr[s] = *reinterpret_cast<const uint4 *>(kt + k_lane + 64 * s);
+            for (int h = 0; h < 2; ++h) {
+                const char *kt = Kh + (int64_t)(base + 16 * h) * row_bytes, *vt = Vh + (int64_t)(base + 16 * h) * row_bytes;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) vr[u] = *reinterpret_cast<const uint4 *>(vt + u * row_bytes + v_lane);
+                for (int s = 0; s < 4; ++s) kr[h][s] = *reinterpret_cast<const uint4 *>(kt + k_lane + 64 * s);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) vr[h][u] = *reinterpret_cast<const uint4 *>(vt + u * row_bytes + v_lane);
+            }
         } else {
-            const char *kp = Kh + (int64_t)min(base + n16, t_end - 1) * row_bytes + kb * 16;
 #pragma unroll
-            for (int s = 0; s < 4; ++s) kr[s] = *reinterpret_cast<const uint4 *>(kp + 64 * s);
+            for (int h = 0; h < 2; ++h) {
+                const char *kp = Kh + (int64_t)min(base + 16 * h + n16, t_end - 1) * row_bytes + kb * 16;
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
-                vr[u] = *reinterpret_cast<const uint4 *>(Vh + (int64_t)min(base + 4 * kb + u, t_end - 1) * row_bytes +
-                                                         n16 * 16);
+                for (int s = 0; s < 4; ++s) kr[h][s] = *reinterpret_cast<const uint4 *>(kp + 64 * s);
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    vr[h][u] = *reinterpret_cast<const uint4 *>(
+                        Vh + (int64_t)min(base + 16 * h + 4 * kb + u, t_end - 1) * row_bytes + n16 * 16);
+            }
         }
     };
 
-    // One 16-token tile against the R row tiles.  kMasked: per-row causal limits apply.  Returns
-    // false, with nothing accumulated, when some reference maximum has to be raised first.
+    // One 32-token tile against the R row tiles.  kMasked: per-row causal limits apply.  Returns
+    // false, with nothing accumulated and the tile's registers intact, when some reference maximum
+    // has to be raised first.  The next tile's loads: with R = 4 (one wave per SIMD fits the
+    // registers, a long tile) they go into the registers of this tile as soon as its keys are
+    // multiplied and its values are in operand order; the smaller variants, whose tiles are too
+    // short to cover the latency that way, load into a second set of registers before anything else.
     float top[R];  // largest scaled logit of this lane in the tile, per row tile
-    auto consume = [&](auto masked, int base, const uint4 (&kr)[4], const uint4 (&vr)[4]) -> bool {
+    int base = c0 + wave * kPTile;
+    auto consume = [&](auto masked) -> bool {
         constexpr bool kMasked = decltype(masked)::value;
-        // V^T as A operand: for channel group e, tokens 4kb .. 4kb+3 of channel 8 n16 + e
-        s16x4 vf[8];
-        {
-            const uint32_t vw[4][4] = {{vr[0].x, vr[0].y, vr[0].z, vr[0].w},
-                                       {vr[1].x, vr[1].y, vr[1].z, vr[1].w},
-                                       {vr[2].x, vr[2].y, vr[2].z, vr[2].w},
-                                       {vr[3].x, vr[3].y, vr[3].z, vr[3].w}};
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                vf[e] = pack_pairs(vw[1][e >> 1], vw[0][e >> 1], vw[3][e >> 1], vw[2][e >> 1],
-                                   (e & 1) ? kHighHalves : kLowHalves);
+        constexpr bool kInPlace = R == 4;
+        const bool more = base + kPStep < c1;
+        uint4 kn[kInPlace ? 1 : 2][4], vn[kInPlace ? 1 : 2][4];
+        if constexpr (!kInPlace) {
+            if (more) load_tile(base + kPStep, kn, vn);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        const int t_lane = base + 4 * kb;  // this lane's logits are for tokens t_lane .. t_lane + 3
-        f32x4 st[R];
+        const int t_lane = base + 4 * kb;  // this lane's logits are for tokens t_lane + 16 h + i
+        f32x4 st[R][2];
         bool grow = false;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            st[r] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int s = 0; s < 4; ++s)
-                st[r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kr[s]), qfrag[r][s], st[r], 0, 0, 0);
-            if (kMasked) {
+            for (int h = 0; h < 2; ++h) {
+                st[r][h] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int i = 0; i < 4; ++i) st[r][i] = t_lane + i < limit[r] ? st[r][i] : -INFINITY;
+                for (int s = 0; s < 4; ++s)
+                    st[r][h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kr[h][s]), qfrag[r][s],
+                                                                       st[r][h], 0, 0, 0);
+                if (kMasked) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) st[r][h][i] = t_lane + 16 * h + i < limit[r] ? st[r][h][i] : -INFINITY;
+                }
             }
-            top[r] = fmaxf(fmaxf(st[r][0], st[r][1]), fmaxf(st[r][2], st[r][3])) * scale2;  // scale2 > 0
+            top[r] = fmaxf(fmaxf(fmaxf(st[r][0][0], st[r][0][1]), fmaxf(st[r][0][2], st[r][0][3])),
+                           fmaxf(fmaxf(st[r][1][0], st[r][1][1]), fmaxf(st[r][1][2], st[r][1][3]))) * scale2;  // scale2 > 0
             grow |= top[r] > m_use[r] + kLazyMax;
         }
         if (__builtin_expect(__any(grow), 0)) return false;
+        // V^T as A operand: for channel group e, the lane's eight tokens (4kb .. 4kb+3 of either
+        // half) of channel 8 n16 + e
+        bf16x8 vf[8];
+        {
+            uint32_t vw[2][4][4];
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    vw[h][u][0] = vr[h][u].x;
+                    vw[h][u][1] = vr[h][u].y;
+                    vw[h][u][2] = vr[h][u].z;
+                    vw[h][u][3] = vr[h][u].w;
+                }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t sel = (e & 1) ? kHighHalves : kLowHalves;
+                const int w = e >> 1;
+                vf[e] = __builtin_bit_cast(
+                    bf16x8, make_uint4(__builtin_amdgcn_perm(vw[0][1][w], vw[0][0][w], sel), __builtin_amdgcn_perm(vw[0][3][w], vw[0][2][w], sel),
+                                       __builtin_amdgcn_perm(vw[1][1][w], vw[1][0][w], sel), __builtin_amdgcn_perm(vw[1][3][w], vw[1][2][w], sel)));
+            }
+        }
+        if constexpr (kInPlace) {
+            __builtin_amdgcn_sched_barrier(0);
+            if (more) load_tile(base + kPStep, kr, vr);
+            __builtin_amdgcn_sched_barrier(0);
+        }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            float pr[4];
+            float pr[2][4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) pr[i] = fast_exp2(fmaf(st[r][i], scale2, -m_use[r]));
-            // P^T as B operand: tokens 4kb .. 4kb+3 of row n16, rounded to bf16
-            const s16x4 pa = __builtin_bit_cast(s16x4, make_uint2(bf16_pair(pr[0], pr[1]), bf16_pair(pr[2], pr[3])));
+            for (int h = 0; h < 2; ++h)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[r][e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vf[e], pa, acc[r][e], 0, 0, 0);
-            lacc[r] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ones, pa, lacc[r], 0, 0, 0);
+                for (int i = 0; i < 4; ++i) pr[h][i] = fast_exp2(fmaf(st[r][h][i], scale2, -m_use[r]));
+            // P^T as B operand: the lane's eight tokens of row n16, rounded to bf16
+            const bf16x8 pb = __builtin_bit_cast(bf16x8, make_uint4(bf16_pair(pr[0][0], pr[0][1]), bf16_pair(pr[0][2], pr[0][3]),
+                                                                   bf16_pair(pr[1][0], pr[1][1]), bf16_pair(pr[1][2], pr[1][3])));
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[r][e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[e], pb, acc[r][e], 0, 0, 0);
+            lacc[r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb, lacc[r], 0, 0, 0);
         }
+        if constexpr (!kInPlace) {
+            if (more) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int s = 0; s < 4; ++s) {
+                        kr[h][s] = kn[h][s];
+                        vr[h][s] = vn[h][s];
+                    }
+            }
+        }
+        base += kPStep;
         return true;
     };
     // Rare (after a row's first tile practically never): bring every row's reference maximum up
@@ -206,33 +268,13 @@ __global__ __launch_bounds__(kPThreads) void prefill_mfma_kernel(const PrefillPa
         }
     };
 
-    // The next tile's loads are issued before the current tile is consumed (one wave per SIMD fits
-    // the registers, so nothing else hides the latency).  Unmasked tiles first, then the masked
-    // ones; a tile that needs a higher reference maximum leaves the loops, and is taken again
-    // after the rescale.
-    uint4 kraw[4], vraw[4];
-    int base = c0 + wave * 16;
-    if (base < c1) load_tile(base, kraw, vraw);
-    auto step = [&](auto masked) -> bool {
-        uint4 knext[4], vnext[4];
-        const bool more = base + kPStep < c1;
-        if (more) load_tile(base + kPStep, knext, vnext);
-        __builtin_amdgcn_sched_barrier(0);
-        if (!consume(masked, base, kraw, vraw)) return false;
-        if (more) {
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                kraw[s] = knext[s];
-                vraw[s] = vnext[s];
-            }
-        }
-        base += kPStep;
-        return true;
-    };
+    // Unmasked tiles first, then the masked ones; a tile that needs a higher reference maximum
+    // leaves the loops, and is taken again after the rescale.
+    if (base < c1) load_tile(base, kr, vr);
     for (;;) {
         bool done = true;
-        while (done && base + 16 <= min(t_full, c1)) done = step(std::false_type{});
-        while (done && base < c1) done = step(std::true_type{});
+        while (done && base + kPTile <= min(t_full, c1)) done = consume(std::false_type{});
+        while (done && base < c1) done = consume(std::true_type{});
         if (done) break;
         raise();
     }
@@ -343,7 +385,6 @@ hipError_t launch_prefill_group(const PrefillParams &p, hipStream_t stream) {
     switch (p.rows_per_wg) {
     case 64: return launch_prefill_rows<G, 4>(p, stream);
     case 32: return launch_prefill_rows<G, 2>(p, stream);
-    case 16: return launch_prefill_rows<G, 1>(p, stream);
     default: return hipErrorInvalidValue;
     }
 }
@@ -351,15 +392,15 @@ hipError_t launch_prefill_group(const PrefillParams &p, hipStream_t stream) {
 }  // namespace
 
 // Rows per workgroup: 64 (the keys and values are streamed once per row block, and the R = 4
-// kernel does the most arithmetic per byte loaded), but 32 at most for a pair with no more than
-// 64 rows: such a prefill is bound by the stream of the cache, like a decode step, and the
-// smaller kernel keeps two waves per SIMD with their loads in flight.  Few row blocks leave most
-// of the chip idle, so the tokens are cut into chunks until every CU has a workgroup; more
-// chunks than that measured slower at every size (each adds a partial state of rows_per_wg * 520
-// bytes, an epilogue and merge work).  A chunk is at least 512 tokens.
+// kernel does the most arithmetic per byte loaded), but 32 for a pair with no more than 128
+// rows: such a prefill is bound by the stream of the cache, like a decode step, and the R = 2
+// kernel has the registers to load a whole tile ahead.  Few row blocks leave most of the chip
+// idle, so the tokens are cut into chunks until every CU has a workgroup; more chunks than that
+// measured slower at every size (each adds a partial state of rows_per_wg * 520 bytes, an
+// epilogue and merge work).  A chunk is at least 512 tokens.
 PrefillPlan plan_prefill(int64_t rows, int64_t pairs, int32_t max_seq_len, size_t part_avail) {
     PrefillPlan pl;
-    pl.rows_per_wg = rows <= 16 ? 16 : rows <= 64 ? 32 : 64;
+    pl.rows_per_wg = rows <= 128 ? 32 : 64;
     pl.row_blocks = (int32_t)((rows + pl.rows_per_wg - 1) / pl.rows_per_wg);
     const int64_t wgs = (int64_t)pl.row_blocks * pairs;
     constexpr int64_t kTargetWgs = 256, kMinChunk = 512;
