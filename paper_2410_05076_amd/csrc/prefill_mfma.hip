@@ -178,19 +178,24 @@ void prefill_mfma_kernel(const PrefillParams p) {
         const int t_lane = base + 4 * kb;  // this lane's logits are for tokens t_lane + 16 h + i
         f32x4 st[R][2];
         bool grow = false;
+        // the 2 R chains of four dependent MFMAs advance together, so that none waits for its own result
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
+        for (int r = 0; r < R; ++r) st[r][0] = st[r][1] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                st[r][h] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int s = 0; s < 4; ++s)
 #pragma unroll
-                for (int s = 0; s < 4; ++s)
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
                     st[r][h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kr[h][s]), qfrag[r][s],
                                                                        st[r][h], 0, 0, 0);
-                if (kMasked) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if (kMasked) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
 #pragma unroll
                     for (int i = 0; i < 4; ++i) st[r][h][i] = t_lane + 16 * h + i < limit[r] ? st[r][h][i] : -INFINITY;
-                }
             }
             top[r] = fmaxf(fmaxf(fmaxf(st[r][0][0], st[r][0][1]), fmaxf(st[r][0][2], st[r][0][3])),
                            fmaxf(fmaxf(st[r][1][0], st[r][1][1]), fmaxf(st[r][1][2], st[r][1][3]))) * scale2;  // scale2 > 0
