@@ -274,9 +274,11 @@ def main():
 
 
 def prefill_bench(args, torch, tidal, W, dev):
-    """Time of td_prefill_attend for P new tokens per sequence on one layer's cache, against the dense MFMA peak.
+    """Time of td_prefill_attend for P new tokens per sequence on one layer's cache, against the higher of its two
+    floors: the stream of the cache from HBM (few new tokens) or the dense MFMA peak (many).
 
-    flop = 4 * d * sum over tokens and heads of the positions each token sees (two products, multiply-add)."""
+    flop = 4 * d * sum over tokens and heads of the positions each token sees (two products, multiply-add);
+    bytes = the keys and values of all positions, once."""
     over = {}
     if args.num_q_heads:
         over["num_q_heads"] = args.num_q_heads
@@ -307,15 +309,26 @@ def prefill_bench(args, torch, tidal, W, dev):
     us = sum(ts) / len(ts)
     seen = sum(sum(max(n - P + j + 1, 0) for j in range(P)) for n in w.seq_lens)
     flop = 4.0 * w.head_dim * w.num_q_heads * seen
-    tflops = flop / (us * 1e-6) / 1e12
+    # the keys and values of every position some new token sees, once
+    esize = 2 if w.dtype == "bf16" else 4
+    kv_bytes = 2.0 * w.num_kv_heads * w.head_dim * esize * sum(w.seq_lens)
     td.close()
+    # whichever of the two floors is higher for this P names the bound
+    if kv_bytes / 8.0e12 > flop / 2.5e15:
+        rate = kv_bytes / (us * 1e-6) / 1e9
+        roof = {"kernel": "prefill_mfma_kernel + prefill_merge_kernel", "bound": "hbm", "achieved": round(rate, 1),
+                "peak": 8000.0, "unit": "GB/s", "frac": round(rate / 8000.0, 4), "traffic": None,
+                "bytes_per_launch": kv_bytes, "flop_per_launch": flop}
+    else:
+        tflops = flop / (us * 1e-6) / 1e12
+        roof = {"kernel": "prefill_mfma_kernel", "bound": "mfma", "achieved": round(tflops, 1), "peak": 2500.0,
+                "unit": "TFLOP/s", "frac": round(tflops / 2500.0, 4), "traffic": None, "flop_per_launch": flop,
+                "bytes_per_launch": kv_bytes}
     return {"metric": "prefill_attention_us", "value": round(us, 2), "unit": "us", "n_gpus": 1, "steps": args.steps,
             "warmup": args.warmup, "ms_per_step": round(us / 1e3, 5), "higher_is_better": False, "scaling": "weak",
             "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
             "config": {"workload": DESCRIPTIONS[w.name] + ", one layer, prefill attention over the last %d tokens" % P},
-            "median_us": round(ts[len(ts) // 2], 2),
-            "roofline": {"kernel": "prefill_mfma_kernel", "bound": "mfma", "achieved": round(tflops, 1), "peak": 2500.0,
-                         "unit": "TFLOP/s", "frac": round(tflops / 2500.0, 4), "traffic": None, "flop_per_launch": flop}}
+            "median_us": round(ts[len(ts) // 2], 2), "roofline": roof}
 
 
 def hbm_probe(torch, tidal, dev, td=None, nbytes=2**30, reps=6):
