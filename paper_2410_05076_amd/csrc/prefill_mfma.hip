@@ -134,16 +134,19 @@ void prefill_mfma_kernel(const PrefillParams p) {
     // its tokens to the last one streamed (masked below).
     const uint32_t k_lane = (uint32_t)(n16 * row_bytes) + kb * 16, v_lane = (uint32_t)(4 * kb * row_bytes) + n16 * 16;
     uint4 kr[2][4], vr[2][4];
+    auto load_full = [&](int base, uint4 (&kr)[2][4], uint4 (&vr)[2][4]) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const char *kt = Kh + (int64_t)(base + 16 * h) * row_bytes, *vt = Vh + (int64_t)(base + 16 * h) * row_bytes;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) kr[h][s] = *reinterpret_cast<const uint4 *>(kt + k_lane + 64 * s);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) vr[h][u] = *reinterpret_cast<const uint4 *>(vt + u * row_bytes + v_lane);
+        }
+    };
     auto load_tile = [&](int base, uint4 (&kr)[2][4], uint4 (&vr)[2][4]) {
         if (base + kPTile <= t_end) {
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const char *kt = Kh + (int64_t)(base + 16 * h) * row_bytes, *vt = Vh + (int64_t)(base + 16 * h) * row_bytes;
-#pragma unroll
-                for (int s = 0; s < 4; ++s) kr[h][s] = *reinterpret_cast<const uint4 *>(kt + k_lane + 64 * s);
-#pragma unroll
-                for (int u = 0; u < 4; ++u) vr[h][u] = *reinterpret_cast<const uint4 *>(vt + u * row_bytes + v_lane);
-            }
+            load_full(base, kr, vr);
         } else {
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
@@ -158,7 +161,8 @@ void prefill_mfma_kernel(const PrefillParams p) {
         }
     };
 
-    // One 32-token tile against the R row tiles.  kMasked: per-row causal limits apply.  Returns
+    // One 32-token tile against the R row tiles.  kMasked: per-row causal limits apply; kSteady:
+    // the wave's next tile exists and is whole, so its loads need no branch.  Returns
     // false, with nothing accumulated and the tile's registers intact, when some reference maximum
     // has to be raised first.  The next tile's loads: with R = 4 (one wave per SIMD fits the
     // registers, a long tile) they go into the registers of this tile as soon as its keys are
@@ -166,13 +170,17 @@ void prefill_mfma_kernel(const PrefillParams p) {
     // short to cover the latency that way, load into a second set of registers before anything else.
     float top[R];  // largest scaled logit of this lane in the tile, per row tile
     int base = c0 + wave * kPTile;
-    auto consume = [&](auto masked) -> bool {
-        constexpr bool kMasked = decltype(masked)::value;
+    auto consume = [&](auto masked, auto steady) -> bool {
+        constexpr bool kMasked = decltype(masked)::value, kSteady = decltype(steady)::value;
         constexpr bool kInPlace = R == 4;
-        const bool more = base + kPStep < c1;
+        const bool more = kSteady || base + kPStep < c1;
         uint4 kn[kInPlace ? 1 : 2][4], vn[kInPlace ? 1 : 2][4];
         if constexpr (!kInPlace) {
-            if (more) load_tile(base + kPStep, kn, vn);
+            if constexpr (kSteady) {
+                load_full(base + kPStep, kn, vn);
+            } else {
+                if (more) load_tile(base + kPStep, kn, vn);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
         const int t_lane = base + 4 * kb;  // this lane's logits are for tokens t_lane + 16 h + i
@@ -227,7 +235,11 @@ void prefill_mfma_kernel(const PrefillParams p) {
         }
         if constexpr (kInPlace) {
             __builtin_amdgcn_sched_barrier(0);
-            if (more) load_tile(base + kPStep, kr, vr);
+            if constexpr (kSteady) {
+                load_full(base + kPStep, kr, vr);
+            } else {
+                if (more) load_tile(base + kPStep, kr, vr);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
@@ -273,13 +285,14 @@ void prefill_mfma_kernel(const PrefillParams p) {
         }
     };
 
-    // Unmasked tiles first, then the masked ones; a tile that needs a higher reference maximum
-    // leaves the loops, and is taken again after the rescale.
+    // First the tiles that need no mask and whose successor is whole, then the rest through the
+    // general path; a tile that needs a higher reference maximum leaves the loops, and is taken
+    // again after the rescale.
     if (base < c1) load_tile(base, kr, vr);
     for (;;) {
         bool done = true;
-        while (done && base + kPTile <= min(t_full, c1)) done = consume(std::false_type{});
-        while (done && base < c1) done = consume(std::true_type{});
+        while (done && base + kPTile <= t_full && base + kPStep + kPTile <= c1) done = consume(std::false_type{}, std::true_type{});
+        while (done && base < c1) done = consume(std::true_type{}, std::false_type{});
         if (done) break;
         raise();
     }
