@@ -87,6 +87,28 @@ def test_prefill_longer_than_a_sequence_yields_zeros_for_the_missing_tokens():
     td.close()
 
 
+def test_chunked_prefill_of_a_ragged_batch_with_a_sequence_shorter_than_the_new_tokens():
+    w = W.workload("c4", seq_lens=(3000, 10, 1700), k=8)    # 5 chunks of 640 tokens; sequence 1 uses none of them
+    (_, K, V), = device_layers(w, [0])
+    g = torch.Generator(device=DEV).manual_seed(2)
+    q = torch.randn((3, 16, w.num_q_heads, w.head_dim), generator=g, device=DEV).to(torch.bfloat16)
+    lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=DEV)
+    shape = tidal.make_shape(q[:, 0].contiguous(), K, lens)
+    assert tidal.lib().td_prefill_workspace_bytes(shape, 16) > 0
+    td = tidal.Tidal(shape, 0, prefill_new=16)
+    out = torch.full_like(q, float("nan"))
+    say("chunked prefill, ragged")
+    td.prefill_attend(shape, q, K, V, out)
+    torch.cuda.synchronize()
+    assert (out[1, :6] == 0).all()                     # tokens at positions -6 .. -1 do not exist
+    ref = O.prefill(host(q[1:2, 6:]).contiguous(), host(K[1:2]), host(V[1:2]), [10])
+    check_output(out[1:2, 6:], ref, "tail of the short sequence", single_bf16_p=True)
+    for b in (0, 2):
+        check_output(out[b:b + 1], O.prefill(host(q[b:b + 1]), host(K[b:b + 1]), host(V[b:b + 1]), [w.seq_lens[b]]),
+                     "sequence %d" % b, single_bf16_p=True)
+    td.close()
+
+
 def test_prefill_rejects_unsupported_shapes():
     w = W.workload("c1", context=100, k=8)               # fp32, head_dim 64
     (q1, K, V), = device_layers(w, [0])
