@@ -163,10 +163,11 @@ void prefill_mfma_kernel(const PrefillParams p) {
 
     // One 32-token tile against the R row tiles.  kMasked: per-row causal limits apply; kSteady:
     // the wave's next tile exists and is whole, so its loads need no branch.  Returns
-    // false, with nothing accumulated and the tile's registers intact, when some reference maximum
-    // has to be raised first.  The next tile's loads: with R = 4 (one wave per SIMD fits the
+    // false, with nothing accumulated, when some reference maximum has to be raised first (the
+    // caller then loads the tile again: its registers may already be receiving the next one).  The next tile's loads: with R = 4 (one wave per SIMD fits the
     // registers, a long tile) they go into the registers of this tile as soon as its keys are
-    // multiplied and its values are in operand order; the smaller variants, whose tiles are too
+    // multiplied and its values are in operand order (both before the maxima are looked at, so
+    // the byte permutes run under the K Q^T MFMAs and the loads get the rest of the tile to land); the smaller variants, whose tiles are too
     // short to cover the latency that way, load into a second set of registers before anything else.
     float top[R];  // largest scaled logit of this lane in the tile, per row tile
     int base = c0 + wave * kPTile;
@@ -197,19 +198,6 @@ void prefill_mfma_kernel(const PrefillParams p) {
                 for (int h = 0; h < 2; ++h)
                     st[r][h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kr[h][s]), qfrag[r][s],
                                                                        st[r][h], 0, 0, 0);
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            if (kMasked) {
-#pragma unroll
-                for (int h = 0; h < 2; ++h)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) st[r][h][i] = t_lane + 16 * h + i < limit[r] ? st[r][h][i] : -INFINITY;
-            }
-            top[r] = fmaxf(fmaxf(fmaxf(st[r][0][0], st[r][0][1]), fmaxf(st[r][0][2], st[r][0][3])),
-                           fmaxf(fmaxf(st[r][1][0], st[r][1][1]), fmaxf(st[r][1][2], st[r][1][3]))) * scale2;  // scale2 > 0
-            grow |= top[r] > m_use[r] + kLazyMax;
-        }
-        if (__builtin_expect(__any(grow), 0)) return false;
         // V^T as A operand: for channel group e, the lane's eight tokens (4kb .. 4kb+3 of either
         // half) of channel 8 n16 + e
         bf16x8 vf[8];
@@ -231,6 +219,7 @@ void prefill_mfma_kernel(const PrefillParams p) {
                 vf[e] = __builtin_bit_cast(
                     bf16x8, make_uint4(__builtin_amdgcn_perm(vw[0][1][w], vw[0][0][w], sel), __builtin_amdgcn_perm(vw[0][3][w], vw[0][2][w], sel),
                                        __builtin_amdgcn_perm(vw[1][1][w], vw[1][0][w], sel), __builtin_amdgcn_perm(vw[1][3][w], vw[1][2][w], sel)));
+                asm volatile("" : "+v"(vf[e]));  // computed here, under the MFMAs above, not sunk below the branch
             }
         }
         if constexpr (kInPlace) {
@@ -242,6 +231,19 @@ void prefill_mfma_kernel(const PrefillParams p) {
             }
             __builtin_amdgcn_sched_barrier(0);
         }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if (kMasked) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) st[r][h][i] = t_lane + 16 * h + i < limit[r] ? st[r][h][i] : -INFINITY;
+            }
+            top[r] = fmaxf(fmaxf(fmaxf(st[r][0][0], st[r][0][1]), fmaxf(st[r][0][2], st[r][0][3])),
+                           fmaxf(fmaxf(st[r][1][0], st[r][1][1]), fmaxf(st[r][1][2], st[r][1][3]))) * scale2;  // scale2 > 0
+            grow |= top[r] > m_use[r] + kLazyMax;
+        }
+        if (__builtin_expect(__any(grow), 0)) return false;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             float pr[2][4];
@@ -295,6 +297,7 @@ void prefill_mfma_kernel(const PrefillParams p) {
         while (done && base < c1) done = consume(std::true_type{}, std::false_type{});
         if (done) break;
         raise();
+        load_tile(base, kr, vr);
     }
 
     // ---- fold the four waves' states of one row tile at a time through LDS and write the rows
