@@ -120,3 +120,33 @@ def test_prefill_rejects_unsupported_shapes():
         td.prefill_attend(shape, q, K, V, torch.empty_like(q))
     assert e.value.status == tidal.ERR_UNSUPPORTED
     td.close()
+
+
+@pytest.mark.parametrize("num_new", [16, 1024])
+def test_prefill_at_the_benchmark_shape_on_sampled_tokens(num_new):
+    """c2 at full size, in the launch configuration `bench.py --prefill` times (16 new tokens: token chunks and
+    the merge kernel; 1024: one chunk, 64-row blocks).  The oracle takes the new tokens one by one: token j is a
+    decode query over the first N - P + j + 1 positions, so a sample of tokens (ends, neighbours across a row
+    block boundary, some in between) is compared with tdo_full on those prefixes."""
+    w = W.workload("c2")
+    (_, K, V), = device_layers(w, [0])
+    g = torch.Generator(device=DEV).manual_seed(11)
+    q = torch.randn((w.batch, num_new, w.num_q_heads, w.head_dim), generator=g, device=DEV).to(torch.bfloat16)
+    lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=DEV)
+    shape = tidal.make_shape(q[:, 0].contiguous(), K, lens)
+    td = tidal.Tidal(shape, 0, prefill_new=num_new)
+    out = torch.full_like(q, float("nan"))
+    say("prefill c2 full size P=%d" % num_new)
+    td.prefill_attend(shape, q, K, V, out)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+    Kh, Vh = host(K), host(V)
+    n = w.seq_lens[0]
+    G = w.num_q_heads // w.num_kv_heads
+    per_block = 64 // G                                 # tokens per 64-row block
+    sample = sorted({0, 1, num_new // 2, num_new - 2, num_new - 1, min(per_block - 1, num_new - 1),
+                     min(per_block, num_new - 1), min(5 * per_block + 3, num_new - 1)})
+    for j in sample:
+        ref = O.full(host(q[:, j]).contiguous(), Kh, Vh, [n - num_new + j + 1])
+        check_output(out[:, j], ref, "c2 P=%d token %d" % (num_new, j), single_bf16_p=True)
+    td.close()
