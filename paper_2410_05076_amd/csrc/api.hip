@@ -473,6 +473,8 @@ td_status td_prefill_attend(td_ctx *ctx, const td_shape *shape, int32_t num_new,
         return fail(ctx, TD_ERR_INVALID_ARG, "%s", "num_new outside [1, max_seq_len]");
     if (shape->dtype != TD_BF16 || shape->head_dim != 128 || shape->page_size != 0)
         return fail(ctx, TD_ERR_UNSUPPORTED, "%s", "prefill attention needs bf16, head_dim 128 and a contiguous cache");
+    if (shape->kv_stride_tok > (int64_t)1 << 24)  // the kernel adds lane offsets of up to 16 rows in 32 bits
+        return fail(ctx, TD_ERR_UNSUPPORTED, "%s", "prefill attention needs kv_stride_tok <= 2^24 elements");
     PrefillParams p;
     memset(&p, 0, sizeof p);
     p.q = q; p.K = K; p.V = V; p.out = out;
