@@ -150,3 +150,42 @@ def test_prefill_at_the_benchmark_shape_on_sampled_tokens(num_new):
         ref = O.full(host(q[:, j]).contiguous(), Kh, Vh, [n - num_new + j + 1])
         check_output(out[:, j], ref, "c2 P=%d token %d" % (num_new, j), single_bf16_p=True)
     td.close()
+
+
+@pytest.mark.parametrize("num_new", [24, 200])
+def test_prefill_with_a_token_major_cache_layout(num_new):
+    # K, V stored [B][N][Hkv][d] and passed through the strides; 200 new tokens use the 64-row blocks
+    w = W.workload("c2", context=2100, k=64)
+    (_, K, V), = device_layers(w, [0])
+    Kt = K.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    Vt = V.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    g = torch.Generator(device=DEV).manual_seed(8)
+    q = torch.randn((w.batch, num_new, w.num_q_heads, w.head_dim), generator=g, device=DEV).to(torch.bfloat16)
+    lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=DEV)
+    shape = tidal.make_shape(q[:, 0].contiguous(), Kt, lens)
+    assert shape.kv_stride_tok == w.num_kv_heads * w.head_dim
+    td = tidal.Tidal(shape, 0, prefill_new=num_new)
+    out = torch.full_like(q, float("nan"))
+    say("prefill token-major P=%d" % num_new)
+    td.prefill_attend(shape, q, Kt, Vt, out)
+    torch.cuda.synchronize()
+    check_output(out, O.prefill(host(q), host(K), host(V), w.seq_lens), "token-major prefill", single_bf16_p=True)
+    td.close()
+
+
+def test_prefill_results_are_deterministic():
+    w = W.workload("c2", context=3000, k=64)
+    (_, K, V), = device_layers(w, [0])
+    g = torch.Generator(device=DEV).manual_seed(9)
+    q = torch.randn((w.batch, 40, w.num_q_heads, w.head_dim), generator=g, device=DEV).to(torch.bfloat16)
+    lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=DEV)
+    shape = tidal.make_shape(q[:, 0].contiguous(), K, lens)
+    td = tidal.Tidal(shape, 0, prefill_new=40)
+    outs = []
+    for _ in range(3):
+        out = torch.full_like(q, float("nan"))
+        td.prefill_attend(shape, q, K, V, out)
+        torch.cuda.synchronize()
+        outs.append(out)
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+    td.close()
