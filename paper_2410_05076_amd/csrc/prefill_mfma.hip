@@ -73,24 +73,23 @@ void prefill_mfma_kernel(const PrefillParams p) {
     const int n16 = lane & 15, kb = lane >> 4;
     const int P = p.num_new, rows_total = P * G, row0 = rb * (16 * R);
 
-    // Q^T fragments: lane (n16, kb) holds d-octet 4s + kb of row row0 + 16r + n16; rows beyond the
-    // last one are zero and never written
-    bf16x8 qfrag[R][4];
+    // Q^T fragments: lane (n16, kb) of fragment (r, s) holds d-octet 4s + kb of row row0 + 16r + n16;
+    // rows beyond the last one are zero and never written.  All four waves use the same fragments,
+    // tile after tile, so they live in LDS (16 bytes per lane and fragment, read back lane by lane)
+    // and leave the registers to the tiles in flight; wave w fetches the fragments with s = w.
+    __shared__ uint4 s_q[R * 4 * kWave];
     int tkn[R];
+    uint4 qv[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int row = row0 + 16 * r + n16;
         tkn[r] = row / G;
         const int head = row - tkn[r] * G;
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            uint4 v = make_uint4(0u, 0u, 0u, 0u);
-            if (row < rows_total)
-                v = *reinterpret_cast<const uint4 *>(
-                    static_cast<const char *>(p.q) +
-                    ((((int64_t)b * P + tkn[r]) * p.num_q_heads + g * G + head) * kPD + (4 * s + kb) * 8) * 2);
-            qfrag[r][s] = __builtin_bit_cast(bf16x8, v);
-        }
+        qv[r] = make_uint4(0u, 0u, 0u, 0u);
+        if (row < rows_total)
+            qv[r] = *reinterpret_cast<const uint4 *>(
+                static_cast<const char *>(p.q) +
+                ((((int64_t)b * P + tkn[r]) * p.num_q_heads + g * G + head) * kPD + (4 * wave + kb) * 8) * 2);
     }
     asm volatile("" ::: "memory");  // the loads above are issued before the sequence length is needed
 
@@ -105,6 +104,9 @@ void prefill_mfma_kernel(const PrefillParams p) {
     // this workgroup's chunk of them
     const int c0 = blockIdx.y * p.chunk, c1 = min(c0 + p.chunk, t_end);
     if (p.chunks > 1 && c0 >= t_end) return;  // the merge kernel knows that this chunk is empty
+#pragma unroll
+    for (int r = 0; r < R; ++r) s_q[(r * 4 + wave) * kWave + lane] = qv[r];
+    __syncthreads();
 
     const int64_t row_bytes = p.stride_tok * 2;
     const int64_t head_off = ((int64_t)b * p.stride_batch + (int64_t)g * p.stride_head) * 2;
@@ -190,14 +192,16 @@ void prefill_mfma_kernel(const PrefillParams p) {
         // the 2 R chains of four dependent MFMAs advance together, so that none waits for its own result
 #pragma unroll
         for (int r = 0; r < R; ++r) st[r][0] = st[r][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+        asm volatile("" ::: "memory");  // the fragments are read from LDS in every tile, not kept in registers
 #pragma unroll
         for (int s = 0; s < 4; ++s)
 #pragma unroll
-            for (int r = 0; r < R; ++r)
+            for (int r = 0; r < R; ++r) {
+                const bf16x8 qf = __builtin_bit_cast(bf16x8, s_q[(r * 4 + s) * kWave + lane]);
 #pragma unroll
                 for (int h = 0; h < 2; ++h)
-                    st[r][h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kr[h][s]), qfrag[r][s],
-                                                                       st[r][h], 0, 0, 0);
+                    st[r][h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kr[h][s]), qf, st[r][h], 0, 0, 0);
+            }
         // V^T as A operand: for channel group e, the lane's eight tokens (4kb .. 4kb+3 of either
         // half) of channel 8 n16 + e
         bf16x8 vf[8];
