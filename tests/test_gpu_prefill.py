@@ -189,3 +189,30 @@ def test_prefill_results_are_deterministic():
         outs.append(out)
     assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
     td.close()
+
+
+def test_chunked_prefill_as_a_hip_graph():
+    # two kernels (chunks, merge) and no memset: replays, with eager work in between, reproduce the eager result
+    w = W.workload("c2", context=5000, k=64)
+    (_, K, V), = device_layers(w, [0])
+    g = torch.Generator(device=DEV).manual_seed(13)
+    q = torch.randn((w.batch, 16, w.num_q_heads, w.head_dim), generator=g, device=DEV).to(torch.bfloat16)
+    lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=DEV)
+    shape = tidal.make_shape(q[:, 0].contiguous(), K, lens)
+    td = tidal.Tidal(shape, 0, prefill_new=16)
+    out = torch.full_like(q, float("nan"))
+    td.prefill_attend(shape, q, K, V, out)
+    torch.cuda.synchronize()
+    eager = out.clone()
+    check_output(eager, O.prefill(host(q), host(K), host(V), w.seq_lens), "eager", single_bf16_p=True)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        td.prefill_attend(shape, q, K, V, out)
+    for rep in range(3):
+        out.fill_(float("nan"))
+        scratch = torch.randn(1 << 20, device=DEV).sum()     # the program's own eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), "replay %d" % rep
+    td.close()
