@@ -292,7 +292,13 @@ def prefill_bench(args, torch, tidal, W, dev):
     q = torch.randn((w.batch, P, w.num_q_heads, w.head_dim), device=dev).to(w.torch_dtype)
     out = torch.empty_like(q)
     lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=dev)
-    shape = tidal.make_shape(q1, K, lens)
+    if args.page_size:      # the same tokens, scattered over a page pool
+        table, num_pages = W.page_table(w, args.page_size, device=dev)
+        _, K = W.paginate(K, table, num_pages, args.page_size, args.page_layout)
+        _, V = W.paginate(V, table, num_pages, args.page_size, args.page_layout)
+        shape = tidal.make_paged_shape(q1, K, table, lens, w.max_seq_len)
+    else:
+        shape = tidal.make_shape(q1, K, lens)
     td = tidal.Tidal(shape, 0, prefill_new=P)
     for _ in range(max(1, args.warmup)):
         td.prefill_attend(shape, q, K, V, out)
@@ -327,7 +333,8 @@ def prefill_bench(args, torch, tidal, W, dev):
     return {"metric": "prefill_attention_us", "value": round(us, 2), "unit": "us", "n_gpus": 1, "steps": args.steps,
             "warmup": args.warmup, "ms_per_step": round(us / 1e3, 5), "higher_is_better": False, "scaling": "weak",
             "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
-            "config": {"workload": DESCRIPTIONS[w.name] + ", one layer, prefill attention over the last %d tokens" % P},
+            "config": {"workload": DESCRIPTIONS[w.name] + ", one layer, prefill attention over the last %d tokens" % P
+                       + (", paged cache, page size %d (%s)" % (args.page_size, args.page_layout) if args.page_size else "")},
             "median_us": round(ts[len(ts) // 2], 2), "roofline": roof}
 
 

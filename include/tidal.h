@@ -187,7 +187,8 @@ td_status td_decode_step(td_ctx *ctx, const td_shape *shape, int32_t num_layers,
  * position seq_lens[b] - num_new + j (its key and value are already in the cache) and attends,
  * with Eq. 1, to the positions up to and including its own; a token that would sit before the
  * start of the cache (num_new > seq_lens[b]) yields zeros.  Supported: bf16, head_dim 128,
- * contiguous cache, kv_stride_tok <= 2^24 elements (TD_ERR_UNSUPPORTED otherwise).
+ * a contiguous cache or a paged one with pages of 16 tokens or more, kv_stride_tok <= 2^24
+ * elements (TD_ERR_UNSUPPORTED otherwise).
  * A prefill over few tokens is bound by the stream of the cache, as a decode step is: the tokens
  * are then cut into chunks whose partial states go through the context's workspace.
  * td_prefill_workspace_bytes is the size that allows every chunk the launch plan would like (0

@@ -471,8 +471,8 @@ td_status td_prefill_attend(td_ctx *ctx, const td_shape *shape, int32_t num_new,
     if (st != TD_OK) return st;
     if (num_new < 1 || num_new > shape->max_seq_len)
         return fail(ctx, TD_ERR_INVALID_ARG, "%s", "num_new outside [1, max_seq_len]");
-    if (shape->dtype != TD_BF16 || shape->head_dim != 128 || shape->page_size != 0)
-        return fail(ctx, TD_ERR_UNSUPPORTED, "%s", "prefill attention needs bf16, head_dim 128 and a contiguous cache");
+    if (shape->dtype != TD_BF16 || shape->head_dim != 128 || (shape->page_size != 0 && shape->page_size < 16))
+        return fail(ctx, TD_ERR_UNSUPPORTED, "%s", "prefill attention needs bf16, head_dim 128 and, if paged, pages of 16 tokens or more");
     if (shape->kv_stride_tok > (int64_t)1 << 24)  // the kernel adds lane offsets of up to 16 rows in 32 bits
         return fail(ctx, TD_ERR_UNSUPPORTED, "%s", "prefill attention needs kv_stride_tok <= 2^24 elements");
     PrefillParams p;
@@ -488,6 +488,12 @@ td_status td_prefill_attend(td_ctx *ctx, const td_shape *shape, int32_t num_new,
     p.max_seq_len = shape->max_seq_len;
     p.num_new = num_new;
     p.scale = shape->sm_scale > 0.f ? shape->sm_scale : 1.0f / sqrtf((float)shape->head_dim);
+    if (shape->page_size > 0) {
+        p.block_table = shape->block_table;
+        p.bt_stride = shape->block_table_stride;
+        p.num_pages = shape->num_pages;
+        while ((1 << p.page_shift) < shape->page_size) ++p.page_shift;
+    }
     // token chunks as far as the workspace holds their partial states
     const size_t avail = ctx->workspace_bytes > kCountersBytes ? ctx->workspace_bytes - kCountersBytes : 0;
     const PrefillPlan pl = prefill_plan_for(shape, num_new, avail);

@@ -73,7 +73,8 @@ hipError_t launch_attend(int dtype, int head_dim, int group, int waves, int mode
                          hipStream_t stream);
 hipError_t launch_attend_mfma(int group, int waves, int mode, const AttendParams &p, hipStream_t stream);
 
-// Prefill attention over the last num_new tokens of every sequence (bf16, head_dim 128, contiguous cache).
+// Prefill attention over the last num_new tokens of every sequence (bf16, head_dim 128; contiguous cache, or
+// paged with pages of at least 16 tokens).
 // The query rows of a KV head are the (token, head) pairs; a workgroup takes rows_per_wg of them and one
 // chunk of the tokens.  With more than one chunk the workgroups leave partial states
 //   part_ml [wg][chunk][rows_per_wg][2], part_acc [wg][chunk][rows_per_wg][128]   (wg = pair * row_blocks + row block)
@@ -83,7 +84,10 @@ struct PrefillParams {
     void *out;              // like q
     const int32_t *seq_lens;
     float *part_acc, *part_ml;
-    int64_t stride_batch, stride_head, stride_tok;  // elements
+    int64_t stride_batch, stride_head, stride_tok;  // elements; paged: stride_batch is the page stride
+    const int32_t *block_table;                     // paged cache: [B][bt_stride] page ids, else nullptr
+    int64_t bt_stride;
+    int32_t page_shift, num_pages;                  // log2(page size) >= 4; pages in the pool
     int32_t batch, num_q_heads, num_kv_heads, max_seq_len, num_new;
     int32_t rows_per_wg;  // 32 or 64
     int32_t row_blocks;   // workgroups per (sequence, KV head) and chunk

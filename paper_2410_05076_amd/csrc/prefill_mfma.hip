@@ -51,7 +51,7 @@ __device__ __forceinline__ uint32_t bf16_pair(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){lo, hi}, bf16x2));
 }
 
-template <int G, int R>
+template <int G, int R, bool PAGED>
 __global__ __launch_bounds__(kPThreads)
 void prefill_mfma_kernel(const PrefillParams p) {
     // Workgroups are handed to the eight XCDs round-robin by their linear index.  The row blocks of
@@ -109,9 +109,29 @@ void prefill_mfma_kernel(const PrefillParams p) {
     __syncthreads();
 
     const int64_t row_bytes = p.stride_tok * 2;
-    const int64_t head_off = ((int64_t)b * p.stride_batch + (int64_t)g * p.stride_head) * 2;
+    const int64_t head_off = ((PAGED ? 0 : (int64_t)b * p.stride_batch) + (int64_t)g * p.stride_head) * 2;
     const char *Kh = static_cast<const char *>(p.K) + head_off;  // wave-uniform
     const char *Vh = static_cast<const char *>(p.V) + head_off;
+    // Paged cache (pages of at least 16 tokens): a 16-token half of a tile lies in one page, so a
+    // whole tile needs two block-table entries, read one tile before the loads that use them.
+    const int64_t page_bytes = p.stride_batch * 2;
+    const int slot_mask = PAGED ? (1 << p.page_shift) - 1 : 0;
+    const int32_t *table = PAGED ? p.block_table + (int64_t)b * p.bt_stride : nullptr;
+    auto page_of = [&](int t) -> int {  // table entry of token t (any t: clamped into the table)
+        if constexpr (PAGED) return table[min(max(t, 0), p.max_seq_len - 1) >> p.page_shift];
+        return 0;
+    };
+    // The entry of a 16-token half is looked up by every lane for its own key token of the half
+    // (t16 + n16: the same entry for all of them).  A wave-uniform lookup would be turned into a
+    // scalar value on the spot, which means waiting for the vector load right behind the tile
+    // loads it was issued after; the per-lane value is only waited for where the next tile's
+    // addresses are formed, a tile later.
+    auto page_of_half = [&](int t16) -> int { return page_of(t16 + n16); };
+    auto row_off = [&](int t, int page) -> int64_t {  // byte offset of token t's row inside the head's cache
+        if constexpr (PAGED)
+            return (int64_t)min(max(page, 0), p.num_pages - 1) * page_bytes + (int64_t)(t & slot_mask) * row_bytes;
+        return (int64_t)t * row_bytes;
+    };
 
     // The softmax denominator is accumulated on the matrix core as well, as one more "channel" of
     // ones: it then sums the same bf16-rounded probabilities as the numerator, which keeps a row
@@ -136,10 +156,11 @@ void prefill_mfma_kernel(const PrefillParams p) {
     // its tokens to the last one streamed (masked below).
     const uint32_t k_lane = (uint32_t)(n16 * row_bytes) + kb * 16, v_lane = (uint32_t)(4 * kb * row_bytes) + n16 * 16;
     uint4 kr[2][4], vr[2][4];
-    auto load_full = [&](int base, uint4 (&kr)[2][4], uint4 (&vr)[2][4]) {
+    auto load_full = [&](int base, uint4 (&kr)[2][4], uint4 (&vr)[2][4], const int (&pages)[2]) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            const char *kt = Kh + (int64_t)(base + 16 * h) * row_bytes, *vt = Vh + (int64_t)(base + 16 * h) * row_bytes;
+            const int64_t off = row_off(base + 16 * h, pages[h]);
+            const char *kt = Kh + off, *vt = Vh + off;
 #pragma unroll
             for (int s = 0; s < 4; ++s) kr[h][s] = *reinterpret_cast<const uint4 *>(kt + k_lane + 64 * s);
 #pragma unroll
@@ -148,29 +169,39 @@ void prefill_mfma_kernel(const PrefillParams p) {
     };
     auto load_tile = [&](int base, uint4 (&kr)[2][4], uint4 (&vr)[2][4]) {
         if (base + kPTile <= t_end) {
-            load_full(base, kr, vr);
+            const int pages[2] = {page_of_half(base), page_of_half(base + 16)};
+            load_full(base, kr, vr, pages);
         } else {
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                const char *kp = Kh + (int64_t)min(base + 16 * h + n16, t_end - 1) * row_bytes + kb * 16;
+                const int tk = min(base + 16 * h + n16, t_end - 1);
+                const char *kp = Kh + row_off(tk, page_of(tk)) + kb * 16;
 #pragma unroll
                 for (int s = 0; s < 4; ++s) kr[h][s] = *reinterpret_cast<const uint4 *>(kp + 64 * s);
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    vr[h][u] = *reinterpret_cast<const uint4 *>(
-                        Vh + (int64_t)min(base + 16 * h + 4 * kb + u, t_end - 1) * row_bytes + n16 * 16);
+                for (int u = 0; u < 4; ++u) {
+                    const int tv = min(base + 16 * h + 4 * kb + u, t_end - 1);
+                    vr[h][u] = *reinterpret_cast<const uint4 *>(Vh + row_off(tv, page_of(tv)) + n16 * 16);
+                }
             }
         }
     };
 
     // One 32-token tile against the R row tiles.  kMasked: per-row causal limits apply; kSteady:
-    // the wave's next tile exists and is whole, so its loads need no branch.  Returns
-    // false, with nothing accumulated, when some reference maximum has to be raised first (the
-    // caller then loads the tile again: its registers may already be receiving the next one).  The next tile's loads: with R = 4 (one wave per SIMD fits the
-    // registers, a long tile) they go into the registers of this tile as soon as its keys are
-    // multiplied and its values are in operand order (both before the maxima are looked at, so
-    // the byte permutes run under the K Q^T MFMAs and the loads get the rest of the tile to land); the smaller variants, whose tiles are too
-    // short to cover the latency that way, load into a second set of registers before anything else.
+    // the wave's next tile exists and is whole, so its loads need no branch (and its block-table
+    // entries are in pages_next already).  Returns false, with nothing accumulated, when some
+    // reference maximum has to be raised first (the caller then loads the tile again: its
+    // registers may already be receiving the next one).  The next tile's loads: with R = 4 (one
+    // wave per SIMD fits the registers, a long tile) they go into the registers of this tile as
+    // soon as its keys are multiplied and its values are in operand order (both before the maxima
+    // are looked at, so the byte permutes run under the K Q^T MFMAs and the loads get the rest of
+    // the tile to land); the smaller variant, whose tiles are too short to cover the latency that
+    // way, loads into a second set of registers before anything else.
+    int pages_next[2] = {0, 0};
+    auto look_ahead = [&](int t) {  // block-table entries of the tile that starts at token t
+        pages_next[0] = page_of_half(t);
+        pages_next[1] = page_of_half(t + 16);
+    };
     float top[R];  // largest scaled logit of this lane in the tile, per row tile
     int base = c0 + wave * kPTile;
     auto consume = [&](auto masked, auto steady) -> bool {
@@ -180,7 +211,8 @@ void prefill_mfma_kernel(const PrefillParams p) {
         uint4 kn[kInPlace ? 1 : 2][4], vn[kInPlace ? 1 : 2][4];
         if constexpr (!kInPlace) {
             if constexpr (kSteady) {
-                load_full(base + kPStep, kn, vn);
+                load_full(base + kPStep, kn, vn, pages_next);
+                look_ahead(base + 2 * kPStep);
             } else {
                 if (more) load_tile(base + kPStep, kn, vn);
             }
@@ -229,7 +261,8 @@ void prefill_mfma_kernel(const PrefillParams p) {
         if constexpr (kInPlace) {
             __builtin_amdgcn_sched_barrier(0);
             if constexpr (kSteady) {
-                load_full(base + kPStep, kr, vr);
+                load_full(base + kPStep, kr, vr, pages_next);
+                look_ahead(base + 2 * kPStep);
             } else {
                 if (more) load_tile(base + kPStep, kr, vr);
             }
@@ -297,6 +330,7 @@ void prefill_mfma_kernel(const PrefillParams p) {
     if (base < c1) load_tile(base, kr, vr);
     for (;;) {
         bool done = true;
+        if (base + kPTile <= t_full && base + kPStep + kPTile <= c1) look_ahead(base + kPStep);
         while (done && base + kPTile <= t_full && base + kPStep + kPTile <= c1) done = consume(std::false_type{}, std::true_type{});
         while (done && base < c1) done = consume(std::true_type{}, std::false_type{});
         if (done) break;
@@ -397,7 +431,10 @@ template <int G, int R>
 hipError_t launch_prefill_rows(const PrefillParams &p, hipStream_t stream) {
     const int pairs = p.num_kv_heads * p.batch;
     const dim3 grid(p.row_blocks * pairs, p.chunks), block(kPThreads);
-    hipLaunchKernelGGL((prefill_mfma_kernel<G, R>), grid, block, 0, stream, p);
+    if (p.block_table)
+        hipLaunchKernelGGL((prefill_mfma_kernel<G, R, true>), grid, block, 0, stream, p);
+    else
+        hipLaunchKernelGGL((prefill_mfma_kernel<G, R, false>), grid, block, 0, stream, p);
     if (p.chunks > 1) {
         const int64_t rows = (int64_t)p.row_blocks * pairs * p.rows_per_wg;
         hipLaunchKernelGGL((prefill_merge_kernel<G>), dim3((unsigned)rows), dim3(kMergeSets * kPD), 0, stream, p);

@@ -216,3 +216,49 @@ def test_chunked_prefill_as_a_hip_graph():
         torch.cuda.synchronize()
         assert torch.equal(out, eager), "replay %d" % rep
     td.close()
+
+
+@pytest.mark.parametrize("name,over,num_new,page_size,layout", [
+    ("c2", dict(context=3000, k=64), 16, 16, "HND"),                      # two pages per tile, token chunks
+    ("c2", dict(context=3000, k=64), 37, 64, "NHD"),                      # token-major pool, ragged last row block
+    ("c2", dict(context=2100, k=64), 200, 32, "HND"),                     # 64-row blocks, one page per tile
+    ("c6", dict(context=2000, k=64), 21, 128, "NHD"),                     # G = 8, pages longer than a tile
+    ("c3", dict(context=2500, k=64, tau=512.0), 100, 16, "HND"),          # G = 1
+    ("c4", dict(seq_lens=(900, 33, 64, 2048), k=64), 33, 16, "HND"),      # ragged batch, P = N for one
+])
+def test_prefill_over_a_paged_cache(name, over, num_new, page_size, layout):
+    """Pages scattered over a pool with spare pages; spare pages and never-written slots hold NaN."""
+    w = W.workload(name, **over)
+    (_, K, V), = device_layers(w, [0])
+    table, num_pages = W.page_table(w, page_size, device=DEV)
+    Kp, Kv = W.paginate(K, table, num_pages, page_size, layout)
+    Vp, Vv = W.paginate(V, table, num_pages, page_size, layout)
+    g = torch.Generator(device=DEV).manual_seed(17)
+    q = torch.randn((w.batch, num_new, w.num_q_heads, w.head_dim), generator=g, device=DEV).to(torch.bfloat16)
+    lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=DEV)
+    shape = tidal.make_paged_shape(q[:, 0].contiguous(), Kv, table, lens, w.max_seq_len)
+    td = tidal.Tidal(shape, 0, prefill_new=num_new)
+    out = torch.full_like(q, float("nan"))
+    say("paged prefill %s P=%d page %d %s" % (w.name, num_new, page_size, layout))
+    td.prefill_attend(shape, q, Kv, Vv, out)
+    torch.cuda.synchronize()
+    t = host(table)
+    Kl = O.gather_pages(host(Kv), t, w.seq_lens, w.max_seq_len)
+    Vl = O.gather_pages(host(Vv), t, w.seq_lens, w.max_seq_len)
+    check_output(out, O.prefill(host(q), Kl, Vl, w.seq_lens), "paged prefill", single_bf16_p=True)
+    td.close()
+
+
+def test_prefill_rejects_pages_shorter_than_sixteen_tokens():
+    w = W.workload("c2", context=500, k=16)
+    (q1, K, V), = device_layers(w, [0])
+    table, num_pages = W.page_table(w, 8, device=DEV)
+    Kp, Kv = W.paginate(K, table, num_pages, 8)
+    lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=DEV)
+    shape = tidal.make_paged_shape(q1, Kv, table, lens, w.max_seq_len)
+    td = tidal.Tidal(shape, 0)
+    q = q1[:, None].contiguous()
+    with pytest.raises(tidal.TidalError) as e:
+        td.prefill_attend(shape, q, Kv, Kv, torch.empty_like(q))
+    assert e.value.status == tidal.ERR_UNSUPPORTED
+    td.close()
