@@ -103,13 +103,18 @@ __device__ __forceinline__ Slice open_slice(const float *scores, int64_t row_str
     return s;
 }
 
-// The slice's scores: granule u of thread t is first + u*256 + t.
-__device__ __forceinline__ void load_slice(const Slice &s, int tid, float4 (&v)[kPerThread]) {
+// The slice's scores: granule u of thread t is first + u*256 + t.  They are requested before the
+// row's length is known (one wait for memory instead of two in a row): indices are clamped to
+// the granule of score max_len - 1, which lies inside the row's buffer, and for_each_score masks
+// what lies beyond the row's length.
+__device__ __forceinline__ void load_slice_early(const float *scores, int64_t row_stride, int max_len, int tid,
+                                                 float4 (&v)[kPerThread]) {
+    const float *src = scores + (int64_t)blockIdx.y * row_stride;
+    const int mis = (int)((reinterpret_cast<uintptr_t>(src) >> 2) & 3);
+    const float4 *src4 = reinterpret_cast<const float4 *>(src - mis);
+    const int last4 = ((mis + max_len + 3) >> 2) - 1;
 #pragma unroll
-    for (int u = 0; u < kPerThread; ++u) {
-        const int i = s.first + u * kTopkThreads + tid;
-        v[u] = i < s.n4 ? s.src4[i] : make_float4(0.f, 0.f, 0.f, 0.f);
-    }
+    for (int u = 0; u < kPerThread; ++u) v[u] = src4[min((int)blockIdx.x * kSliceGranules + u * kTopkThreads + tid, last4)];
 }
 
 template <class Fn>
@@ -136,12 +141,13 @@ __global__ __launch_bounds__(kTopkThreads) void topk_hist_kernel(const float *sc
                                                                 const int32_t *row_lens, int rows_per_len,
                                                                 int max_len, int k, void *scratch) {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+    float4 v[kPerThread];
+    load_slice_early(scores, row_stride, max_len, tid, v);
+    asm volatile("" ::: "memory");  // requested before the row's length is read
     const Slice s = open_slice(scores, row_stride, row_lens, rows_per_len, max_len, k, scratch);
     if (!s.active) return;
     __shared__ uint32_t s_hist[kBins];
     __shared__ float s_lo[kTopkWaves], s_hi[kTopkWaves];
-    float4 v[kPerThread];
-    load_slice(s, tid, v);
     // value range from 256 samples of the whole row: the same in every slice of the row
     const float x = s.src[(int64_t)tid * s.n / kTopkThreads];
     float lo = x, hi = x;
@@ -184,20 +190,23 @@ __global__ __launch_bounds__(kTopkThreads) void topk_pick_kernel(const float *sc
                                                                 int32_t *cand_idx, uint32_t *slice_above,
                                                                 int slices_per_row) {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+    // the slice's scores, the row histogram and the bin map are requested before the row's length is read
+    float4 v[kPerThread];
+    load_slice_early(scores, row_stride, max_len, tid, v);
+    // bin of the k-th largest: thread t owns bins 2047-8t .. 2040-8t, the scan walks downwards
+    constexpr int PER = kBins / kTopkThreads;
+    const TopkRow *early = static_cast<const TopkRow *>(scratch) + blockIdx.y;
+    uint32_t cnt[PER], mine = 0;
+#pragma unroll
+    for (int e = 0; e < PER; ++e) cnt[e] = early->hist[kBins - 1 - PER * tid - e];
+    const float lo = early->lo, inv = early->inv;
+    asm volatile("" ::: "memory");
     const Slice s = open_slice(scores, row_stride, row_lens, rows_per_len, max_len, k, scratch);
     if (!s.active) return;
     __shared__ uint32_t s_tot[kTopkWaves];
     __shared__ uint32_t s_bin, s_remaining;
-    float4 v[kPerThread];
-    load_slice(s, tid, v);
-    // bin of the k-th largest: thread t owns bins 2047-8t .. 2040-8t, the scan walks downwards
-    constexpr int PER = kBins / kTopkThreads;
-    uint32_t cnt[PER], mine = 0;
 #pragma unroll
-    for (int e = 0; e < PER; ++e) {
-        cnt[e] = s.state->hist[kBins - 1 - PER * tid - e];
-        mine += cnt[e];
-    }
+    for (int e = 0; e < PER; ++e) mine += cnt[e];
     uint32_t total;
     const uint32_t incl = block_inclusive_scan(mine, lane, wave, s_tot, &total);
     const uint32_t want = (uint32_t)k;
@@ -218,7 +227,6 @@ __global__ __launch_bounds__(kTopkThreads) void topk_pick_kernel(const float *sc
         s.state->kth_bin = kth_bin;
         s.state->remaining = s_remaining;
     }
-    const float lo = s.state->lo, inv = s.state->inv;
     const int row = blockIdx.y;
     uint32_t above = 0;
     for_each_score(s, tid, v, [&](float f, int j) {
@@ -310,6 +318,31 @@ __global__ __launch_bounds__(kTopkThreads) void topk_emit_kernel(const float *sc
     static_assert(kTopkThreads == 256, "one radix bin per thread");
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
     const int row = blockIdx.y;
+    // Everything whose address follows from the launch arguments alone is requested before the
+    // row's length is read, so that the kernel waits for memory once, not three times in a row:
+    // the row's state, the first candidates (rarely more than a workgroup's worth), the counts
+    // of the earlier slices, and the slice's own scores (granules clamped into the row's buffer
+    // of max_len scores; what lies beyond the row's length is masked further down).
+    const TopkRow *state = static_cast<const TopkRow *>(scratch) + row;
+    const uint32_t ncand = state->ncand, remaining = state->remaining;
+    const int kth_bin = state->kth_bin;
+    const float lo = state->lo, inv = state->inv;
+    const uint32_t early_key = cand_key[(int64_t)row * kCandMax + tid];
+    const int32_t early_idx = cand_idx[(int64_t)row * kCandMax + tid];
+    uint32_t gt_before = 0, eq_before = 0;
+    for (int i = tid; i < (int)blockIdx.x; i += kTopkThreads) gt_before += slice_above[(int64_t)row * slices_per_row + i];
+    float4 own[kPerThread];
+    {
+        const float *src = scores + (int64_t)row * row_stride;
+        const int mis = (int)((reinterpret_cast<uintptr_t>(src) >> 2) & 3);
+        const float4 *src4 = reinterpret_cast<const float4 *>(src - mis);
+        const int last4 = ((mis + max_len + 3) >> 2) - 1;
+#pragma unroll
+        for (int u = 0; u < kPerThread; ++u)
+            own[u] = src4[min((int)blockIdx.x * kSliceGranules + kPerThread * tid + u, last4)];
+    }
+    asm volatile("" ::: "memory");  // the loads above stay above the branches on the row's length
+
     const Slice s = open_slice(scores, row_stride, row_lens, rows_per_len, max_len, k, scratch);
     int32_t *dst = positions + (int64_t)row * k;
     if (k >= s.n) {  // every token is selected: slice x writes entries x*4096 .. and the last one the -1 tail
@@ -321,24 +354,14 @@ __global__ __launch_bounds__(kTopkThreads) void topk_emit_kernel(const float *sc
     if (!s.active) return;
 
     __shared__ EmitShared sm;
-    // this thread owns the 16 consecutive scores of granules first + 4*tid .. first + 4*tid + 3
-    float4 own[kPerThread];
-#pragma unroll
-    for (int u = 0; u < kPerThread; ++u) {
-        const int i = s.first + kPerThread * tid + u;
-        own[u] = i < s.n4 ? s.src4[i] : make_float4(0.f, 0.f, 0.f, 0.f);
-    }
-    const uint32_t ncand = s.state->ncand, remaining = s.state->remaining;
-    const int kth_bin = s.state->kth_bin;
-    const float lo = s.state->lo, inv = s.state->inv;
     const int slice_start = 4 * s.first - s.mis;  // first token index of this slice
 
-    // scores of earlier slices above the bin
-    uint32_t gt_before = 0, eq_before = 0;
-    for (int i = tid; i < (int)blockIdx.x; i += kTopkThreads) gt_before += slice_above[(int64_t)row * slices_per_row + i];
-
     if (ncand <= (uint32_t)kCandMax) {
-        for (uint32_t i = tid; i < ncand; i += kTopkThreads) {
+        if (tid < (int)ncand) {
+            sm.key[tid] = early_key;
+            sm.idx[tid] = early_idx;
+        }
+        for (uint32_t i = tid + kTopkThreads; i < ncand; i += kTopkThreads) {
             sm.key[i] = cand_key[(int64_t)row * kCandMax + i];
             sm.idx[i] = cand_idx[(int64_t)row * kCandMax + i];
         }
