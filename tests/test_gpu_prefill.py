@@ -262,3 +262,69 @@ def test_prefill_rejects_pages_shorter_than_sixteen_tokens():
         td.prefill_attend(shape, q, Kv, Kv, torch.empty_like(q))
     assert e.value.status == tidal.ERR_UNSUPPORTED
     td.close()
+
+
+def _random_prefill_case(seed):
+    """A small random prefill: shape, lengths around tile and chunk boundaries, cache kind and workspace by seed."""
+    r = torch.Generator().manual_seed(1000 + seed)
+    pick = lambda xs: xs[int(torch.randint(len(xs), (1,), generator=r))]
+    G, Hkv, B = pick([1, 2, 4, 8]), pick([1, 2]), pick([1, 2, 3])
+    n_max = pick([40, 130, 257, 600, 1100])
+    lens = [int(torch.randint(1, n_max + 1, (1,), generator=r)) for _ in range(B)]
+    lens[int(torch.randint(B, (1,), generator=r))] = n_max
+    P = min(pick([1, 3, 17, 40, 90]), n_max)
+    page = pick([0, 0, 16, 32])
+    chunked = pick([True, False])
+    return G, Hkv, B, lens, n_max, P, page, chunked
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_small_prefills(seed):
+    G, Hkv, B, lens, n_max, P, page, chunked = _random_prefill_case(seed)
+    g = torch.Generator(device=DEV).manual_seed(seed)
+    d = 128
+    q = torch.randn((B, P, G * Hkv, d), generator=g, device=DEV).to(torch.bfloat16)
+    K = torch.randn((B, Hkv, n_max, d), generator=g, device=DEV).to(torch.bfloat16)
+    V = torch.randn((B, Hkv, n_max, d), generator=g, device=DEV).to(torch.bfloat16)
+    lens_d = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    Kc, Vc = K, V
+    if page:
+        w = W.workload("c4", seq_lens=tuple(lens), k=8, num_q_heads=G * Hkv, num_kv_heads=Hkv)
+        table, num_pages = W.page_table(w, page, device=DEV)
+        _, Kc = W.paginate(K, table, num_pages, page)
+        _, Vc = W.paginate(V, table, num_pages, page)
+        shape = tidal.make_paged_shape(q[:, 0].contiguous(), Kc, table, lens_d, n_max)
+    else:
+        shape = tidal.make_shape(q[:, 0].contiguous(), K, lens_d)
+    td = tidal.Tidal(shape, 0, prefill_new=P) if chunked else tidal.Tidal(shape, 0, workspace_bytes=0)
+    out = torch.full_like(q, float("nan"))
+    say("random prefill %d: G%d Hkv%d lens %s P%d page %d chunked %s" % (seed, G, Hkv, lens, P, page, chunked))
+    td.prefill_attend(shape, q, Kc, Vc, out)
+    torch.cuda.synchronize()
+    for b, n in enumerate(lens):        # new tokens that would sit before the start of the cache yield zeros
+        m = min(P, n)
+        assert (out[b, :P - m] == 0).all()
+        ref = O.prefill(host(q[b:b + 1, P - m:]).contiguous(), host(K[b:b + 1]), host(V[b:b + 1]), [n])
+        check_output(out[b:b + 1, P - m:], ref, "random prefill %d, sequence %d" % (seed, b), single_bf16_p=True)
+    td.close()
+
+
+def test_prefill_whose_row_maxima_keep_rising():
+    """Keys grow along the sequence, so every later tile raises the rows' reference maxima by far more than the
+    lazy margin: the rescale path and the reload after it run throughout, also across token chunks."""
+    n, P, Hq, Hkv, d = 3000, 20, 8, 2, 128
+    g = torch.Generator(device=DEV).manual_seed(4)
+    q = torch.randn((1, P, Hq, d), generator=g, device=DEV).abs().to(torch.bfloat16)
+    ramp = torch.linspace(0.05, 3.0, n, device=DEV)[None, None, :, None]
+    K = (torch.randn((1, Hkv, n, d), generator=g, device=DEV).abs() * ramp).to(torch.bfloat16)
+    V = torch.randn((1, Hkv, n, d), generator=g, device=DEV).to(torch.bfloat16)
+    lens = torch.tensor([n], dtype=torch.int32, device=DEV)
+    shape = tidal.make_shape(q[:, 0].contiguous(), K, lens)
+    for chunked in (True, False):
+        td = tidal.Tidal(shape, 0, prefill_new=P) if chunked else tidal.Tidal(shape, 0, workspace_bytes=0)
+        out = torch.full_like(q, float("nan"))
+        say("rising maxima, chunked %s" % chunked)
+        td.prefill_attend(shape, q, K, V, out)
+        torch.cuda.synchronize()
+        check_output(out, O.prefill(host(q), host(K), host(V), [n]), "rising maxima", single_bf16_p=True)
+        td.close()
