@@ -27,7 +27,11 @@
  *              b*kv_stride_batch + g*kv_stride_head + j*kv_stride_tok + c
  *              (strides in elements, multiples of 8; head_dim contiguous).
  *              Token j of sequence b is valid for 0 <= j < seq_lens[b]; the
- *              cache already holds the current token (Alg. 1 appends first).
+ *              cache already holds the current token (Alg. 1 appends first),
+ *              so 1 <= seq_lens[b] <= max_seq_len.  The lengths live in device
+ *              memory and are not checked: values above max_seq_len count as
+ *              max_seq_len, and for a sequence of length 0 (or less) the decode
+ *              calls leave its rows of `out` untouched and fill its rho with -1.
  *     Pointers must be 16-byte aligned.
  *   - Paged cache (shape.page_size > 0; serving systems hand the cache out in
  *     pages, as the paged full-attention baseline and the page-level method

@@ -296,3 +296,29 @@ def test_correction_prefill_as_pseudo_sequences_sharing_one_cache():
     ref = O.full(host(q), host(K).expand(P_tok, -1, -1, -1), host(V).expand(P_tok, -1, -1, -1), lens_list)
     check_output(out, ref, "correction prefill")
     td.close()
+
+
+def test_a_sequence_of_length_zero_is_left_alone():
+    # lengths live in device memory and are not checked: an empty sequence gets no output rows and a rho of -1
+    w = W.workload("c4", seq_lens=(300, 5, 1200), k=64)
+    layers = device_layers(w, range(3))
+    q, K, V = layers[0]
+    lens = torch.tensor([300, 0, 1200], dtype=torch.int32, device=DEV)
+    shape = tidal.make_shape(q, K, lens)
+    td = tidal.Tidal(shape, w.k)
+    outs = [torch.full_like(q, 7.0) for _ in range(3)]
+    pos = torch.full((1, w.batch, w.num_kv_heads, w.k), -7, dtype=torch.int32, device=DEV)
+    say("decode step with an empty sequence")
+    td.decode_step(shape, (W.DENSE, W.SELECT, W.SPARSE), [l[0] for l in layers], [l[1] for l in layers],
+                   [l[2] for l in layers], w.k, outs, pos)
+    torch.cuda.synchronize()
+    for o in outs:
+        assert (o[1] == 7.0).all() and torch.isfinite(o.float()).all()
+    assert (pos[0, 1] == -1).all()
+    keep = [0, 2]
+    sub = [300, 1200]
+    for i, kind in enumerate((W.DENSE, W.SELECT)):
+        qi, Ki, Vi = layers[i]
+        ref = O.full(host(qi[keep]).contiguous(), host(Ki[keep]).contiguous(), host(Vi[keep]).contiguous(), sub)
+        check_output(outs[i][keep], ref, "layer %d beside an empty sequence" % i)
+    td.close()
