@@ -246,10 +246,21 @@ td_status td_plan_launch(const td_ctx *ctx, const td_shape *shape, int32_t layer
 td_status td_set_tuning(td_ctx *ctx, int32_t target_workgroups, int32_t min_chunk_dense,
                         int32_t min_chunk_sparse, int32_t max_splits, int32_t kernel_variant);
 
+/* Split launches of the attention calls meet through ticket counters in the context's workspace
+ * (one per sequence and KV head), which every launch leaves at zero.  td_reset enqueues a kernel
+ * on `hip_stream` that zeroes them: the way back for a context whose launch was cut short (a
+ * device error, a process that aborted a stream) or that two streams used at once, both of which
+ * would otherwise leave every later result on that context undefined.  A launch that the library
+ * itself sees fail triggers the same clearing before the next attention call.  Costs one small
+ * launch; not needed in normal operation. */
+td_status td_reset(td_ctx *ctx, void *hip_stream);
+
 /* Measurement helper, not part of the attention path: a plain streaming kernel
  * of known size.  Copies `bytes` (rounded down to 16) from src to dst, or only
  * reads src when dst is NULL.  Used to calibrate hardware counters and to
- * report a measured streaming rate next to the published HBM peak. */
+ * report a measured streaming rate next to the published HBM peak.  It touches
+ * nothing of the context's workspace (its only write besides dst goes to a word
+ * that the context allocates for this call alone). */
 td_status td_probe_stream(td_ctx *ctx, void *dst, const void *src, size_t bytes, void *hip_stream);
 
 const char *td_status_string(td_status s);

@@ -14,6 +14,8 @@ struct td_ctx {
     int device = 0;
     char *workspace = nullptr;
     size_t workspace_bytes = 0;
+    uint32_t *probe_sink = nullptr;  // one word of its own for td_probe_stream; never product state
+    bool counters_dirty = false;     // a launch failed: the ticket counters are cleared before the next one
     int32_t target_workgroups = 0, min_chunk_dense = 0, min_chunk_sparse = 0, max_splits = 0, kernel_variant = 0;
     char error[256] = {0};
 };
@@ -102,6 +104,19 @@ struct Workspace {
 };
 
 constexpr size_t kCountersBytes = (size_t)kCountersMax * sizeof(int32_t);
+
+// Zeroes n 32-bit words.  A kernel rather than hipMemsetAsync so that the callers stay capturable
+// into a HIP graph.
+__global__ __launch_bounds__(256) void clear_words_kernel(uint32_t *dst, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = 0u;
+}
+
+hipError_t clear_counters(char *workspace, size_t counters, hipStream_t stream) {
+    const int blocks = (int)std::min<size_t>(64, (counters + 255) / 256);
+    hipLaunchKernelGGL(clear_words_kernel, dim3(blocks), dim3(256), 0, stream, reinterpret_cast<uint32_t *>(workspace),
+                       counters);
+    return hipGetLastError();
+}
 
 Workspace workspace_layout(const td_shape *s, int32_t k) {
     Workspace w;
@@ -246,9 +261,17 @@ td_status attend(td_ctx *ctx, const td_shape *s, int mode, const void *q, const 
     p.num_splits = plan.splits;
     const int group = plan.group, waves = plan.waves;
     const bool mfma = plan.matrix_core;
+    if (ctx->counters_dirty) {  // an earlier launch on this context failed: start from zeroed tickets
+        const hipError_t ce = clear_counters(ctx->workspace, kCountersMax, stream);
+        if (ce != hipSuccess) return fail(ctx, TD_ERR_HIP, "clearing the ticket counters failed: %s", hipGetErrorString(ce));
+        ctx->counters_dirty = false;
+    }
     const hipError_t e = mfma ? launch_attend_mfma(group, waves, mode, p, stream)
                               : launch_attend(s->dtype, s->head_dim, group, waves, mode, p, stream);
-    if (e != hipSuccess) return fail(ctx, TD_ERR_HIP, "attention launch failed: %s", hipGetErrorString(e));
+    if (e != hipSuccess) {
+        ctx->counters_dirty = true;
+        return fail(ctx, TD_ERR_HIP, "attention launch failed: %s", hipGetErrorString(e));
+    }
     return TD_OK;
 }
 
@@ -380,8 +403,12 @@ td_status td_create(td_ctx **out, int device, size_t workspace_bytes) {
     hipError_t e = hipSetDevice(device);
     if (e == hipSuccess && workspace_bytes) e = hipMalloc(reinterpret_cast<void **>(&ctx->workspace), workspace_bytes);
     if (e == hipSuccess && workspace_bytes) e = hipMemset(ctx->workspace, 0, workspace_bytes);  // chunk counters start at zero
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&ctx->probe_sink), 256);
+    if (e == hipSuccess) e = hipMemset(ctx->probe_sink, 0, 256);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
+        if (ctx->workspace) (void)hipFree(ctx->workspace);
+        if (ctx->probe_sink) (void)hipFree(ctx->probe_sink);
         delete ctx;
         return TD_ERR_HIP;
     }
@@ -394,6 +421,10 @@ td_status td_destroy(td_ctx *ctx) {
     if (!ctx) return TD_ERR_INVALID_ARG;
     hipError_t e = hipSuccess;
     if (ctx->workspace) e = hipFree(ctx->workspace);
+    if (ctx->probe_sink) {
+        const hipError_t e2 = hipFree(ctx->probe_sink);
+        if (e == hipSuccess) e = e2;
+    }
     delete ctx;
     return e == hipSuccess ? TD_OK : TD_ERR_HIP;
 }
@@ -556,8 +587,7 @@ td_status td_probe_stream(td_ctx *ctx, void *dst, const void *src, size_t bytes,
     if (!ctx) return TD_ERR_INVALID_ARG;
     if (!src || bytes < 16 || misaligned(src) || (dst && misaligned(dst)))
         return fail(ctx, TD_ERR_INVALID_ARG, "%s", "src (and dst) must be 16-byte aligned and bytes >= 16");
-    const hipError_t e = launch_probe(dst, src, bytes, reinterpret_cast<uint32_t *>(ctx->workspace),
-                                      static_cast<hipStream_t>(hip_stream));
+    const hipError_t e = launch_probe(dst, src, bytes, ctx->probe_sink, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return fail(ctx, TD_ERR_HIP, "probe launch failed: %s", hipGetErrorString(e));
     return TD_OK;
 }
@@ -574,5 +604,17 @@ const char *td_status_string(td_status s) {
 }
 
 const char *td_last_error(const td_ctx *ctx) { return ctx ? ctx->error : "context is NULL"; }
+
+td_status td_reset(td_ctx *ctx, void *hip_stream) {
+    if (!ctx) return TD_ERR_INVALID_ARG;
+    if (!ctx->workspace || ctx->workspace_bytes < kCountersBytes) {
+        ctx->counters_dirty = false;  // no attention call fits this workspace, nothing to clear
+        return TD_OK;
+    }
+    const hipError_t e = clear_counters(ctx->workspace, kCountersMax, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail(ctx, TD_ERR_HIP, "clearing the ticket counters failed: %s", hipGetErrorString(e));
+    ctx->counters_dirty = false;
+    return TD_OK;
+}
 
 }  // extern "C"

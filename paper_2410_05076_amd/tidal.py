@@ -19,7 +19,7 @@ LAYER_DENSE, LAYER_SELECT, LAYER_SPARSE = 0, 1, 2
 
 EXPORTS = ("td_validate", "td_workspace_bytes", "td_topk_workspace_bytes", "td_create", "td_destroy", "td_full_attend",
            "td_select_tokens", "td_sparse_attend", "td_prefill_attend", "td_prefill_workspace_bytes", "td_topk", "td_decode_step", "td_decode_step_append",
-           "td_plan_launch", "td_set_tuning", "td_probe_stream",
+           "td_plan_launch", "td_set_tuning", "td_probe_stream", "td_reset",
            "td_status_string", "td_last_error")
 
 
@@ -98,6 +98,7 @@ def lib():
     L.td_plan_launch.restype = ctypes.c_int
     L.td_set_tuning.argtypes, L.td_set_tuning.restype = [vp, i32, i32, i32, i32, i32], ctypes.c_int
     L.td_probe_stream.argtypes, L.td_probe_stream.restype = [vp, vp, vp, sz, vp], ctypes.c_int
+    L.td_reset.argtypes, L.td_reset.restype = [vp, vp], ctypes.c_int
     L.td_status_string.argtypes, L.td_status_string.restype = [ctypes.c_int], ctypes.c_char_p
     L.td_last_error.argtypes, L.td_last_error.restype = [vp], ctypes.c_char_p
     _lib = L
@@ -179,6 +180,10 @@ class Tidal:
                    kernel_variant=0):
         self._check(lib().td_set_tuning(self._ctx, target_workgroups, min_chunk_dense, min_chunk_sparse,
                                         max_splits, kernel_variant))
+
+    def reset(self):
+        """td_reset: zeroes the ticket counters on the current stream."""
+        self._check(lib().td_reset(self._ctx, _stream()))
 
     def full_attend(self, shape, q, K, V, out):
         self._check(lib().td_full_attend(self._ctx, ctypes.byref(shape), q.data_ptr(), K.data_ptr(),
