@@ -218,6 +218,23 @@ td_status td_decode_step_append(td_ctx *ctx, const td_shape *shape, int32_t num_
                                 void *const *K_layers, void *const *V_layers, int32_t k,
                                 void *const *out_layers, int32_t *positions, void *hip_stream);
 
+/* For callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): td_decode_step without a context.  The workspace is a device array with
+ * static storage inside the library, TD_STATIC_SCRATCH_BYTES per GPU that the library runs on, held
+ * until the process ends; the call allocates and frees nothing and uses the default launch plan.
+ * Arguments and results are those of td_decode_step.  Shapes with td_workspace_bytes(shape, k) above
+ * TD_STATIC_SCRATCH_BYTES return TD_ERR_WORKSPACE before anything is enqueued (the single-sequence
+ * benchmark shapes up to 128K tokens and batch 4 x 128K fit; batch 16 x 64K does not).  The kernels
+ * run on the device that is current when the call is made; `hip_stream` must belong to it.  Every
+ * call on a GPU shares that GPU's array: calls that overlap on one GPU (two streams, two threads)
+ * race and give undefined results; calls ordered on one stream are safe, each one zeroes the ticket
+ * counters it uses first.  td_last_error(NULL) returns the text of this thread's last failure. */
+#define TD_STATIC_SCRATCH_BYTES ((size_t)48 << 20)
+td_status td_decode_step_static(const td_shape *shape, int32_t num_layers, const int32_t *schedule,
+                                const void *const *q_layers, const void *const *K_layers,
+                                const void *const *V_layers, int32_t k, void *const *out_layers,
+                                int32_t *positions, void *hip_stream);
+
 /* Host-only: how a layer of kind `layer_kind` (td_layer_kind) would be launched for this shape
  * and budget - nothing is enqueued.  ctx may be NULL (default tuning).  For sizing, logging
  * and tests of the launch planning. */

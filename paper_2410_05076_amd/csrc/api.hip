@@ -414,6 +414,7 @@ td_status td_create(td_ctx **out, int device, size_t workspace_bytes) {
     }
     ctx->workspace_bytes = workspace_bytes;
     *out = ctx;
+    (void)static_scratch_setup();  // set-up for td_decode_step_static on this device; that call repeats it on failure
     return TD_OK;
 }
 
@@ -603,7 +604,39 @@ const char *td_status_string(td_status s) {
     return "unknown status";
 }
 
-const char *td_last_error(const td_ctx *ctx) { return ctx ? ctx->error : "context is NULL"; }
+const char *td_last_error(const td_ctx *ctx) { return ctx ? ctx->error : static_last_error(); }
+
+}  // extern "C"
+
+// The layer loop on a workspace that the caller names, with the default launch plan.  The ticket
+// counters that this shape uses are zeroed first (the workspace may hold anything); `error`
+// receives the text of a failure.
+td_status tidal::decode_step_on_workspace(char *workspace, size_t workspace_bytes, const td_shape *shape,
+                                          int32_t num_layers, const int32_t *schedule, const void *const *q_layers,
+                                          const void *const *K_layers, const void *const *V_layers, int32_t k,
+                                          void *const *out_layers, int32_t *positions, void *hip_stream,
+                                          char (&error)[256]) {
+    td_ctx local;
+    local.workspace = workspace;
+    local.workspace_bytes = workspace_bytes;
+    td_status code;
+    td_status st;
+    if (const char *why = shape_problem(shape, k, &code)) {
+        st = fail(&local, code, "%s", why);
+    } else {
+        const size_t rows = (size_t)shape->batch * std::max(shape->num_kv_heads, selection_rows(shape));
+        const hipError_t e = workspace_layout(shape, k).total <= workspace_bytes
+                                 ? clear_counters(workspace, rows, static_cast<hipStream_t>(hip_stream))
+                                 : hipSuccess;  // too small: decode_step says so before anything is enqueued
+        st = e != hipSuccess ? fail(&local, TD_ERR_HIP, "clearing the ticket counters failed: %s", hipGetErrorString(e))
+                             : decode_step(&local, shape, num_layers, schedule, q_layers, nullptr, nullptr, K_layers,
+                                           V_layers, k, out_layers, positions, hip_stream);
+    }
+    memcpy(error, local.error, sizeof local.error);
+    return st;
+}
+
+extern "C" {
 
 td_status td_reset(td_ctx *ctx, void *hip_stream) {
     if (!ctx) return TD_ERR_INVALID_ARG;

@@ -118,6 +118,18 @@ hipError_t launch_topk(const float *scores, int64_t row_stride, int32_t rows, co
                        int32_t rows_per_len, int32_t max_len, int32_t k, int32_t *positions, void *scratch,
                        bool reset, hipStream_t stream);
 
+// The layer loop of td_decode_step on a workspace that the caller names (default launch plan).  The
+// ticket counters the shape uses are zeroed first; `error` receives the text of a failure.
+td_status decode_step_on_workspace(char *workspace, size_t workspace_bytes, const td_shape *shape, int32_t num_layers,
+                                   const int32_t *schedule, const void *const *q_layers, const void *const *K_layers,
+                                   const void *const *V_layers, int32_t k, void *const *out_layers, int32_t *positions,
+                                   void *hip_stream, char (&error)[256]);
+
+// static_entry.hip: resolves the current device's copy of the static scratch array (idempotent);
+// the text of the last failure of td_decode_step_static on this thread.
+hipError_t static_scratch_setup();
+const char *static_last_error();
+
 // Streaming probe: copies `bytes` from src to dst, or (dst == nullptr) only reads src.
 hipError_t launch_probe(void *dst, const void *src, size_t bytes, uint32_t *sink, hipStream_t stream);
 

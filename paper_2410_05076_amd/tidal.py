@@ -19,7 +19,7 @@ LAYER_DENSE, LAYER_SELECT, LAYER_SPARSE = 0, 1, 2
 
 EXPORTS = ("td_validate", "td_workspace_bytes", "td_topk_workspace_bytes", "td_create", "td_destroy", "td_full_attend",
            "td_select_tokens", "td_sparse_attend", "td_prefill_attend", "td_prefill_workspace_bytes", "td_topk", "td_decode_step", "td_decode_step_append",
-           "td_plan_launch", "td_set_tuning", "td_probe_stream", "td_reset",
+           "td_decode_step_static", "td_plan_launch", "td_set_tuning", "td_probe_stream", "td_reset",
            "td_status_string", "td_last_error")
 
 
@@ -94,6 +94,8 @@ def lib():
     pv = ctypes.POINTER(vp)
     L.td_decode_step_append.argtypes = [vp, shp, i32, ctypes.POINTER(i32), pv, pv, pv, pv, pv, i32, pv, vp, vp]
     L.td_decode_step_append.restype = ctypes.c_int
+    L.td_decode_step_static.argtypes = [shp, i32, ctypes.POINTER(i32), pv, pv, pv, i32, pv, vp, vp]
+    L.td_decode_step_static.restype = ctypes.c_int
     L.td_plan_launch.argtypes = [vp, shp, i32, i32, ctypes.POINTER(LaunchPlan)]
     L.td_plan_launch.restype = ctypes.c_int
     L.td_set_tuning.argtypes, L.td_set_tuning.restype = [vp, i32, i32, i32, i32, i32], ctypes.c_int
@@ -142,6 +144,22 @@ def make_paged_shape(q, pool, block_table, seq_lens, max_seq_len, sm_scale=0.0, 
 
 def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+STATIC_SCRATCH_BYTES = 48 << 20
+
+
+def decode_step_static(shape, schedule, qs, Ks, Vs, k, outs, positions):
+    """td_decode_step_static: the decode step on the library's static scratch, no context, no allocation."""
+    n = len(schedule)
+    arr = ctypes.c_void_p * n
+    sched = (ctypes.c_int32 * n)(*[int(x) for x in schedule])
+    st = lib().td_decode_step_static(
+        ctypes.byref(shape), n, sched, arr(*[t.data_ptr() for t in qs]), arr(*[t.data_ptr() for t in Ks]),
+        arr(*[t.data_ptr() for t in Vs]), k, arr(*[t.data_ptr() for t in outs]), positions.data_ptr(), _stream())
+    if st != OK:
+        raise TidalError(st, lib().td_last_error(None).decode())
+    return outs, positions
 
 
 class Tidal:
