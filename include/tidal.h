@@ -244,6 +244,7 @@ typedef struct td_launch_plan {
     int32_t waves_per_workgroup; /* 4 or 8 wave64s */
     int32_t matrix_core;         /* 1: the MFMA kernel, 0: the vector-ALU kernel */
     int32_t grid_rows;           /* batch * KV heads (query heads for a per-head sparse layer) */
+    int32_t merge_launch;        /* 1: a second small launch folds the chunk partials, 0: the last chunk does */
     int64_t workgroups;          /* grid_rows * chunks_per_row, empty chunks of short sequences included */
 } td_launch_plan;
 td_status td_plan_launch(const td_ctx *ctx, const td_shape *shape, int32_t layer_kind, int32_t k,
@@ -258,8 +259,10 @@ td_status td_plan_launch(const td_ctx *ctx, const td_shape *shape, int32_t layer
  * the vector-ALU kernel; four or eight waves per workgroup; 1: the matrix-core
  * kernel wherever it applies; 2 / 3:
  * the vector-ALU kernel with four / eight waves per workgroup in every launch;
- * 4 / 5: the same for the matrix-core kernel).  The workspace size does not
- * depend on them. */
+ * 4 / 5: the same for the matrix-core kernel; plus 8: the chunk partials of
+ * every split launch are folded by a second small launch, plus 16: by the
+ * chunk that finishes last, instead of the choice per launch).  The workspace
+ * size does not depend on them. */
 td_status td_set_tuning(td_ctx *ctx, int32_t target_workgroups, int32_t min_chunk_dense,
                         int32_t min_chunk_sparse, int32_t max_splits, int32_t kernel_variant);
 

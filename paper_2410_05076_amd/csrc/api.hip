@@ -17,6 +17,7 @@ struct td_ctx {
     uint32_t *probe_sink = nullptr;  // one word of its own for td_probe_stream; never product state
     bool counters_dirty = false;     // a launch failed: the ticket counters are cleared before the next one
     int32_t target_workgroups = 0, min_chunk_dense = 0, min_chunk_sparse = 0, max_splits = 0, kernel_variant = 0;
+    int32_t merge_mode = 0;          // 0: chosen per launch, 1: a second launch merges the partials, 2: the last chunk does
     char error[256] = {0};
 };
 
@@ -180,6 +181,7 @@ struct LaunchPlan {
     int32_t group;               // query heads served by a grid row
     int32_t grid_rows_per_seq;   // KV heads, or query heads when a sparse layer follows the per-head rule
     bool matrix_core;
+    bool separate_merge;         // the chunk partials are folded by a second launch instead of the last chunk
 };
 
 LaunchPlan plan_launch(const td_ctx *ctx, const td_shape *s, int mode, int32_t k) {
@@ -198,7 +200,7 @@ LaunchPlan plan_launch(const td_ctx *ctx, const td_shape *s, int mode, int32_t k
     // 16-row tile is empty.  Hence: every layer kind for groups of four and more, full layers
     // only for smaller groups.
     const bool mfma_ok = s->dtype == TD_BF16 && s->head_dim == 128;
-    const int32_t kv = ctx ? ctx->kernel_variant : 0;
+    const int32_t kv = ctx ? ctx->kernel_variant : 0;  // the low three bits of td_set_tuning's kernel_variant
     plan.matrix_core = mfma_ok && (kv == 1 || kv == 4 || kv == 5 || (kv == 0 && (plan.group >= 4 || mode == kDense)));
     // Workgroup size.  Full and selection layers use eight waves (half as many partials to merge
     // across workgroups; measured 3 to 9 % faster per launch on the uniform workloads) unless the
@@ -213,6 +215,8 @@ LaunchPlan plan_launch(const td_ctx *ctx, const td_shape *s, int mode, int32_t k
     if (kv == 3 || kv == 5) plan.waves = 8;
     if (!attend_supports_waves(plan.group, plan.waves)) plan.waves = 4;
     plan_chunks(ctx, s, mode, plan.waves, mode == kSparse ? k : s->max_seq_len, &plan.chunk, &plan.splits);
+    const int32_t merge_mode = ctx ? ctx->merge_mode : 0;
+    plan.separate_merge = plan.splits > 1 && merge_mode == 1;
     return plan;
 }
 
@@ -259,6 +263,7 @@ td_status attend(td_ctx *ctx, const td_shape *s, int mode, const void *q, const 
     }
     p.chunk = plan.chunk;
     p.num_splits = plan.splits;
+    p.separate_merge = plan.separate_merge ? 1 : 0;
     const int group = plan.group, waves = plan.waves;
     const bool mfma = plan.matrix_core;
     if (ctx->counters_dirty) {  // an earlier launch on this context failed: start from zeroed tickets
@@ -271,6 +276,10 @@ td_status attend(td_ctx *ctx, const td_shape *s, int mode, const void *q, const 
     if (e != hipSuccess) {
         ctx->counters_dirty = true;
         return fail(ctx, TD_ERR_HIP, "attention launch failed: %s", hipGetErrorString(e));
+    }
+    if (plan.separate_merge) {
+        const hipError_t me = launch_merge(s->dtype, s->head_dim, mode, p, stream);
+        if (me != hipSuccess) return fail(ctx, TD_ERR_HIP, "merge launch failed: %s", hipGetErrorString(me));
     }
     return TD_OK;
 }
@@ -440,6 +449,7 @@ td_status td_plan_launch(const td_ctx *ctx, const td_shape *shape, int32_t layer
     plan->chunks_per_row = lp.splits;
     plan->waves_per_workgroup = lp.waves;
     plan->matrix_core = lp.matrix_core ? 1 : 0;
+    plan->merge_launch = lp.separate_merge ? 1 : 0;
     plan->grid_rows = shape->batch * lp.grid_rows_per_seq;
     plan->workgroups = (int64_t)plan->grid_rows * lp.splits;
     return TD_OK;
@@ -449,13 +459,14 @@ td_status td_set_tuning(td_ctx *ctx, int32_t target_workgroups, int32_t min_chun
                         int32_t min_chunk_sparse, int32_t max_splits, int32_t kernel_variant) {
     if (!ctx) return TD_ERR_INVALID_ARG;
     if (target_workgroups < 0 || min_chunk_dense < 0 || min_chunk_sparse < 0 || max_splits < 0 ||
-        kernel_variant < 0 || kernel_variant > 5)
-        return fail(ctx, TD_ERR_INVALID_ARG, "%s", "tuning values must be >= 0");
+        kernel_variant < 0 || (kernel_variant & 7) > 5 || (kernel_variant >> 3) > 2)
+        return fail(ctx, TD_ERR_INVALID_ARG, "%s", "tuning values must be >= 0, kernel_variant one of those the header lists");
     ctx->target_workgroups = target_workgroups;
     ctx->min_chunk_dense = min_chunk_dense;
     ctx->min_chunk_sparse = min_chunk_sparse;
     ctx->max_splits = max_splits;
-    ctx->kernel_variant = kernel_variant;
+    ctx->kernel_variant = kernel_variant & 7;
+    ctx->merge_mode = kernel_variant >> 3;
     return TD_OK;
 }
 

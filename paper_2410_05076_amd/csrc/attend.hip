@@ -359,7 +359,7 @@ void attend_split_kernel(const AttendParams p) {
         __syncthreads();
         fold_states<DT, D, G, GC, RG, T>(p, sm, b, g, split, ns, h0);
     }
-    if (ns == 1) return;
+    if (ns == 1 || p.separate_merge) return;
     finish_chunks<DT, D, G, GC, RG, T>(p, sm, b, g, ns);
 }
 

@@ -328,7 +328,7 @@ void attend_mfma_kernel(const AttendParams p) {
     }
     __syncthreads();
     fold_states<TD_BF16, kD, G, G, RG, T>(p, sm, b, g, split, ns, 0);
-    if (ns == 1) return;
+    if (ns == 1 || p.separate_merge) return;
     finish_chunks<TD_BF16, kD, G, G, RG, T>(p, sm, b, g, ns);
 }
 

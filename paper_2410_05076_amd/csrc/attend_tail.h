@@ -112,6 +112,13 @@ __device__ __forceinline__ void fold_states(const AttendParams &p, TailShared<D,
                 p.ml_out[head * 2] = mx;
                 p.ml_out[head * 2 + 1] = ls;
             }
+        } else if (p.separate_merge) {  // a second launch merges: the kernel boundary makes plain stores visible
+            const int64_t slot = head * p.num_splits + split;
+            p.part_acc[slot * D + ch] = as;
+            if (ch == 0) {
+                p.part_ml[slot * 2] = mx;
+                p.part_ml[slot * 2 + 1] = ls;
+            }
         } else {
             const int64_t slot = head * p.num_splits + split;
             publish(&p.part_acc[slot * D + ch], as);
@@ -123,45 +130,37 @@ __device__ __forceinline__ void fold_states(const AttendParams &p, TailShared<D,
     }
 }
 
-// After every head's partial of this chunk has been published: the chunk that finishes last
-// merges all partials of its (sequence, KV head).  Partials are published with device-scope
-// write-through stores and every wave waits for its stores to complete before the barrier,
-// so they are in memory before this workgroup's ticket is taken.  (A release fence in every
-// workgroup would write back the whole L2 each time.)  The counter returns to zero for the
-// next launch.
-template <int DT, int D, int G, int GC, int RG, int T>
-__device__ __forceinline__ void finish_chunks(const AttendParams &p, TailShared<D, GC, RG, T> &sm, int b, int g,
-                                              int ns) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        int *counter = p.counters + b * p.num_kv_heads + g;
-        const int done = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        sm.last = done == ns - 1;
-        if (sm.last) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    __syncthreads();
-    if (!sm.last) return;
+// LDS of merge_partials for a workgroup of T threads: one float4 and one (max, sum) pair per thread.
+template <int T>
+struct MergeShared {
+    __align__(16) float4 a[T];
+    float2 ml[T];
+};
 
-    // One pass over the partials: thread (sg, col) folds chunks sg, sg + NG, ... of one float4
-    // column of one head with the online rescaling rule, eight chunks in flight at a time,
-    // then the NG threads of a column are folded through LDS.  The partials are read with
-    // device-scope loads (they come from other workgroups' write-through stores), which
-    // needs no cache invalidate.  (A single CU sustains only about 30 GB/s on these loads
-    // however many are in flight, so this phase costs about 1 us per 32 KiB of partials.)
-    constexpr int COLS = G * D / 4;  // float4 columns over all heads of the group
-    constexpr int NG = T / COLS;     // chunk groups working in parallel
-    static_assert(NG >= 1 && NG * COLS == T, "G * D / 4 must divide the workgroup size");
+// Folds the ns chunk partials of GH query heads (head0 .. head0 + GH - 1 of the flattened
+// [sequence][query head] index) and writes their output rows.  Every thread of a workgroup of T
+// threads calls it.  One pass over the partials: thread (sg, col) folds chunks sg, sg + NG, ... of
+// one float4 column of one head with the online rescaling rule, eight chunks in flight at a time,
+// then the NG threads of a column are folded through LDS.
+// COHERENT: the partials come from workgroups of the same launch (device-scope write-through
+// stores), so they are read with device-scope loads, which need no cache invalidate; otherwise an
+// earlier launch wrote them and ordinary loads do.  (A single CU sustains only about 30 GB/s on
+// these loads however many are in flight, so this phase costs about 1 us per 32 KiB of partials.)
+template <int DT, int D, int GH, int T, bool COHERENT>
+__device__ __forceinline__ void merge_partials(const AttendParams &p, MergeShared<T> &red, int64_t head0, int ns) {
+    constexpr int COLS = GH * D / 4;  // float4 columns over all heads merged here
+    constexpr int NG = T / COLS;      // chunk groups working in parallel
+    static_assert(NG >= 1 && NG * COLS == T, "GH * D / 4 must divide the workgroup size");
     const int col = threadIdx.x % COLS, sg = threadIdx.x / COLS;
     const int hi = col / (D / 4), c4 = col % (D / 4);
-    const int64_t head0 = (int64_t)b * p.num_q_heads + g * G;
     const int64_t head = head0 + hi;
-    const __amdgpu_buffer_rsrc_t pa =  // the group's partials, [G][num_splits][D]
-        partial_resource(p.part_acc + head0 * p.num_splits * D, (uint32_t)(G * p.num_splits * D) * 4);
-    const __amdgpu_buffer_rsrc_t pml =  // and their (max, sum) pairs, [G][num_splits][2]
-        partial_resource(p.part_ml + head0 * p.num_splits * 2, (uint32_t)(G * p.num_splits) * 8);
+    const __amdgpu_buffer_rsrc_t pa =  // the heads' partials, [GH][num_splits][D]
+        partial_resource(p.part_acc + head0 * p.num_splits * D, (uint32_t)(GH * p.num_splits * D) * 4);
+    const __amdgpu_buffer_rsrc_t pml =  // and their (max, sum) pairs, [GH][num_splits][2]
+        partial_resource(p.part_ml + head0 * p.num_splits * 2, (uint32_t)(GH * p.num_splits) * 8);
     const uint32_t pa_off = ((uint32_t)(hi * p.num_splits) * D + c4 * 4) * 4;
     const uint32_t pml_off = (uint32_t)(hi * p.num_splits) * 8;
+    constexpr int kPolicy = COHERENT ? kCachePolicySc1 : 0;
     float mm = kEmptyMax, ll = 0.f;
     float4 aa = make_float4(0.f, 0.f, 0.f, 0.f);
     constexpr int kBatch = 8;  // partials in flight per thread
@@ -171,8 +170,8 @@ __device__ __forceinline__ void finish_chunks(const AttendParams &p, TailShared<
 #pragma unroll
         for (int j = 0; j < kBatch; ++j) {
             const uint32_t s = min(s0 + j * NG, ns - 1);  // clamped repeats are ignored below
-            x[j] = coherent_load16(pa, pa_off + s * (D * 4));
-            v[j] = coherent_load8(pml, pml_off + s * 8);
+            x[j] = __builtin_amdgcn_raw_buffer_load_b128(pa, pa_off + s * (D * 4), 0, kPolicy);
+            v[j] = __builtin_amdgcn_raw_buffer_load_b64(pml, pml_off + s * 8, 0, kPolicy);
         }
 #pragma unroll
         for (int j = 0; j < kBatch; ++j) {
@@ -190,16 +189,14 @@ __device__ __forceinline__ void finish_chunks(const AttendParams &p, TailShared<
         }
     }
     if constexpr (NG > 1) {
-        float4 *red_a = reinterpret_cast<float4 *>(sm.acc);      // [T], sm.acc is free now
-        float2 *red_ml = reinterpret_cast<float2 *>(red_a + T);  // [T]
-        red_a[threadIdx.x] = aa;
-        red_ml[threadIdx.x] = make_float2(mm, ll);
+        red.a[threadIdx.x] = aa;
+        red.ml[threadIdx.x] = make_float2(mm, ll);
         __syncthreads();
         if (sg == 0) {
 #pragma unroll
             for (int o = 1; o < NG; ++o) {
-                const float2 v = red_ml[o * COLS + col];
-                const float4 x = red_a[o * COLS + col];
+                const float2 v = red.ml[o * COLS + col];
+                const float4 x = red.a[o * COLS + col];
                 const float mn = fmaxf(mm, v.x);
                 const float wa = fast_exp2(mm - mn), wb = fast_exp2(v.x - mn);
                 ll = ll * wa + v.y * wb;
@@ -223,6 +220,30 @@ __device__ __forceinline__ void finish_chunks(const AttendParams &p, TailShared<
         store_out<DT>(p.out, oi + 2, aa.z * inv);
         store_out<DT>(p.out, oi + 3, aa.w * inv);
     }
+}
+
+// After every head's partial of this chunk has been published: the chunk that finishes last
+// merges all partials of its (sequence, KV head).  Partials are published with device-scope
+// write-through stores and every wave waits for its stores to complete before the barrier,
+// so they are in memory before this workgroup's ticket is taken.  (A release fence in every
+// workgroup would write back the whole L2 each time.)  The counter returns to zero for the
+// next launch.
+template <int DT, int D, int G, int GC, int RG, int T>
+__device__ __forceinline__ void finish_chunks(const AttendParams &p, TailShared<D, GC, RG, T> &sm, int b, int g,
+                                              int ns) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int *counter = p.counters + b * p.num_kv_heads + g;
+        const int done = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sm.last = done == ns - 1;
+        if (sm.last) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (!sm.last) return;
+    static_assert(sizeof(MergeShared<T>) <= sizeof(sm.acc), "the merge reuses the state buffer");
+    merge_partials<DT, D, G, T, true>(p, *reinterpret_cast<MergeShared<T> *>(sm.acc),  // sm.acc is free now
+                                      (int64_t)b * p.num_q_heads + g * G, ns);
 }
 
 }  // namespace

@@ -61,6 +61,7 @@ struct AttendParams {
     int32_t k;
     int32_t chunk;       // tokens per workgroup
     int32_t num_splits;  // grid.x
+    int32_t separate_merge;  // 1: the chunks only leave their partials and launch_merge folds them
     float scale;
 };
 
@@ -72,6 +73,11 @@ bool attend_supports_waves(int group, int waves);
 hipError_t launch_attend(int dtype, int head_dim, int group, int waves, int mode, const AttendParams &p,
                          hipStream_t stream);
 hipError_t launch_attend_mfma(int group, int waves, int mode, const AttendParams &p, hipStream_t stream);
+
+// Second launch of a split layer (p.separate_merge): one workgroup per (sequence, query head)
+// folds the chunk partials that the attention launch left and writes the output row.  p and mode
+// are those of the attention launch.
+hipError_t launch_merge(int dtype, int head_dim, int mode, const AttendParams &p, hipStream_t stream);
 
 // Prefill attention over the last num_new tokens of every sequence (bf16, head_dim 128; contiguous cache, or
 // paged with pages of at least 16 tokens).

@@ -41,7 +41,8 @@ class LaunchPlan(ctypes.Structure):
     """td_launch_plan of include/tidal.h."""
     _fields_ = [("chunk_tokens", ctypes.c_int32), ("chunks_per_row", ctypes.c_int32),
                 ("waves_per_workgroup", ctypes.c_int32), ("matrix_core", ctypes.c_int32),
-                ("grid_rows", ctypes.c_int32), ("workgroups", ctypes.c_int64)]
+                ("grid_rows", ctypes.c_int32), ("merge_launch", ctypes.c_int32),
+                ("workgroups", ctypes.c_int64)]
 
 
 def plan_launch(shape, layer_kind, k, ctx=None):
