@@ -229,7 +229,7 @@ td_status td_decode_step_append(td_ctx *ctx, const td_shape *shape, int32_t num_
  * call on a GPU shares that GPU's array: calls that overlap on one GPU (two streams, two threads)
  * race and give undefined results; calls ordered on one stream are safe, each one zeroes the ticket
  * counters it uses first.  td_last_error(NULL) returns the text of this thread's last failure. */
-#define TD_STATIC_SCRATCH_BYTES ((size_t)48 << 20)
+#define TD_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
 td_status td_decode_step_static(const td_shape *shape, int32_t num_layers, const int32_t *schedule,
                                 const void *const *q_layers, const void *const *K_layers,
                                 const void *const *V_layers, int32_t k, void *const *out_layers,

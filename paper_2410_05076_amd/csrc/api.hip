@@ -31,6 +31,8 @@ constexpr int32_t kChunkGranule = 128;
 // chunks per (sequence, KV head): every chunk takes a ticket on one counter and the last one
 // merges all partials alone, so the tail grows with the count
 constexpr int32_t kDefaultMaxSplits = 64;
+// a selection layer's attention launch bins its scores itself when a row has at most this many chunks
+constexpr int32_t kFusedHistMaxSplits = 32;
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 int32_t ceil_div(int64_t a, int64_t b) { return (int32_t)((a + b - 1) / b); }
@@ -97,25 +99,49 @@ const char *shape_problem(const td_shape *s, int32_t k, td_status *code) {
 
 bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
-// Workspace: [ticket counters, fixed size][top-k scratch][chunk partials][group scores].
-// Only the counters carry state from one call to the next (they are zero between launches).
+// Workspace: [ticket counters | top-k state of up to kTopkFusedRows rows: fixed size, the same place for every
+// shape][top-k state of larger launches][top-k scratch][chunk partials][group scores].
+// Only the fixed part carries state from one call to the next: it is zero between launches, and because no
+// launch of any shape writes anything else there, it stays so when calls with different shapes share a context.
 struct Workspace {
-    size_t counters, topk, part_acc, part_ml, scores, head_logits, ml_final, total;
+    size_t counters, fused, topk_state, topk, part_acc, part_ml, scores, head_logits, ml_final, total;
     int64_t score_stride;
 };
 
 constexpr size_t kCountersBytes = (size_t)kCountersMax * sizeof(int32_t);
+constexpr size_t kFusedBytes = (size_t)kTopkFusedRows * sizeof(TopkRow);
+constexpr size_t kFixedBytes = kCountersBytes + kFusedBytes;
+static_assert(kFixedBytes % 256 == 0, "what follows the fixed part stays aligned");
 
-// Zeroes n 32-bit words.  A kernel rather than hipMemsetAsync so that the callers stay capturable
-// into a HIP graph.
-__global__ __launch_bounds__(256) void clear_words_kernel(uint32_t *dst, size_t n) {
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = 0u;
+// Where the top-k state of a launch with `rows` rows lives and what follows it.
+struct TopkPlace {
+    size_t state, scratch;  // byte offsets in the workspace
+    bool fixed;             // state inside the fixed part (zero between launches); else it is reset before use
+};
+TopkPlace topk_place(int32_t rows) {
+    TopkPlace t;
+    t.fixed = rows <= kTopkFusedRows;
+    t.state = t.fixed ? kCountersBytes : kFixedBytes;
+    t.scratch = t.fixed ? kFixedBytes : kFixedBytes + (size_t)rows * sizeof(TopkRow);
+    t.scratch = (t.scratch + 255) / 256 * 256;
+    return t;
 }
 
-hipError_t clear_counters(char *workspace, size_t counters, hipStream_t stream) {
-    const int blocks = (int)std::min<size_t>(64, (counters + 255) / 256);
+// Zeroes the first n0 32-bit words of a and the first n1 of b.  A kernel rather than hipMemsetAsync so that
+// the callers stay capturable into a HIP graph.
+__global__ __launch_bounds__(256) void clear_words_kernel(uint32_t *a, size_t n0, uint32_t *b, size_t n1) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n0 + n1; i += (size_t)gridDim.x * 256) {
+        if (i < n0) a[i] = 0u; else b[i - n0] = 0u;
+    }
+}
+
+// Zeroes the state that launches expect to find at zero: the first `counters` ticket counters and the top-k
+// state of the first `topk_rows` rows of the fixed part.
+hipError_t clear_counters(char *workspace, size_t counters, size_t topk_rows, hipStream_t stream) {
+    const size_t n1 = topk_rows * (sizeof(TopkRow) / 4);
+    const int blocks = (int)std::min<size_t>(512, (counters + n1 + 255) / 256);
     hipLaunchKernelGGL(clear_words_kernel, dim3(blocks), dim3(256), 0, stream, reinterpret_cast<uint32_t *>(workspace),
-                       counters);
+                       counters, reinterpret_cast<uint32_t *>(workspace + kCountersBytes), n1);
     return hipGetLastError();
 }
 
@@ -125,8 +151,11 @@ Workspace workspace_layout(const td_shape *s, int32_t k) {
     const int32_t rows = s->batch * selection_rows(s);
     w.score_stride = (int64_t)align_up((size_t)s->max_seq_len, 4);
     w.counters = 0;
-    w.topk = kCountersBytes;
-    w.part_acc = align_up(w.topk + (k > 0 ? topk_scratch_bytes(rows, s->max_seq_len) : 0), 256);
+    w.fused = kCountersBytes;
+    const TopkPlace tp = topk_place(rows);
+    w.topk_state = tp.state;
+    w.topk = k > 0 ? tp.scratch : kFixedBytes;
+    w.part_acc = align_up(w.topk + (k > 0 ? topk_scratch_bytes(rows, s->max_seq_len, k) : 0), 256);
     w.part_ml = align_up(w.part_acc + heads * kSplitsMax * s->head_dim * sizeof(float), 256);
     w.scores = align_up(w.part_ml + heads * kSplitsMax * 2 * sizeof(float), 256);
     const size_t score_bytes = k > 0 ? (size_t)rows * w.score_stride * sizeof(float) : 0;
@@ -223,7 +252,7 @@ LaunchPlan plan_launch(const td_ctx *ctx, const td_shape *s, int mode, int32_t k
 td_status attend(td_ctx *ctx, const td_shape *s, int mode, const void *q, const void *K, const void *V,
                  const int32_t *positions, int32_t k, float *scores, int64_t score_stride, void *out,
                  hipStream_t stream, const void *k_new = nullptr, const void *v_new = nullptr,
-                 int32_t score_rule = -1, float *ml_out = nullptr) {
+                 int32_t score_rule = -1, float *ml_out = nullptr, TopkRow *fused_rows = nullptr) {
     const Workspace w = workspace_layout(s, mode == kDense ? 0 : k);
     AttendParams p;
     memset(&p, 0, sizeof p);
@@ -236,7 +265,7 @@ td_status attend(td_ctx *ctx, const td_shape *s, int mode, const void *q, const 
     p.part_acc = reinterpret_cast<float *>(ctx->workspace + w.part_acc);
     p.part_ml = reinterpret_cast<float *>(ctx->workspace + w.part_ml);
     p.counters = reinterpret_cast<int32_t *>(ctx->workspace + w.counters);
-    p.topk_scratch = ctx->workspace + w.topk;
+    p.topk_rows = fused_rows;
     p.stride_batch = s->kv_stride_batch;
     if (s->page_size > 0) {
         p.block_table = s->block_table;
@@ -267,7 +296,7 @@ td_status attend(td_ctx *ctx, const td_shape *s, int mode, const void *q, const 
     const int group = plan.group, waves = plan.waves;
     const bool mfma = plan.matrix_core;
     if (ctx->counters_dirty) {  // an earlier launch on this context failed: start from zeroed tickets
-        const hipError_t ce = clear_counters(ctx->workspace, kCountersMax, stream);
+        const hipError_t ce = clear_counters(ctx->workspace, kCountersMax, kTopkFusedRows, stream);
         if (ce != hipSuccess) return fail(ctx, TD_ERR_HIP, "clearing the ticket counters failed: %s", hipGetErrorString(ce));
         ctx->counters_dirty = false;
     }
@@ -322,16 +351,32 @@ td_status select_tokens(td_ctx *ctx, const td_shape *s, const void *q, const voi
         if (pe != hipSuccess) return fail(ctx, TD_ERR_HIP, "mean-probability launch failed: %s", hipGetErrorString(pe));
         scores = rank;
         stride_for_topk = w.score_stride;
-    } else {
-        st = attend(ctx, s, kSelect, q, K, V, nullptr, k, scores, stride, out, stream, k_new, v_new);
+    }
+    // The group rules leave one score row per KV head, staged in LDS by the attention launch, which then also
+    // bins them for the top-k launch; that needs top-k state at a place that is zero between launches, the
+    // fixed part of the workspace.
+    const int32_t rows = selection_rows(s), all_rows = s->batch * rows;
+    const TopkPlace tp = topk_place(all_rows);
+    TopkRow *state = reinterpret_cast<TopkRow *>(ctx->workspace + tp.state);
+    // (With many short chunks per row - a ragged batch - the chunks' histogram updates trickle into memory
+    // between the streaming reads all through the launch and cost more than the histogram launch they
+    // replace: 553 vs 483 us for the attention launch of 16 ragged sequences with 63 chunks each.)
+    const bool fused = tp.fixed && (s->selection == TD_SELECT_GROUP_SUM || s->selection == TD_SELECT_GROUP_MAX) &&
+                       plan_launch(ctx, s, kSelect, k).splits <= kFusedHistMaxSplits;
+    if (s->selection != TD_SELECT_GROUP_MEAN_PROB) {
+        st = attend(ctx, s, kSelect, q, K, V, nullptr, k, scores, stride, out, stream, k_new, v_new, -1, nullptr,
+                    fused ? state : nullptr);
         if (st != TD_OK) return st;
     }
-    // the selection kernel clears the top-k state of its KV head's row on the way; with one row
-    // per query head the state is cleared by top-k's own reset instead
-    const int32_t rows = selection_rows(s);
-    const hipError_t e = launch_topk(scores, stride_for_topk, s->batch * rows, s->seq_lens, rows, s->max_seq_len, k, positions,
-                                     ctx->workspace + w.topk, s->selection == TD_SELECT_PER_HEAD, stream);
-    if (e != hipSuccess) return fail(ctx, TD_ERR_HIP, "top-k launch failed: %s", hipGetErrorString(e));
+    hipError_t e = hipSuccess;
+    if (!tp.fixed) e = launch_topk_reset(state, all_rows, stream);
+    if (e == hipSuccess)
+        e = launch_topk(scores, stride_for_topk, all_rows, s->seq_lens, rows, s->max_seq_len, k, positions, state,
+                        ctx->workspace + w.topk, fused, stream);
+    if (e != hipSuccess) {
+        ctx->counters_dirty = true;
+        return fail(ctx, TD_ERR_HIP, "top-k launch failed: %s", hipGetErrorString(e));
+    }
     return TD_OK;
 }
 
@@ -400,7 +445,7 @@ size_t td_workspace_bytes(const td_shape *shape, int32_t k) {
 
 size_t td_topk_workspace_bytes(int32_t rows, int32_t max_len) {
     if (rows < 1 || max_len < 1) return 0;
-    return align_up(kCountersBytes + topk_scratch_bytes(rows, max_len), 256);
+    return align_up(topk_place(rows).scratch + topk_scratch_bytes(rows, max_len, max_len), 256);
 }
 
 td_status td_create(td_ctx **out, int device, size_t workspace_bytes) {
@@ -505,7 +550,7 @@ size_t td_prefill_workspace_bytes(const td_shape *shape, int32_t num_new) {
     td_status code;
     if (shape_problem(shape, 0, &code) || num_new < 1 || num_new > shape->max_seq_len) return 0;
     const PrefillPlan pl = prefill_plan_for(shape, num_new, ~(size_t)0);
-    return pl.chunks > 1 ? align_up(kCountersBytes + 256 + pl.part_bytes, 256) : 0;
+    return pl.chunks > 1 ? align_up(kFixedBytes + 256 + pl.part_bytes, 256) : 0;
 }
 
 td_status td_prefill_attend(td_ctx *ctx, const td_shape *shape, int32_t num_new, const void *q, const void *K,
@@ -538,15 +583,15 @@ td_status td_prefill_attend(td_ctx *ctx, const td_shape *shape, int32_t num_new,
         while ((1 << p.page_shift) < shape->page_size) ++p.page_shift;
     }
     // token chunks as far as the workspace holds their partial states
-    const size_t avail = ctx->workspace_bytes > kCountersBytes ? ctx->workspace_bytes - kCountersBytes : 0;
+    const size_t avail = ctx->workspace_bytes > kFixedBytes ? ctx->workspace_bytes - kFixedBytes : 0;
     const PrefillPlan pl = prefill_plan_for(shape, num_new, avail);
     p.rows_per_wg = pl.rows_per_wg;
     p.row_blocks = pl.row_blocks;
     p.chunk = pl.chunk;
     p.chunks = pl.chunks;
     if (pl.chunks > 1) {
-        p.part_ml = reinterpret_cast<float *>(ctx->workspace + kCountersBytes);
-        p.part_acc = reinterpret_cast<float *>(ctx->workspace + kCountersBytes + prefill_ml_bytes(pl, shape));
+        p.part_ml = reinterpret_cast<float *>(ctx->workspace + kFixedBytes);
+        p.part_acc = reinterpret_cast<float *>(ctx->workspace + kFixedBytes + prefill_ml_bytes(pl, shape));
     }
     const hipError_t e = launch_prefill(shape->num_q_heads / shape->num_kv_heads, p, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return fail(ctx, TD_ERR_HIP, "prefill launch failed: %s", hipGetErrorString(e));
@@ -569,11 +614,24 @@ td_status td_topk(td_ctx *ctx, const float *scores, int64_t row_stride, int32_t 
         return fail(ctx, TD_ERR_INVALID_ARG, "%s", "rows, rows_per_len, max_len, k must be >= 1 and row_stride >= max_len");
     if (misaligned(scores)) return fail(ctx, TD_ERR_INVALID_ARG, "%s", "scores must be 16-byte aligned");
     if (rows > 65535) return fail(ctx, TD_ERR_UNSUPPORTED, "%s", "more than 65535 rows");
-    if (kCountersBytes + topk_scratch_bytes(rows, max_len) > ctx->workspace_bytes)
+    const TopkPlace tp = topk_place(rows);
+    if (tp.scratch + topk_scratch_bytes(rows, max_len, k) > ctx->workspace_bytes)
         return fail(ctx, TD_ERR_WORKSPACE, "%s", "workspace is smaller than td_topk_workspace_bytes(rows, max_len)");
-    const hipError_t e = launch_topk(scores, row_stride, rows, row_lens, rows_per_len, max_len, k, positions,
-                                     ctx->workspace + kCountersBytes, true, static_cast<hipStream_t>(hip_stream));
-    if (e != hipSuccess) return fail(ctx, TD_ERR_HIP, "top-k launch failed: %s", hipGetErrorString(e));
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    TopkRow *state = reinterpret_cast<TopkRow *>(ctx->workspace + tp.state);
+    hipError_t e = hipSuccess;
+    if (ctx->counters_dirty) {
+        e = clear_counters(ctx->workspace, kCountersMax, kTopkFusedRows, stream);
+        if (e == hipSuccess) ctx->counters_dirty = false;
+    }
+    if (e == hipSuccess && !tp.fixed) e = launch_topk_reset(state, rows, stream);
+    if (e == hipSuccess)
+        e = launch_topk(scores, row_stride, rows, row_lens, rows_per_len, max_len, k, positions, state,
+                        ctx->workspace + tp.scratch, false, stream);
+    if (e != hipSuccess) {
+        ctx->counters_dirty = true;
+        return fail(ctx, TD_ERR_HIP, "top-k launch failed: %s", hipGetErrorString(e));
+    }
     return TD_OK;
 }
 
@@ -637,7 +695,8 @@ td_status tidal::decode_step_on_workspace(char *workspace, size_t workspace_byte
     } else {
         const size_t rows = (size_t)shape->batch * std::max(shape->num_kv_heads, selection_rows(shape));
         const hipError_t e = workspace_layout(shape, k).total <= workspace_bytes
-                                 ? clear_counters(workspace, rows, static_cast<hipStream_t>(hip_stream))
+                                 ? clear_counters(workspace, rows, std::min<size_t>(rows, kTopkFusedRows),
+                                                  static_cast<hipStream_t>(hip_stream))
                                  : hipSuccess;  // too small: decode_step says so before anything is enqueued
         st = e != hipSuccess ? fail(&local, TD_ERR_HIP, "clearing the ticket counters failed: %s", hipGetErrorString(e))
                              : decode_step(&local, shape, num_layers, schedule, q_layers, nullptr, nullptr, K_layers,
@@ -651,11 +710,11 @@ extern "C" {
 
 td_status td_reset(td_ctx *ctx, void *hip_stream) {
     if (!ctx) return TD_ERR_INVALID_ARG;
-    if (!ctx->workspace || ctx->workspace_bytes < kCountersBytes) {
+    if (!ctx->workspace || ctx->workspace_bytes < kFixedBytes) {
         ctx->counters_dirty = false;  // no attention call fits this workspace, nothing to clear
         return TD_OK;
     }
-    const hipError_t e = clear_counters(ctx->workspace, kCountersMax, static_cast<hipStream_t>(hip_stream));
+    const hipError_t e = clear_counters(ctx->workspace, kCountersMax, kTopkFusedRows, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return fail(ctx, TD_ERR_HIP, "clearing the ticket counters failed: %s", hipGetErrorString(e));
     ctx->counters_dirty = false;
     return TD_OK;

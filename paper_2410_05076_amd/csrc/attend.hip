@@ -99,11 +99,6 @@ void attend_split_kernel(const AttendParams p) {
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
     const int r = lane / LPR, c = lane % LPR;
 
-    if constexpr (MODE == kSelect) {  // leave the row's top-k state clear for the kernels that follow
-        TopkRow *row = static_cast<TopkRow *>(p.topk_scratch) + (b * p.num_kv_heads + g);
-        for (int i = split * T + threadIdx.x; i < kTopkBins; i += p.num_splits * T) row->hist[i] = 0;
-        if (split == 0 && threadIdx.x == 0) row->ncand = 0;
-    }
     // A workgroup owns p.chunk consecutive tokens (a multiple of the 128-token granule): a
     // contiguous stream per workgroup keeps TLB and DRAM-page locality.
     constexpr int TILE = W * STEP;
@@ -224,10 +219,18 @@ void attend_split_kernel(const AttendParams p) {
     constexpr int RG = W * TPW;          // row groups per workgroup
     constexpr int GC = G < 4 ? G : 4;    // heads per pass of the tail
     using Tail = TailShared<D, GC, RG, T>;
+    // While they sit there they are also binned for the top-k launch that follows (p.topk_rows);
+    // the histogram lies behind the stage.
     constexpr size_t kStageBytes = MODE == kSelect ? W * kScoreStagePerWave * sizeof(float) : 0;
-    __shared__ __align__(16) char lds_tail[sizeof(Tail) > kStageBytes ? sizeof(Tail) : kStageBytes];
+    constexpr size_t kHistBytes = MODE == kSelect ? kTopkBins * sizeof(uint32_t) : 0;
+    __shared__ __align__(16) char lds_tail[sizeof(Tail) > kStageBytes + kHistBytes ? sizeof(Tail) : kStageBytes + kHistBytes];
     float *s_scores = reinterpret_cast<float *>(lds_tail);
+    uint32_t *s_hist = reinterpret_cast<uint32_t *>(lds_tail + kStageBytes);
     const bool per_head = MODE == kSelect && p.select_rule == TD_SELECT_PER_HEAD;
+    if constexpr (MODE == kSelect) {
+        if (p.topk_rows)
+            for (int i = threadIdx.x; i < kTopkBins; i += T) s_hist[i] = 0;  // ordered before its use by the barrier in write_staged_scores
+    }
 
     for (int base = t0 + wave * STEP; base < t1; base += TILE) {
         uint4 kraw[kUnroll], vraw[kUnroll];
@@ -334,6 +337,7 @@ void attend_split_kernel(const AttendParams p) {
     if constexpr (MODE == kSelect) {
         if (!per_head) {
             write_staged_scores<T>(s_scores, t1 - t0, p.scores + ((int64_t)b * p.num_kv_heads + g) * p.score_stride + t0);
+            if (p.topk_rows) add_score_histogram<T>(p.topk_rows + (b * p.num_kv_heads + g), s_scores, t1 - t0, s_hist, split == 0);
             __syncthreads();  // the stage has been read; its LDS now takes the states
         }
     }

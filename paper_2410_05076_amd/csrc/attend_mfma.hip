@@ -45,11 +45,6 @@ void attend_mfma_kernel(const AttendParams p) {
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
     const int n16 = lane & 15, kb = lane >> 4;
 
-    if constexpr (MODE == kSelect) {  // leave the row's top-k state clear for the kernels that follow
-        TopkRow *row = static_cast<TopkRow *>(p.topk_scratch) + (b * p.num_kv_heads + g);
-        for (int i = split * T + threadIdx.x; i < kTopkBins; i += p.num_splits * T) row->hist[i] = 0;
-        if (split == 0 && threadIdx.x == 0) row->ncand = 0;
-    }
     const int t0 = split * p.chunk;
 
     // Loads that depend on the launch arguments only, issued ahead of the read of the sequence
@@ -183,8 +178,21 @@ void attend_mfma_kernel(const AttendParams p) {
     // them with one contiguous burst after the loop: writes that trickle out between the
     // streaming reads make HBM switch direction and row all the time (34 us per 16 MiB of
     // scores, measured).  The launch plan keeps such chunks within W * kScoreStagePerWave tokens.
-    __shared__ float s_scores[MODE == kSelect ? W * kScoreStagePerWave : 1];
+    // While they sit there they are also binned for the top-k launch that follows (p.topk_rows).
+    // Stage and histogram share their LDS with the tail's state buffers, which are used only
+    // after both have been read.
+    constexpr int RG = W;
+    using Tail = TailShared<kD, G, RG, T>;
+    constexpr size_t kStageBytes = MODE == kSelect ? W * kScoreStagePerWave * sizeof(float) : 0;
+    constexpr size_t kHistBytes = MODE == kSelect ? kTopkBins * sizeof(uint32_t) : 0;
+    __shared__ __align__(16) char lds_tail[sizeof(Tail) > kStageBytes + kHistBytes ? sizeof(Tail) : kStageBytes + kHistBytes];
+    float *s_scores = reinterpret_cast<float *>(lds_tail);
+    uint32_t *s_hist = reinterpret_cast<uint32_t *>(lds_tail + kStageBytes);
     const bool per_head = MODE == kSelect && p.select_rule == TD_SELECT_PER_HEAD;
+    if constexpr (MODE == kSelect) {
+        if (p.topk_rows)
+            for (int i = threadIdx.x; i < kTopkBins; i += T) s_hist[i] = 0;  // ordered before its use by the barrier in write_staged_scores
+    }
 
     for (int base = t0 + wave * STEP; base < t1; base += W * STEP) {
         uint4 kraw[kTiles][4], vraw[kTiles][4];
@@ -306,13 +314,16 @@ void attend_mfma_kernel(const AttendParams p) {
     }
 
     if constexpr (MODE == kSelect) {
-        if (!per_head) write_staged_scores<T>(s_scores, t1 - t0, score_row + t0);
+        if (!per_head) {
+            write_staged_scores<T>(s_scores, t1 - t0, score_row + t0);
+            if (p.topk_rows) add_score_histogram<T>(p.topk_rows + (b * p.num_kv_heads + g), s_scores, t1 - t0, s_hist, split == 0);
+            __syncthreads();  // stage and histogram have been read; their LDS now takes the states
+        }
     }
 
     // ---- one state per wave into LDS, then the common tail
     l_run = cross_rows_sum(l_run);
-    constexpr int RG = W;
-    __shared__ TailShared<kD, G, RG, T> sm;
+    Tail &sm = *reinterpret_cast<Tail *>(lds_tail);
     if (kb == 0 && n16 < G) {
         sm.m[wave][n16] = m_run;
         sm.l[wave][n16] = l_run;

@@ -3,6 +3,7 @@
 // taking a ticket, and (in the chunk that finishes last) merging all partials of the
 // (sequence, KV head) and writing the output row.
 #pragma once
+#include "coherent.h"
 #include "common.h"
 
 namespace tidal {
@@ -17,7 +18,6 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // 16-byte load of cache data that is read exactly once: the non-temporal hint keeps the
 // stream from displacing other lines (a plain 2 GiB streaming read measures ~6.3 TB/s with
 // ordinary loads and ~7.2 TB/s with this hint on MI355X).
-typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ uint4 stream_load16(const void *p) {
     const u32x4_t v = __builtin_nontemporal_load(static_cast<const u32x4_t *>(p));
     return make_uint4(v.x, v.y, v.z, v.w);
@@ -37,30 +37,6 @@ __device__ __forceinline__ void store_out(void *out, int64_t i, float v) {
         static_cast<float *>(out)[i] = v;
 }
 
-// Device-scope store that goes through to memory instead of staying in this XCD's L2, and
-// the matching load that does not trust this XCD's caches.
-__device__ __forceinline__ void publish(float *p, float v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ uint64_t coherent_load(const uint64_t *p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-// Device-scope 16- and 8-byte loads for the final merge, as buffer loads: the compiler has
-// no atomic load of 16 bytes, and a buffer load takes the scope as a cache-policy operand
-// (bit 4 = sc1 on gfx94x/gfx950) while staying an ordinary tracked load.  The resource
-// covers exactly the partials of one (sequence, KV head); its base is wave-uniform.
-typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
-constexpr int kCachePolicySc1 = 16;
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t partial_resource(const float *base, uint32_t bytes) {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(base), 0, bytes, 0x00020000);
-}
-__device__ __forceinline__ u32x4_t coherent_load16(__amdgpu_buffer_rsrc_t r, uint32_t byte_offset) {
-    return __builtin_amdgcn_raw_buffer_load_b128(r, byte_offset, 0, kCachePolicySc1);
-}
-__device__ __forceinline__ u32x2_t coherent_load8(__amdgpu_buffer_rsrc_t r, uint32_t byte_offset) {
-    return __builtin_amdgcn_raw_buffer_load_b64(r, byte_offset, 0, kCachePolicySc1);
-}
-
 // Writes the n scores that the workgroup's waves have put into LDS to dst, 16 bytes per lane
 // where dst allows it.  Every thread of the workgroup calls it.
 template <int T>
@@ -73,6 +49,26 @@ __device__ __forceinline__ void write_staged_scores(const float *staged, int n, 
         for (int i = n4 + threadIdx.x; i < n; i += T) dst[i] = staged[i];
     } else {
         for (int i = threadIdx.x; i < n; i += T) dst[i] = staged[i];
+    }
+}
+
+// Fused histogram of a selection layer: bins the n group scores that the workgroup has staged in
+// LDS (after write_staged_scores, whose barrier has passed) with the top-k launch's bin map centred
+// on zero, and adds the non-empty bins to the row's histogram.  hist: kTopkBins zeroed LDS words.
+// The row's histogram is zero when the launch starts (the top-k launch leaves it so).
+template <int T>
+__device__ __forceinline__ void add_score_histogram(TopkRow *row, const float *staged, int n, uint32_t *hist,
+                                                    bool first_chunk) {
+    for (int i = threadIdx.x; i < n; i += T) atomicAdd(&hist[topk_bin(staged[i], 0.f, 1.f)], 1u);
+    __syncthreads();
+    for (int i = threadIdx.x; i < kTopkBins; i += T) {
+        const uint32_t c = hist[i];
+        if (c) atomicAdd(&row->hist[i], c);
+    }
+    if (first_chunk && threadIdx.x == 0) {
+        row->center = 0.f;
+        row->inv = 1.f;
+        row->ncand = 0;  // the candidate list of the launches that follow starts empty
     }
 }
 
@@ -155,9 +151,9 @@ __device__ __forceinline__ void merge_partials(const AttendParams &p, MergeShare
     const int hi = col / (D / 4), c4 = col % (D / 4);
     const int64_t head = head0 + hi;
     const __amdgpu_buffer_rsrc_t pa =  // the heads' partials, [GH][num_splits][D]
-        partial_resource(p.part_acc + head0 * p.num_splits * D, (uint32_t)(GH * p.num_splits * D) * 4);
+        coherent_window(p.part_acc + head0 * p.num_splits * D, (uint32_t)(GH * p.num_splits * D) * 4);
     const __amdgpu_buffer_rsrc_t pml =  // and their (max, sum) pairs, [GH][num_splits][2]
-        partial_resource(p.part_ml + head0 * p.num_splits * 2, (uint32_t)(GH * p.num_splits) * 8);
+        coherent_window(p.part_ml + head0 * p.num_splits * 2, (uint32_t)(GH * p.num_splits) * 8);
     const uint32_t pa_off = ((uint32_t)(hi * p.num_splits) * D + c4 * 4) * 4;
     const uint32_t pml_off = (uint32_t)(hi * p.num_splits) * 8;
     constexpr int kPolicy = COHERENT ? kCachePolicySc1 : 0;
@@ -231,7 +227,7 @@ __device__ __forceinline__ void merge_partials(const AttendParams &p, MergeShare
 template <int DT, int D, int G, int GC, int RG, int T>
 __device__ __forceinline__ void finish_chunks(const AttendParams &p, TailShared<D, GC, RG, T> &sm, int b, int g,
                                               int ns) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    wait_for_stores();
     __syncthreads();
     if (threadIdx.x == 0) {
         int *counter = p.counters + b * p.num_kv_heads + g;

@@ -4,6 +4,7 @@
 #include <stdint.h>
 
 #include "tidal.h"
+#include "topk_math.h"
 
 namespace tidal {
 
@@ -16,22 +17,25 @@ constexpr int kSparseChunkMax = 2048;  // positions of one chunk are staged in L
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr int kCountersMax = 65536;    // ticket counters, one per (sequence, KV head)
-constexpr int kTopkBins = 2048;        // linear histogram bins per row
-constexpr int kTopkCandMax = 4096;     // scores of the k-th bin kept per row
-constexpr int kTopkSliceScores = 4096; // scores per top-k workgroup
-
-// Per-row state of the top-k kernels (global memory).
+// Per-row state of the top-k kernels.  `hist` must be zero when a selection launch sequence starts
+// and the last top-k launch leaves it at zero again (like the ticket counters).  A selection
+// layer's attention launch adds its chunks' score histograms to it (fused mode); this is only
+// possible for state at a place that no other shape's launch ever writes, so the fused rows live
+// in a fixed region right after the ticket counters, kTopkFusedRows of them; launches with more
+// rows reset their state and run the histogram as a kernel.
 struct TopkRow {
-    uint32_t hist[kTopkBins];  // zero when the histogram kernel starts
-    uint32_t ncand;            // zero when the pick kernel starts
-    uint32_t remaining;        // rank of the k-th largest inside its bin
+    uint32_t hist[kTopkBins];
+    uint32_t ncand;      // scores of the k-th bin appended to the candidate list (zeroed by whoever builds the histogram)
+    uint32_t remaining;  // rank of the k-th largest inside its bin
     int32_t kth_bin;
-    float lo, inv;             // bin(x) = clamp((x - lo) * inv)
+    float center, inv;   // bin(x) = topk_bin(x, center, inv)
     uint32_t pad[3];
 };
+static_assert(sizeof(TopkRow) % 16 == 0, "rows of state stay 16-byte aligned");
+constexpr int kTopkFusedRows = 256;
 
-inline int topk_slices(int32_t max_len) { return (int)(((int64_t)max_len + 3 + kTopkSliceScores - 1) / kTopkSliceScores); }
-size_t topk_scratch_bytes(int32_t rows, int32_t max_len);
+// Global scratch of the top-k launch for `rows` rows of at most max_len scores and budget k.
+size_t topk_scratch_bytes(int32_t rows, int32_t max_len, int32_t k);
 
 enum AttendMode { kDense = 0, kSelect = 1, kSparse = 2 };
 
@@ -44,7 +48,7 @@ struct AttendParams {
     float *part_acc;           // [B][Hq][num_splits][D]
     float *part_ml;            // [B][Hq][num_splits][2]  (running max in log2 units, sum)
     int32_t *counters;         // [B][Hkv] chunks finished so far; zero between launches
-    void *topk_scratch;        // select: TopkRow [B][Hkv], histogram and candidate count cleared here
+    TopkRow *topk_rows;        // select, fused histogram: TopkRow [B][Hkv] that receives the chunks' histograms, else nullptr
     void *out;                 // [B][Hq][D]
     float *ml_out;             // optional [B][Hq][2]: final softmax maximum (log2 units) and sum per head
     int64_t stride_batch, stride_head, stride_tok;  // elements; paged: stride_batch is the page stride
@@ -118,11 +122,15 @@ hipError_t launch_mean_prob(const float *head_logits, int64_t logit_stride, cons
                             int32_t batch, int32_t num_kv_heads, int32_t group, int32_t max_seq_len, float *rank,
                             int64_t rank_stride, float *prob, int64_t prob_stride, hipStream_t stream);
 
-// argTopK over rows of fp32 scores.  scratch: topk_scratch_bytes(rows, max_len) bytes; reset
-// clears the per-row state first (not needed right after a selection attention launch).
+// argTopK over rows of fp32 scores.  state: TopkRow[rows], zero on entry and on exit; scratch:
+// topk_scratch_bytes(rows, max_len, k) bytes.  have_histogram: a selection attention launch has
+// already added every score to state[row].hist and set its bin map (one launch follows);
+// otherwise the histogram is built here (two launches).
 hipError_t launch_topk(const float *scores, int64_t row_stride, int32_t rows, const int32_t *row_lens,
-                       int32_t rows_per_len, int32_t max_len, int32_t k, int32_t *positions, void *scratch,
-                       bool reset, hipStream_t stream);
+                       int32_t rows_per_len, int32_t max_len, int32_t k, int32_t *positions, TopkRow *state,
+                       void *scratch, bool have_histogram, hipStream_t stream);
+// Zeroes TopkRow[rows] (state outside the fixed region, before a launch_topk without histogram).
+hipError_t launch_topk_reset(TopkRow *state, int32_t rows, hipStream_t stream);
 
 // The layer loop of td_decode_step on a workspace that the caller names (default launch plan).  The
 // ticket counters the shape uses are zeroed first; `error` receives the text of a failure.

@@ -2,14 +2,16 @@
 // then an order-preserving compaction, so positions come out in ascending token order and
 // ties at the k-th value go to the smaller index.
 //
-// A row (up to 128K scores per KV head, few rows) is cut into slices of 4096 scores, one
-// workgroup of 256 threads each, so that a handful of rows still fills the chip.  Slices of
-// a row meet through global memory at kernel boundaries (three short kernels):
-//   hist  256 samples of the row give a value range [lo, hi]; every score is binned by the
-//         monotone map bin(x) = clamp(floor((x - lo) * 2048 / (hi - lo))).  Linear bins spread
-//         the counts (the top bits of a float key would pile most scores into a handful of
-//         bins).  Each slice builds its histogram in LDS and adds the non-empty bins to the
-//         row's histogram.
+// A row (up to 128K scores and more per KV head, few rows) is cut into slices of 4096 scores,
+// one workgroup of 256 threads each, so that a handful of rows still fills the chip.  Slices of
+// a row meet through global memory at kernel boundaries:
+//   hist  every score is binned by the monotone map topk_bin (64 bins per octave around a
+//         centre; bins of constant relative width resolve the upper tail, where the k-th largest
+//         lives).  A selection layer's attention launch does this itself while the chunk's scores
+//         sit in LDS (map centred on zero), so that two launches follow it; rows that come from
+//         elsewhere are binned by topk_hist_kernel, which centres and scales the map on 256
+//         samples of the row.  Each slice builds its histogram in LDS and adds the non-empty bins
+//         to the row's histogram.
 //   pick  every slice scans the row histogram from the top for the bin b* holding the k-th
 //         largest score, counts its own scores above b* and appends its scores inside b*
 //         (a few dozen per row for smooth distributions) to the row's candidate list.
@@ -19,30 +21,20 @@
 //         consecutive scores, one prefix sum over the workgroup orders the slice).
 // If a row has more candidates than the list holds (many equal scores), emit falls back to
 // an exact radix select over the row's scores inside b*: slow, but never wrong.
-// The row histogram and candidate count must be zero when hist starts: the selection
-// attention kernel clears them on its way, a stand-alone call runs a reset kernel first.
+// The row histogram is zero when a launch sequence starts and emit leaves it zero again (state
+// of up to kTopkFusedRows rows lives where no other launch writes, so this holds across calls of
+// different shapes; larger launches reset their state first).
 #include "common.h"
 
 namespace tidal {
 namespace {
 
-constexpr int kTopkThreads = 256;
 constexpr int kTopkWaves = kTopkThreads / kWave;
-constexpr int kPerThread = 4;                              // 16-byte granules per thread
+constexpr int kPerThread = kTopkPerThread / 4;             // 16-byte granules per thread
 constexpr int kSliceGranules = kTopkThreads * kPerThread;  // 1024 granules = 4096 scores
 constexpr int kBins = kTopkBins;
 constexpr int kCandMax = kTopkCandMax;
 static_assert(kSliceGranules * 4 == kTopkSliceScores, "slice size");
-
-__device__ __forceinline__ uint32_t order_key(float f) {
-    uint32_t u = __float_as_uint(f);
-    if (u == 0x80000000u) u = 0;  // -0 and +0 compare equal
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
-__device__ __forceinline__ int linear_bin(float x, float lo, float inv) {
-    return (int)fminf(fmaxf((x - lo) * inv, 0.f), (float)(kBins - 1));
-}
 
 __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v, int lane) {
 #pragma unroll
@@ -89,16 +81,16 @@ struct Slice {
 };
 
 __device__ __forceinline__ Slice open_slice(const float *scores, int64_t row_stride, const int32_t *row_lens,
-                                            int rows_per_len, int max_len, int k, void *scratch) {
+                                            int rows_per_len, int max_len, int k, TopkRow *states) {
     Slice s;
     const int row = blockIdx.y;
     s.n = min(max(row_lens[row / rows_per_len], 0), max_len);
     s.src = scores + (int64_t)row * row_stride;
     s.mis = (int)((reinterpret_cast<uintptr_t>(s.src) >> 2) & 3);
     s.src4 = reinterpret_cast<const float4 *>(s.src - s.mis);
-    s.n4 = (s.mis + s.n + 3) >> 2;
+    s.n4 = topk_row_granules(s.mis, s.n);
     s.first = blockIdx.x * kSliceGranules;
-    s.state = static_cast<TopkRow *>(scratch) + row;
+    s.state = states + row;
     s.active = k < s.n && s.first < s.n4;  // k >= n needs no selection at all
     return s;
 }
@@ -131,20 +123,19 @@ __device__ __forceinline__ void for_each_score(const Slice &s, int tid, const fl
     }
 }
 
-__global__ __launch_bounds__(kTopkThreads) void topk_reset_kernel(void *scratch) {
-    TopkRow *state = static_cast<TopkRow *>(scratch) + blockIdx.x;
-    for (int i = threadIdx.x; i < kBins; i += kTopkThreads) state->hist[i] = 0;
-    if (threadIdx.x == 0) state->ncand = 0;
+__global__ __launch_bounds__(kTopkThreads) void topk_reset_kernel(TopkRow *states) {
+    uint32_t *words = reinterpret_cast<uint32_t *>(states + blockIdx.x);
+    for (int i = threadIdx.x; i < (int)(sizeof(TopkRow) / 4); i += kTopkThreads) words[i] = 0;
 }
 
 __global__ __launch_bounds__(kTopkThreads) void topk_hist_kernel(const float *scores, int64_t row_stride,
                                                                 const int32_t *row_lens, int rows_per_len,
-                                                                int max_len, int k, void *scratch) {
+                                                                int max_len, int k, TopkRow *states) {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
     float4 v[kPerThread];
     load_slice_early(scores, row_stride, max_len, tid, v);
     asm volatile("" ::: "memory");  // requested before the row's length is read
-    const Slice s = open_slice(scores, row_stride, row_lens, rows_per_len, max_len, k, scratch);
+    const Slice s = open_slice(scores, row_stride, row_lens, rows_per_len, max_len, k, states);
     if (!s.active) return;
     __shared__ uint32_t s_hist[kBins];
     __shared__ float s_lo[kTopkWaves], s_hi[kTopkWaves];
@@ -167,16 +158,20 @@ __global__ __launch_bounds__(kTopkThreads) void topk_hist_kernel(const float *sc
         lo = fminf(lo, s_lo[w]);
         hi = fmaxf(hi, s_hi[w]);
     }
-    // The k largest live in the upper tail, which 256 samples do not reach (their maximum is
-    // about the row's 99.6th percentile): the binned range extends above the sampled maximum
-    // by the sampled width, so that the tail is resolved instead of piling up in the last bin.
-    hi += hi - lo;
-    const float inv = hi > lo ? (float)kBins / (hi - lo) : 0.f;
+    // The map is centred on the middle of the sampled range and scaled so that one sampled width is
+    // 64 units: its 2^-8 .. 2^8 span then covers four sampled widths either side of the centre, at a
+    // resolution far below the width.  A degenerate range puts every score into one bin and
+    // leaves the decision to the exact paths.
+    const float width = hi - lo;
+    const bool usable = width > 0.f && width < 3.0e38f;
+    const float center = usable ? 0.5f * lo + 0.5f * hi : 0.f;
+    const float inv = usable ? 64.f / width : 0.f;
     if (blockIdx.x == 0 && tid == 0) {
-        s.state->lo = lo;
+        s.state->center = center;
         s.state->inv = inv;
+        s.state->ncand = 0;
     }
-    for_each_score(s, tid, v, [&](float f, int) { atomicAdd(&s_hist[linear_bin(f, lo, inv)], 1u); });
+    for_each_score(s, tid, v, [&](float f, int) { atomicAdd(&s_hist[topk_bin(f, center, inv)], 1u); });
     __syncthreads();
     for (int i = tid; i < kBins; i += kTopkThreads) {
         const uint32_t c = s_hist[i];
@@ -186,7 +181,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_hist_kernel(const float *sc
 
 __global__ __launch_bounds__(kTopkThreads) void topk_pick_kernel(const float *scores, int64_t row_stride,
                                                                 const int32_t *row_lens, int rows_per_len,
-                                                                int max_len, int k, void *scratch, uint32_t *cand_key,
+                                                                int max_len, int k, TopkRow *states, uint32_t *cand_key,
                                                                 int32_t *cand_idx, uint32_t *slice_above,
                                                                 int slices_per_row) {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
@@ -195,13 +190,13 @@ __global__ __launch_bounds__(kTopkThreads) void topk_pick_kernel(const float *sc
     load_slice_early(scores, row_stride, max_len, tid, v);
     // bin of the k-th largest: thread t owns bins 2047-8t .. 2040-8t, the scan walks downwards
     constexpr int PER = kBins / kTopkThreads;
-    const TopkRow *early = static_cast<const TopkRow *>(scratch) + blockIdx.y;
+    const TopkRow *early = states + blockIdx.y;
     uint32_t cnt[PER], mine = 0;
 #pragma unroll
     for (int e = 0; e < PER; ++e) cnt[e] = early->hist[kBins - 1 - PER * tid - e];
-    const float lo = early->lo, inv = early->inv;
+    const float lo = early->center, inv = early->inv;  // the bin map's centre and scale
     asm volatile("" ::: "memory");
-    const Slice s = open_slice(scores, row_stride, row_lens, rows_per_len, max_len, k, scratch);
+    const Slice s = open_slice(scores, row_stride, row_lens, rows_per_len, max_len, k, states);
     if (!s.active) return;
     __shared__ uint32_t s_tot[kTopkWaves];
     __shared__ uint32_t s_bin, s_remaining;
@@ -228,28 +223,37 @@ __global__ __launch_bounds__(kTopkThreads) void topk_pick_kernel(const float *sc
         s.state->remaining = s_remaining;
     }
     const int row = blockIdx.y;
-    uint32_t above = 0;
-    for_each_score(s, tid, v, [&](float f, int j) {
-        const int bin = linear_bin(f, lo, inv);
+    // its scores above the bin are counted, those inside it go to the row's candidate list: the
+    // workgroup reserves room for all of its candidates with one atomic (one per candidate would
+    // queue up on the row's counter)
+    uint32_t above = 0, cand_mask = 0, slot = 0;  // bit `slot` of the mask: the thread's slot-th score
+    for_each_score(s, tid, v, [&](float f, int) {
+        const int bin = topk_bin(f, lo, inv);
         above += bin > kth_bin ? 1u : 0u;
-        if (bin == kth_bin) {
-            const uint32_t at = atomicAdd(&s.state->ncand, 1u);
+        cand_mask |= (bin == kth_bin ? 1u : 0u) << slot;
+        ++slot;
+    });
+    const uint32_t mine_c = (uint32_t)__popc(cand_mask);
+    uint32_t both;
+    const uint32_t excl = block_inclusive_scan(above | (mine_c << 16), lane, wave, s_tot, &both) - (above | (mine_c << 16));
+    __shared__ uint32_t s_base;
+    if (tid == 0) {
+        slice_above[(int64_t)row * slices_per_row + blockIdx.x] = both & 0xffffu;
+        s_base = (both >> 16) ? atomicAdd(&s.state->ncand, both >> 16) : 0u;
+    }
+    __syncthreads();
+    uint32_t at = s_base + (excl >> 16);
+    slot = 0;
+    for_each_score(s, tid, v, [&](float f, int j) {
+        if ((cand_mask >> slot) & 1u) {
             if (at < (uint32_t)kCandMax) {
                 cand_key[(int64_t)row * kCandMax + at] = order_key(f);
                 cand_idx[(int64_t)row * kCandMax + at] = j;
             }
+            ++at;
         }
+        ++slot;
     });
-    above = wave_sum(above);
-    __syncthreads();
-    if (lane == 0) s_tot[wave] = above;
-    __syncthreads();
-    if (tid == 0) {
-        uint32_t t = 0;
-#pragma unroll
-        for (int w = 0; w < kTopkWaves; ++w) t += s_tot[w];
-        slice_above[(int64_t)row * slices_per_row + blockIdx.x] = t;
-    }
 }
 
 struct EmitShared {
@@ -281,7 +285,7 @@ __device__ __forceinline__ void radix_select(const Slice &s, EmitShared &sm, uin
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int j = 4 * i - s.mis + e;
-                    if (j >= 0 && j < s.n && linear_bin(f[e], lo, inv) == kth_bin) add(order_key(f[e]));
+                    if (j >= 0 && j < s.n && topk_bin(f[e], lo, inv) == kth_bin) add(order_key(f[e]));
                 }
             }
         } else {
@@ -311,7 +315,7 @@ __device__ __forceinline__ void radix_select(const Slice &s, EmitShared &sm, uin
 
 __global__ __launch_bounds__(kTopkThreads) void topk_emit_kernel(const float *scores, int64_t row_stride,
                                                                 const int32_t *row_lens, int rows_per_len,
-                                                                int max_len, int k, void *scratch,
+                                                                int max_len, int k, TopkRow *states,
                                                                 const uint32_t *cand_key, const int32_t *cand_idx,
                                                                 const uint32_t *slice_above, int slices_per_row,
                                                                 int32_t *positions) {
@@ -323,10 +327,10 @@ __global__ __launch_bounds__(kTopkThreads) void topk_emit_kernel(const float *sc
     // the row's state, the first candidates (rarely more than a workgroup's worth), the counts
     // of the earlier slices, and the slice's own scores (granules clamped into the row's buffer
     // of max_len scores; what lies beyond the row's length is masked further down).
-    const TopkRow *state = static_cast<const TopkRow *>(scratch) + row;
+    TopkRow *state = states + row;
     const uint32_t ncand = state->ncand, remaining = state->remaining;
     const int kth_bin = state->kth_bin;
-    const float lo = state->lo, inv = state->inv;
+    const float lo = state->center, inv = state->inv;  // the bin map's centre and scale
     const uint32_t early_key = cand_key[(int64_t)row * kCandMax + tid];
     const int32_t early_idx = cand_idx[(int64_t)row * kCandMax + tid];
     uint32_t gt_before = 0, eq_before = 0;
@@ -342,8 +346,11 @@ __global__ __launch_bounds__(kTopkThreads) void topk_emit_kernel(const float *sc
             own[u] = src4[min((int)blockIdx.x * kSliceGranules + kPerThread * tid + u, last4)];
     }
     asm volatile("" ::: "memory");  // the loads above stay above the branches on the row's length
+    // the row's histogram has served (pick read it in the launch before): back to zero for the next
+    // launch sequence, every slice of the grid a share of the bins
+    for (int i = blockIdx.x * kTopkThreads + tid; i < kBins; i += gridDim.x * kTopkThreads) state->hist[i] = 0;
 
-    const Slice s = open_slice(scores, row_stride, row_lens, rows_per_len, max_len, k, scratch);
+    const Slice s = open_slice(scores, row_stride, row_lens, rows_per_len, max_len, k, states);
     int32_t *dst = positions + (int64_t)row * k;
     if (k >= s.n) {  // every token is selected: slice x writes entries x*4096 .. and the last one the -1 tail
         const int lo_i = blockIdx.x * kTopkSliceScores;
@@ -399,7 +406,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_emit_kernel(const float *sc
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int j = 4 * i - s.mis + e;
-                if (j >= 0 && j < s.n && linear_bin(f[e], lo, inv) == kth_bin) {
+                if (j >= 0 && j < s.n && topk_bin(f[e], lo, inv) == kth_bin) {
                     const uint32_t key = order_key(f[e]);
                     gt_before += key > kth ? 1u : 0u;
                     eq_before += key == kth ? 1u : 0u;
@@ -435,7 +442,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_emit_kernel(const float *sc
         for (int e = 0; e < 4; ++e) {
             const int j = 4 * i - s.mis + e;
             const bool inside = i < s.n4 && j >= 0 && j < s.n;
-            const int bin = linear_bin(f[e], lo, inv);
+            const int bin = topk_bin(f[e], lo, inv);
             const uint32_t key = order_key(f[e]);
             const bool gt = inside && (bin > kth_bin || (bin == kth_bin && key > kth));
             const bool eq = inside && bin == kth_bin && key == kth;
@@ -462,27 +469,31 @@ __global__ __launch_bounds__(kTopkThreads) void topk_emit_kernel(const float *sc
 
 }  // namespace
 
-size_t topk_scratch_bytes(int32_t rows, int32_t max_len) {
+size_t topk_scratch_bytes(int32_t rows, int32_t max_len, int32_t) {
     const size_t slices = (size_t)topk_slices(max_len);
-    return (size_t)rows * (sizeof(TopkRow) + (size_t)kCandMax * 8 + slices * 4);
+    return (size_t)rows * ((size_t)kCandMax * 8 + slices * 4);
+}
+
+hipError_t launch_topk_reset(TopkRow *state, int32_t rows, hipStream_t stream) {
+    hipLaunchKernelGGL(topk_reset_kernel, dim3(rows), dim3(kTopkThreads), 0, stream, state);
+    return hipGetLastError();
 }
 
 hipError_t launch_topk(const float *scores, int64_t row_stride, int32_t rows, const int32_t *row_lens,
-                       int32_t rows_per_len, int32_t max_len, int32_t k, int32_t *positions, void *scratch,
-                       bool reset, hipStream_t stream) {
+                       int32_t rows_per_len, int32_t max_len, int32_t k, int32_t *positions, TopkRow *state,
+                       void *scratch, bool have_histogram, hipStream_t stream) {
     const int slices = topk_slices(max_len);
-    char *base = static_cast<char *>(scratch);
-    uint32_t *cand_key = reinterpret_cast<uint32_t *>(base + (size_t)rows * sizeof(TopkRow));
+    uint32_t *cand_key = static_cast<uint32_t *>(scratch);
     int32_t *cand_idx = reinterpret_cast<int32_t *>(cand_key + (size_t)rows * kCandMax);
     uint32_t *slice_above = reinterpret_cast<uint32_t *>(cand_idx + (size_t)rows * kCandMax);
     const dim3 grid(slices, rows), block(kTopkThreads);
-    if (reset) hipLaunchKernelGGL(topk_reset_kernel, dim3(rows), block, 0, stream, scratch);
-    hipLaunchKernelGGL(topk_hist_kernel, grid, block, 0, stream, scores, row_stride, row_lens, rows_per_len, max_len,
-                       k, scratch);
+    if (!have_histogram)
+        hipLaunchKernelGGL(topk_hist_kernel, grid, block, 0, stream, scores, row_stride, row_lens, rows_per_len, max_len,
+                           k, state);
     hipLaunchKernelGGL(topk_pick_kernel, grid, block, 0, stream, scores, row_stride, row_lens, rows_per_len, max_len,
-                       k, scratch, cand_key, cand_idx, slice_above, slices);
+                       k, state, cand_key, cand_idx, slice_above, slices);
     hipLaunchKernelGGL(topk_emit_kernel, grid, block, 0, stream, scores, row_stride, row_lens, rows_per_len, max_len,
-                       k, scratch, cand_key, cand_idx, slice_above, slices, positions);
+                       k, state, cand_key, cand_idx, slice_above, slices, positions);
     return hipGetLastError();
 }
 

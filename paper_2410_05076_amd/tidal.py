@@ -147,7 +147,7 @@ def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-STATIC_SCRATCH_BYTES = 48 << 20
+STATIC_SCRATCH_BYTES = 64 << 20
 
 
 def decode_step_static(shape, schedule, qs, Ks, Vs, k, outs, positions):
