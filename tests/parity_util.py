@@ -15,7 +15,8 @@ Positions: bit-exact against the oracle except inside a band around the
 oracle's k-th largest score s*: with tau = 1e-4 * max(|s*|, 1), every token
 scoring above s* + tau must be selected, none below s* - tau may be, and the
 list must hold exactly min(k, N) distinct in-range tokens in ascending order
-followed by -1.
+followed by -1.  Where the oracle's (k+1)-th largest score lies below s* - tau the band leaves no
+freedom, and check_positions then asserts the oracle's positions bit for bit (when they are given).
 """
 import torch
 
@@ -42,14 +43,16 @@ def check_output(gpu_out, oracle_out, what="", single_bf16_p=False):
     return max_abs, rel
 
 
-def check_positions(gpu_pos, oracle_scores, seq_lens, k, what="", relative_band=False):
+def check_positions(gpu_pos, oracle_scores, seq_lens, k, what="", relative_band=False, oracle_pos=None):
     """gpu_pos [B][Hkv][k] int32, oracle_scores [B][Hkv][N_max] fp32 (oracle's group scores).
+    oracle_pos (optional, like gpu_pos): rows whose (k+1)-th largest score lies below the band must equal it.
+    Returns (rows checked, rows that had to be, and were, identical to the oracle's).
 
     relative_band: tau = 1e-4 * |s*| without the floor of 1, for scores that are probabilities
     (far below 1, where the floor would make the band wider than the scores themselves)."""
     gp = gpu_pos.detach().cpu()
     B, H, _ = gp.shape
-    exact = 0
+    exact = decided = 0
     for b in range(B):
         n = int(seq_lens[b])
         ke = min(k, n)
@@ -60,7 +63,8 @@ def check_positions(gpu_pos, oracle_scores, seq_lens, k, what="", relative_band=
             assert sel.min() >= 0 and sel.max() < n, "%s: out of range at (%d,%d)" % (what, b, h)
             assert (sel[1:] > sel[:-1]).all(), "%s: not strictly ascending at (%d,%d)" % (what, b, h)
             r = oracle_scores[b, h, :n]
-            kth = torch.topk(r, ke).values[-1]
+            top = torch.topk(r, min(ke + 1, n)).values
+            kth = top[ke - 1]
             tau = BAND * (abs(kth.item()) if relative_band else max(abs(kth.item()), 1.0))
             chosen = torch.zeros(n, dtype=torch.bool)
             chosen[sel] = True
@@ -69,7 +73,11 @@ def check_positions(gpu_pos, oracle_scores, seq_lens, k, what="", relative_band=
             assert chosen[must].all(), "%s: a token above the band is missing at (%d,%d)" % (what, b, h)
             assert not chosen[never].any(), "%s: a token below the band was taken at (%d,%d)" % (what, b, h)
             exact += 1
-    return exact
+            if oracle_pos is not None and (ke == n or top[ke] < kth - tau):
+                assert torch.equal(row, oracle_pos[b, h].to(row.dtype)), \
+                    "%s: (%d,%d) differs from the oracle although its k-th score is clear of the next" % (what, b, h)
+                decided += 1
+    return exact, decided
 
 
 def same_positions(a, b):

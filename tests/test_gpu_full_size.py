@@ -4,7 +4,9 @@ launch configuration bench.py times (one call for all layers, eager and as a HIP
 The oracle checks one layer at a time (one layer's K and V on the host at once): every full
 attention and selection layer, and a sample of sparse layers (all of them for c2).  Sparse
 layers are compared with the oracle run on the positions the GPU selected, after those
-positions have passed the position rule against the oracle's own scores.
+positions have passed the position rule against the oracle's own scores (rows whose k-th score is
+clear of the (k+1)-th by more than the band must be the oracle's bit for bit); the first sparse layer
+checked after each selection layer is also compared with the oracle run on the oracle's own positions.
 """
 import gc
 import sys
@@ -81,7 +83,7 @@ def run_step(w, sparse_to_check, graph=False, tag="", page_size=0):
         say("%s: 3 graph replays identical to eager" % tag)
         del g
     slot = -1
-    exact = []
+    exact, decided, own_rho = [], [], {}
     for i, kind in enumerate(w.schedule):
         if kind == W.SPARSE and i not in sparse_to_check:
             continue
@@ -94,14 +96,19 @@ def run_step(w, sparse_to_check, graph=False, tag="", page_size=0):
         elif kind == W.SELECT:
             slot += 1
             ref, o_pos, o_scores = O.select(q, K, V, w.seq_lens, w.k, return_scores=True)
-            check_positions(pos[slot], o_scores, w.seq_lens, w.k, "%s L%d" % (tag, i))
+            rows, clear = check_positions(pos[slot], o_scores, w.seq_lens, w.k, "%s L%d" % (tag, i), oracle_pos=o_pos)
             exact.append(same_positions(pos[slot], o_pos))
+            decided.append("%d of %d rows clear of the band" % (clear, rows))
+            own_rho[slot] = o_pos
         else:
             cur = sum(1 for x in w.schedule[:i] if x == W.SELECT) - 1
             ref = O.sparse(q, K, V, w.seq_lens, pos[cur].cpu())
+            if cur in own_rho:   # once per selection layer: the oracle on its own positions
+                check_output(outs[i], O.sparse(q, K, V, w.seq_lens, own_rho.pop(cur)), "%s L%d, oracle's own rho" % (tag, i))
         ma, rel = check_output(outs[i], ref, "%s L%d" % (tag, i))
         say("%s: layer %2d kind %d max-abs %.2e rel-L2 %.2e" % (tag, i, kind, ma, rel))
-    say("%s: positions identical to the oracle's per selection layer: %s (%.1f s)" % (tag, exact, time.time() - t0))
+    say("%s: positions identical to the oracle's per selection layer: %s, %s (%.1f s)"
+        % (tag, exact, decided, time.time() - t0))
     td.close()
     del qs, Ks, Vs, outs, pos
     free()

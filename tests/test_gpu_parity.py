@@ -73,7 +73,7 @@ def run_layer_checks(w, layer_kinds, tag, kernel_variant=0):
                 d = (host(scores)[b, :, :n] - o_scores[b, :, :n]).abs().max().item()
                 assert d <= 1e-4 * max(1.0, o_scores[b, :, :n].abs().max().item()), "%s scores %g" % (tag, d)
                 assert torch.isnan(host(scores)[b, :, n:]).all(), "scores written beyond the sequence"
-            check_positions(pos, o_scores, w.seq_lens, w.k, "%s L%d" % (tag, i))
+            check_positions(pos, o_scores, w.seq_lens, w.k, "%s L%d" % (tag, i), oracle_pos=o_pos)
             say("%s: layer %d positions identical to oracle: %s" % (tag, i, same_positions(pos, o_pos)))
             # same result without the caller's score buffer (workspace path)
             pos2 = torch.full_like(pos, -7)

@@ -66,3 +66,99 @@ def test_ragged_rows_and_misaligned_stride(td):
     k = 256
     got = run(td, buf, lens, 2, k)
     assert torch.equal(got, expect(buf, lens, 2, k))
+
+
+# ---- boundaries of the kernels' arithmetic: slice edges (4096 scores per workgroup), the candidate
+# list's capacity (3840 per row) and the switch between rank counting and radix select (256
+# candidates), misaligned row starts, many rows.  Seeded and bounded; integer work, bit-exact.
+
+LENGTHS = [255, 256, 257, 4093, 4094, 4095, 4096, 4097, 4099, 8191, 8192, 8193, 12287, 12289, 16385]
+BUDGETS = [1, 2, 255, 256, 257, 3839, 3840, 3841, 4095, 4096, 4097]
+
+
+@pytest.mark.parametrize("n", LENGTHS)
+def test_lengths_and_budgets_around_slice_boundaries(td, n):
+    g = torch.Generator().manual_seed(n)
+    for stride in (n, n + 1, n + 2, n + 3):              # rows start at every alignment
+        scores = torch.randn((4, stride), generator=g) * 2.5
+        scores[:, n:] = float("inf")                      # beyond the row: must never be picked
+        for k in BUDGETS + [n - 1, n, n + 3]:
+            if k < 1:
+                continue
+            assert torch.equal(run(td, scores, [n], 4, k), expect(scores, [n], 4, k)), (n, stride, k)
+
+
+@pytest.mark.parametrize("cands", [255, 256, 257, 3839, 3840, 3841, 5000])
+def test_population_of_the_kth_bin_around_the_candidate_list_limits(td, cands):
+    """Rows whose k-th bin holds exactly `cands` scores: rank counting up to 256, radix select over the
+    list up to its capacity, exact select over the whole row beyond."""
+    n = 3 * 4096 + 100
+    g = torch.Generator().manual_seed(cands)
+    rows = []
+    for spread in (0.002, 0.0):                           # distinct keys inside the bin / all of them equal
+        scores = torch.rand(n, generator=g) * 0.5         # bulk far below
+        where = torch.randperm(n, generator=g)[:cands + 40]
+        scores[where[:cands]] = 8.0 + torch.rand(cands, generator=g) * spread
+        scores[where[cands:]] = 100.0                     # 40 certain ones above
+        rows.append(scores)
+    scores = torch.stack(rows)
+    for k in (41, 40 + cands // 2, 40 + cands - 1, 40 + cands):
+        assert torch.equal(run(td, scores, [n], 2, k), expect(scores, [n], 2, k)), (cands, k)
+
+
+def test_many_rows_with_their_own_lengths():
+    """300 rows (more than the rows whose state lives in the fixed part of the workspace), every row with a
+    length of its own, odd stride."""
+    g = torch.Generator().manual_seed(77)
+    rows, stride, k = 300, 5003, 129
+    lens = [int(x) for x in torch.randint(1, 5001, (rows,), generator=g)]
+    lens[:6] = [1, 128, 129, 130, 4096, 5000]
+    scores = torch.randn((rows, stride), generator=g)
+    for r, n in enumerate(lens):
+        scores[r, n:] = float("inf")
+    lens_t = torch.ones(1, dtype=torch.int32, device=DEV)
+    q = torch.zeros((1, 1, 64), dtype=torch.float32, device=DEV)
+    K = torch.zeros((1, 1, 8, 64), dtype=torch.float32, device=DEV)
+    t = tidal.Tidal(tidal.make_shape(q, K, lens_t), 1, topk_rows=rows, topk_max_len=stride)
+    for _ in range(2):                                    # the state is reset before every use
+        assert torch.equal(run(t, scores, lens, 1, k), expect(scores, lens, 1, k))
+    t.close()
+
+
+def test_repeated_calls_leave_the_row_state_clean(td):
+    """The row histogram returns to zero after every call: alternating rows of different shapes and budgets
+    on one context keep giving the oracle's answer."""
+    g = torch.Generator().manual_seed(9)
+    cases = [(torch.randn((8, 32768), generator=g) * 2, [32768], 8, 2048),
+             (torch.randn((3, 5000), generator=g), [5000], 3, 4999),          # k close to n
+             (torch.randn((16, 777), generator=g), [777], 16, 800),           # k >= n: no selection
+             (torch.randint(-2, 3, (5, 9000), generator=g).float(), [9000], 5, 4500)]
+    want = [expect(*c) for c in cases]
+    for i in [0, 1, 2, 3, 2, 0, 3, 1, 0]:
+        assert torch.equal(run(td, *cases[i]), want[i]), i
+
+
+def test_selection_layer_with_tied_scores_matches_the_oracle_exactly():
+    """The fused path (the attention launch bins the scores itself): keys drawn from five vectors give
+    scores with five distinct values and thousands of exact ties, more than the candidate list holds."""
+    from paper_2410_05076_amd import workloads as W
+    g = torch.Generator().manual_seed(21)
+    B, Hq, Hkv, d, N, k = 2, 8, 2, 128, 9000, 3000
+    q = torch.randn((B, Hq, d), generator=g).to(torch.bfloat16)
+    base = torch.randn((5, d), generator=g).to(torch.bfloat16)
+    pick = torch.randint(0, 5, (B, Hkv, N), generator=g)
+    K = base[pick]                                         # [B][Hkv][N][d]
+    V = torch.randn((B, Hkv, N, d), generator=g).to(torch.bfloat16)
+    lens = [N, 7001]
+    qd, Kd, Vd = q.to(DEV), K.contiguous().to(DEV), V.to(DEV)
+    lens_t = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    shape = tidal.make_shape(qd, Kd, lens_t)
+    t = tidal.Tidal(shape, k)
+    out = torch.empty_like(qd)
+    pos = torch.full((B, Hkv, k), -7, dtype=torch.int32, device=DEV)
+    for _ in range(2):
+        t.select_tokens(shape, qd, Kd, Vd, k, out, pos)
+        torch.cuda.synchronize()
+        _, o_pos = O.select(q, K.contiguous(), V, lens, k)
+        assert torch.equal(pos.cpu(), o_pos)
+    t.close()
