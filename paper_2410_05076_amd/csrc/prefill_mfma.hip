@@ -288,12 +288,32 @@ void prefill_mfma_kernel(const PrefillParams p) {
             for (int h = 0; h < 2; ++h)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) pr[h][i] = fast_exp2(fmaf(st[r][h][i], scale2, -m_use[r]));
-            // P^T as B operand: the lane's eight tokens of row n16, rounded to bf16
-            const bf16x8 pb = __builtin_bit_cast(bf16x8, make_uint4(bf16_pair(pr[0][0], pr[0][1]), bf16_pair(pr[0][2], pr[0][3]),
-                                                                   bf16_pair(pr[1][0], pr[1][1]), bf16_pair(pr[1][2], pr[1][3])));
+            // P^T as B operand: the lane's eight tokens of row n16, as two bf16 parts (the upper
+            // half of the float, and the rest rounded to bf16), so that the probabilities carry
+            // 16 bits like those of the decode kernels: with a single bf16 rounding, two or three
+            // comparable tokens with far-apart values put up to 2^-10 of that distance on the
+            // output, a quarter of the stated tolerance on top of the output's own rounding
+            uint32_t ph[2][4];
+            float pl[2][4];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[r][e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[e], pb, acc[r][e], 0, 0, 0);
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    ph[h][i] = __float_as_uint(pr[h][i]);
+                    pl[h][i] = pr[h][i] - __uint_as_float(ph[h][i] & 0xffff0000u);
+                }
+            const bf16x8 pb = __builtin_bit_cast(
+                bf16x8, make_uint4(__builtin_amdgcn_perm(ph[0][1], ph[0][0], kHighHalves), __builtin_amdgcn_perm(ph[0][3], ph[0][2], kHighHalves),
+                                   __builtin_amdgcn_perm(ph[1][1], ph[1][0], kHighHalves), __builtin_amdgcn_perm(ph[1][3], ph[1][2], kHighHalves)));
+            const bf16x8 pb_lo = __builtin_bit_cast(bf16x8, make_uint4(bf16_pair(pl[0][0], pl[0][1]), bf16_pair(pl[0][2], pl[0][3]),
+                                                                      bf16_pair(pl[1][0], pl[1][1]), bf16_pair(pl[1][2], pl[1][3])));
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                acc[r][e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[e], pb, acc[r][e], 0, 0, 0);
+                acc[r][e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[e], pb_lo, acc[r][e], 0, 0, 0);
+            }
             lacc[r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb, lacc[r], 0, 0, 0);
+            lacc[r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb_lo, lacc[r], 0, 0, 0);
         }
         if constexpr (!kInPlace) {
             if (more) {

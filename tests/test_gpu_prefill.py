@@ -24,8 +24,7 @@ def run_prefill(w, num_new, seed=3, chunked=True):
     say("prefill %s P=%d chunked=%s" % (w.name, num_new, chunked))
     td.prefill_attend(shape, q, K, V, out)
     torch.cuda.synchronize()
-    check_output(out, O.prefill(host(q), host(K), host(V), w.seq_lens), "prefill %s P=%d" % (w.name, num_new),
-                 single_bf16_p=True)
+    check_output(out, O.prefill(host(q), host(K), host(V), w.seq_lens), "prefill %s P=%d" % (w.name, num_new))
     td.close()
 
 
@@ -65,7 +64,7 @@ def test_prefill_with_a_workspace_for_some_of_the_chunks():
         say("prefill with %d workspace bytes" % ws)
         td.prefill_attend(shape, q, K, V, out)
         torch.cuda.synchronize()
-        check_output(out, ref, "workspace %d" % ws, single_bf16_p=True)
+        check_output(out, ref, "workspace %d" % ws)
         td.close()
 
 
@@ -82,8 +81,8 @@ def test_prefill_longer_than_a_sequence_yields_zeros_for_the_missing_tokens():
     torch.cuda.synchronize()
     assert (out[1, :6] == 0).all()                     # tokens at positions -6 .. -1 do not exist
     ref = O.prefill(host(q[1:, 6:]).contiguous(), host(K[1:]), host(V[1:]), [10])
-    check_output(out[1:, 6:], ref, "tail of the short sequence", single_bf16_p=True)
-    check_output(out[:1], O.prefill(host(q[:1]), host(K[:1]), host(V[:1]), [50]), "long sequence", single_bf16_p=True)
+    check_output(out[1:, 6:], ref, "tail of the short sequence")
+    check_output(out[:1], O.prefill(host(q[:1]), host(K[:1]), host(V[:1]), [50]), "long sequence")
     td.close()
 
 
@@ -102,10 +101,10 @@ def test_chunked_prefill_of_a_ragged_batch_with_a_sequence_shorter_than_the_new_
     torch.cuda.synchronize()
     assert (out[1, :6] == 0).all()                     # tokens at positions -6 .. -1 do not exist
     ref = O.prefill(host(q[1:2, 6:]).contiguous(), host(K[1:2]), host(V[1:2]), [10])
-    check_output(out[1:2, 6:], ref, "tail of the short sequence", single_bf16_p=True)
+    check_output(out[1:2, 6:], ref, "tail of the short sequence")
     for b in (0, 2):
         check_output(out[b:b + 1], O.prefill(host(q[b:b + 1]), host(K[b:b + 1]), host(V[b:b + 1]), [w.seq_lens[b]]),
-                     "sequence %d" % b, single_bf16_p=True)
+                     "sequence %d" % b)
     td.close()
 
 
@@ -148,7 +147,7 @@ def test_prefill_at_the_benchmark_shape_on_sampled_tokens(num_new):
                      min(per_block, num_new - 1), min(5 * per_block + 3, num_new - 1)})
     for j in sample:
         ref = O.full(host(q[:, j]).contiguous(), Kh, Vh, [n - num_new + j + 1])
-        check_output(out[:, j], ref, "c2 P=%d token %d" % (num_new, j), single_bf16_p=True)
+        check_output(out[:, j], ref, "c2 P=%d token %d" % (num_new, j))
     td.close()
 
 
@@ -169,7 +168,7 @@ def test_prefill_with_a_token_major_cache_layout(num_new):
     say("prefill token-major P=%d" % num_new)
     td.prefill_attend(shape, q, Kt, Vt, out)
     torch.cuda.synchronize()
-    check_output(out, O.prefill(host(q), host(K), host(V), w.seq_lens), "token-major prefill", single_bf16_p=True)
+    check_output(out, O.prefill(host(q), host(K), host(V), w.seq_lens), "token-major prefill")
     td.close()
 
 
@@ -204,7 +203,7 @@ def test_chunked_prefill_as_a_hip_graph():
     td.prefill_attend(shape, q, K, V, out)
     torch.cuda.synchronize()
     eager = out.clone()
-    check_output(eager, O.prefill(host(q), host(K), host(V), w.seq_lens), "eager", single_bf16_p=True)
+    check_output(eager, O.prefill(host(q), host(K), host(V), w.seq_lens), "eager")
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
         td.prefill_attend(shape, q, K, V, out)
@@ -245,7 +244,7 @@ def test_prefill_over_a_paged_cache(name, over, num_new, page_size, layout):
     t = host(table)
     Kl = O.gather_pages(host(Kv), t, w.seq_lens, w.max_seq_len)
     Vl = O.gather_pages(host(Vv), t, w.seq_lens, w.max_seq_len)
-    check_output(out, O.prefill(host(q), Kl, Vl, w.seq_lens), "paged prefill", single_bf16_p=True)
+    check_output(out, O.prefill(host(q), Kl, Vl, w.seq_lens), "paged prefill")
     td.close()
 
 
@@ -305,7 +304,7 @@ def test_random_small_prefills(seed):
         m = min(P, n)
         assert (out[b, :P - m] == 0).all()
         ref = O.prefill(host(q[b:b + 1, P - m:]).contiguous(), host(K[b:b + 1]), host(V[b:b + 1]), [n])
-        check_output(out[b:b + 1, P - m:], ref, "random prefill %d, sequence %d" % (seed, b), single_bf16_p=True)
+        check_output(out[b:b + 1, P - m:], ref, "random prefill %d, sequence %d" % (seed, b))
     td.close()
 
 
@@ -326,5 +325,5 @@ def test_prefill_whose_row_maxima_keep_rising():
         say("rising maxima, chunked %s" % chunked)
         td.prefill_attend(shape, q, K, V, out)
         torch.cuda.synchronize()
-        check_output(out, O.prefill(host(q), host(K), host(V), [n]), "rising maxima", single_bf16_p=True)
+        check_output(out, O.prefill(host(q), host(K), host(V), [n]), "rising maxima")
         td.close()
