@@ -406,6 +406,21 @@ def prefill_bench(args, torch, tidal, W, dev):
     torch.cuda.synchronize()
     ts = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
     us = sum(ts) / len(ts)
+    cpu = None
+    if not args.no_cpu_baseline and not args.page_size:
+        # the oracle's causal attention for a bounded sample of the new tokens (the last ones, which see the
+        # most positions), scaled to all of them by the positions they see
+        from oracle import tidal_oracle as O
+        sample = min(P, 8)
+        qh, Kh, Vh = q[:, P - sample:].cpu().contiguous(), K.cpu(), V.cpu()
+        t0 = time.perf_counter()
+        O.prefill(qh, Kh, Vh, w.seq_lens)
+        dt = time.perf_counter() - t0
+        seen_sample = sum(sum(max(n - sample + j + 1, 0) for j in range(sample)) for n in w.seq_lens)
+        seen_all = sum(sum(max(n - P + j + 1, 0) for j in range(P)) for n in w.seq_lens)
+        cpu = {"value": round(dt * 1e6 * seen_all / max(seen_sample, 1), 1), "unit": "us", "cores": O.num_threads(),
+               "kind": "oracle",
+               "sample": "the last %d of the %d new tokens of every sequence, scaled by the positions attended" % (sample, P)}
     seen = sum(sum(max(n - P + j + 1, 0) for j in range(P)) for n in w.seq_lens)
     flop = 4.0 * w.head_dim * w.num_q_heads * seen
     # the keys and values of every position some new token sees, once
@@ -428,7 +443,7 @@ def prefill_bench(args, torch, tidal, W, dev):
             "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
             "config": {"workload": DESCRIPTIONS[w.name] + ", one layer, prefill attention over the last %d tokens" % P
                        + (", paged cache, page size %d (%s)" % (args.page_size, args.page_layout) if args.page_size else "")},
-            "median_us": round(ts[len(ts) // 2], 2), "roofline": roof}
+            "median_us": round(ts[len(ts) // 2], 2), "roofline": roof, "cpu_baseline": cpu}
 
 
 def hbm_probe(torch, tidal, dev, td=None, nbytes=2**30, reps=6):

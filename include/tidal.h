@@ -61,7 +61,8 @@
  *     TD_ERR_WORKSPACE; a failed HIP call gives TD_ERR_HIP.  td_last_error
  *     returns a text for the most recent failure on that context.
  *     Supported: head_dim 64 or 128, group size 1, 2, 4 or 8,
- *     batch * num_kv_heads <= 65535.
+ *     batch * num_kv_heads <= 65535, max_seq_len <= 2^30 (2^20 for calls with a
+ *     token budget).
  *   - A context serves one stream at a time: calls that use the same context
  *     must be ordered on one stream (they share its workspace).
  */

@@ -49,6 +49,25 @@ def build(extra=(), incremental=False, jobs=None):
     return LIB
 
 
+def build_sanitized_host_check():
+    """Builds tests/abi_host_check.cpp against the library with the host side of api.hip (argument checks,
+    workspace layout, launch planning) compiled with AddressSanitizer and UndefinedBehaviorSanitizer; the
+    device code and the other objects are the normal ones (build() must have run).  Returns the executable."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined"]
+    api_obj = os.path.join(OBJ_DIR, "api_san.o")
+    chk_obj = os.path.join(OBJ_DIR, "abi_host_check.o")
+    exe = os.path.join(OBJ_DIR, "abi_host_check")
+    flags = [f for f in HIPCC_FLAGS if f != "-O3"] + ["-O1", "-g"]
+    subprocess.run([hipcc, *flags, *san, "-c", os.path.join(HERE, "csrc", "api.hip"), "-o", api_obj], check=True)
+    subprocess.run([hipcc, "-O1", "-g", "-std=c++17", "-I", os.path.join(ROOT, "include"), *san, "-c", "-x", "c++",
+                    os.path.join(ROOT, "tests", "abi_host_check.cpp"), "-o", chk_obj], check=True)
+    others = [os.path.join(OBJ_DIR, os.path.basename(src)[:-4] + ".o") for src in SOURCES if not src.endswith("api.hip")]
+    subprocess.run([hipcc, "--offload-arch=gfx950", "-fsanitize=address,undefined", "-fno-gpu-sanitize", chk_obj, api_obj,
+                    *others, "-o", exe], check=True)
+    return exe
+
+
 if __name__ == "__main__":
     import sys
     args = sys.argv[1:]

@@ -83,6 +83,7 @@ const char *shape_problem(const td_shape *s, int32_t k, td_status *code) {
     }
     *code = TD_ERR_UNSUPPORTED;
     if (s->head_dim != 64 && s->head_dim != 128) return "head_dim must be 64 or 128";
+    if (s->max_seq_len > (1 << 30)) return "max_seq_len above 2^30";  // chunk arithmetic is done in 32 bits
     const int g = s->num_q_heads / s->num_kv_heads;
     if (g != 1 && g != 2 && g != 4 && g != 8) return "group size must be 1, 2, 4 or 8";
     if (s->batch > 65535 || s->num_kv_heads > 65535 || (int64_t)s->batch * selection_rows(s) > 65535)

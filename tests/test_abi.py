@@ -3,6 +3,7 @@ the header declares, and rejects bad arguments before touching the device."""
 import ctypes
 import os
 import re
+import subprocess
 
 import pytest
 
@@ -83,6 +84,7 @@ def test_validate_rejects_paged(over, code):
     (dict(selection=-1), 1, tidal.ERR_INVALID_ARG),
     (dict(), 600000, tidal.ERR_INVALID_ARG),
     (dict(head_dim=96, kv_stride_tok=96), 1, tidal.ERR_UNSUPPORTED),
+    (dict(max_seq_len=(1 << 30) + 1), 0, tidal.ERR_UNSUPPORTED),
     (dict(num_q_heads=24, num_kv_heads=8), 1, tidal.ERR_UNSUPPORTED),
     (dict(num_q_heads=128, num_kv_heads=8), 1, tidal.ERR_UNSUPPORTED),
 ])
@@ -112,3 +114,15 @@ def test_calls_without_a_context_fail_cleanly():
     assert L.td_create(None, 0, 0) == tidal.ERR_INVALID_ARG
     assert L.td_status_string(tidal.ERR_WORKSPACE) == b"workspace too small"
     assert L.td_last_error(None) == b"context is NULL"
+
+
+def test_host_logic_under_sanitizers():
+    """Argument checks, workspace layout and launch planning, compiled with AddressSanitizer and
+    UndefinedBehaviorSanitizer (host code only), over a grid of valid, invalid and extreme shapes."""
+    from paper_2410_05076_amd import build
+    if not all(os.path.exists(os.path.join(build.OBJ_DIR, os.path.basename(s)[:-4] + ".o")) for s in build.SOURCES):
+        build.build()
+    exe = build.build_sanitized_host_check()
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="halt_on_error=1:print_stacktrace=1")
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=300, env=env)
+    assert r.returncode == 0 and r.stdout.startswith("ok"), (r.returncode, r.stdout[-2000:], r.stderr[-4000:])
