@@ -227,9 +227,12 @@ void attend_split_kernel(const AttendParams p) {
     float *s_scores = reinterpret_cast<float *>(lds_tail);
     uint32_t *s_hist = reinterpret_cast<uint32_t *>(lds_tail + kStageBytes);
     const bool per_head = MODE == kSelect && p.select_rule == TD_SELECT_PER_HEAD;
+    const bool fused_hist = MODE == kSelect && p.topk_rows != nullptr;  // never with the per-head rule
     if constexpr (MODE == kSelect) {
-        if (p.topk_rows)
-            for (int i = threadIdx.x; i < kTopkBins; i += T) s_hist[i] = 0;  // ordered before its use by the barrier in write_staged_scores
+        if (fused_hist) {
+            for (int i = threadIdx.x; i < kTopkBins; i += T) s_hist[i] = 0;
+            __syncthreads();
+        }
     }
 
     for (int base = t0 + wave * STEP; base < t1; base += TILE) {
@@ -293,7 +296,10 @@ void attend_split_kernel(const AttendParams p) {
                 float mine = gsum[0];
 #pragma unroll
                 for (int u = 1; u < kUnroll; ++u) mine = c == u ? gsum[u] : mine;
-                if (c < kUnroll && t < t1) s_scores[t - t0] = mine;
+                if (c < kUnroll && t < t1) {
+                    s_scores[t - t0] = mine;
+                    if (fused_hist) bin_score(s_hist, mine);
+                }
             } else {  // one score row per query head: the head's own scaled logits
 #pragma unroll
                 for (int i = 0; i < G; ++i) {
@@ -337,7 +343,7 @@ void attend_split_kernel(const AttendParams p) {
     if constexpr (MODE == kSelect) {
         if (!per_head) {
             write_staged_scores<T>(s_scores, t1 - t0, p.scores + ((int64_t)b * p.num_kv_heads + g) * p.score_stride + t0);
-            if (p.topk_rows) add_score_histogram<T>(p.topk_rows + (b * p.num_kv_heads + g), s_scores, t1 - t0, s_hist, split == 0);
+            if (fused_hist) flush_score_histogram<T>(p.topk_rows + (b * p.num_kv_heads + g), s_hist, split == 0);
             __syncthreads();  // the stage has been read; its LDS now takes the states
         }
     }

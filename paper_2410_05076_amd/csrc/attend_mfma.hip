@@ -189,9 +189,12 @@ void attend_mfma_kernel(const AttendParams p) {
     float *s_scores = reinterpret_cast<float *>(lds_tail);
     uint32_t *s_hist = reinterpret_cast<uint32_t *>(lds_tail + kStageBytes);
     const bool per_head = MODE == kSelect && p.select_rule == TD_SELECT_PER_HEAD;
+    const bool fused_hist = MODE == kSelect && p.topk_rows != nullptr;  // never with the per-head rule
     if constexpr (MODE == kSelect) {
-        if (p.topk_rows)
-            for (int i = threadIdx.x; i < kTopkBins; i += T) s_hist[i] = 0;  // ordered before its use by the barrier in write_staged_scores
+        if (fused_hist) {
+            for (int i = threadIdx.x; i < kTopkBins; i += T) s_hist[i] = 0;
+            __syncthreads();
+        }
     }
 
     for (int base = t0 + wave * STEP; base < t1; base += W * STEP) {
@@ -256,6 +259,11 @@ void attend_mfma_kernel(const AttendParams p) {
                             for (int i = 0; i < 4; ++i)
                                 if (valid[x][i]) s_scores[tok[x][i] - t0] = gs[i];
                         }
+                        if (fused_hist) {
+#pragma unroll
+                            for (int i = 0; i < 4; ++i)
+                                if (valid[x][i]) bin_score(s_hist, gs[i]);
+                        }
                     }
                 } else if (n16 < G) {  // one 16-byte store per head where the row allows it
                     float *dst = score_row + (int64_t)n16 * p.score_stride + tok[x][0];
@@ -316,7 +324,7 @@ void attend_mfma_kernel(const AttendParams p) {
     if constexpr (MODE == kSelect) {
         if (!per_head) {
             write_staged_scores<T>(s_scores, t1 - t0, score_row + t0);
-            if (p.topk_rows) add_score_histogram<T>(p.topk_rows + (b * p.num_kv_heads + g), s_scores, t1 - t0, s_hist, split == 0);
+            if (fused_hist) flush_score_histogram<T>(p.topk_rows + (b * p.num_kv_heads + g), s_hist, split == 0);
             __syncthreads();  // stage and histogram have been read; their LDS now takes the states
         }
     }

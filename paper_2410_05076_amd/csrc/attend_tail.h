@@ -52,18 +52,26 @@ __device__ __forceinline__ void write_staged_scores(const float *staged, int n, 
     }
 }
 
-// Fused histogram of a selection layer: bins the n group scores that the workgroup has staged in
-// LDS (after write_staged_scores, whose barrier has passed) with the top-k launch's bin map centred
-// on zero, and adds the non-empty bins to the row's histogram.  hist: kTopkBins zeroed LDS words.
-// The row's histogram is zero when the launch starts (the top-k launch leaves it so).
+// Fused histogram of a selection layer: while a chunk's group scores pass through the kernel they
+// are also binned, with the top-k launch's bin map centred on zero, into a histogram in LDS
+// (kTopkBins words, 8-byte aligned, zeroed before the loop and a barrier), one LDS atomic per score
+// inside the streaming loop, where it hides behind the loads; after the loop (and a barrier) the
+// non-empty bins are added to the row's histogram in memory.  That one is zero when the launch
+// starts (the top-k launch leaves it so).
+// (Leaving out the bins below the one where the chunk's own count from the top reaches k, which the
+// top-k launch can never need, was measured and gained nothing.)
+__device__ __forceinline__ void bin_score(uint32_t *hist, float score) {
+    atomicAdd(&hist[topk_bin(score, 0.f, 1.f)], 1u);
+}
 template <int T>
-__device__ __forceinline__ void add_score_histogram(TopkRow *row, const float *staged, int n, uint32_t *hist,
-                                                    bool first_chunk) {
-    for (int i = threadIdx.x; i < n; i += T) atomicAdd(&hist[topk_bin(staged[i], 0.f, 1.f)], 1u);
-    __syncthreads();
-    for (int i = threadIdx.x; i < kTopkBins; i += T) {
-        const uint32_t c = hist[i];
-        if (c) atomicAdd(&row->hist[i], c);
+__device__ __forceinline__ void flush_score_histogram(TopkRow *row, const uint32_t *hist, bool first_chunk) {
+    // two neighbouring bins per 64-bit atomic (a count never carries out of its 32 bits: a row has
+    // fewer than 2^32 scores): half as many updates of the row's histogram in memory
+    const uint64_t *pairs = reinterpret_cast<const uint64_t *>(hist);
+    uint64_t *row_pairs = reinterpret_cast<uint64_t *>(row->hist);
+    for (int i = threadIdx.x; i < kTopkBins / 2; i += T) {
+        const uint64_t c = pairs[i];
+        if (c) __hip_atomic_fetch_add(&row_pairs[i], c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     if (first_chunk && threadIdx.x == 0) {
         row->center = 0.f;

@@ -137,7 +137,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_hist_kernel(const float *sc
     asm volatile("" ::: "memory");  // requested before the row's length is read
     const Slice s = open_slice(scores, row_stride, row_lens, rows_per_len, max_len, k, states);
     if (!s.active) return;
-    __shared__ uint32_t s_hist[kBins];
+    __shared__ __align__(8) uint32_t s_hist[kBins];
     __shared__ float s_lo[kTopkWaves], s_hi[kTopkWaves];
     // value range from 256 samples of the whole row: the same in every slice of the row
     const float x = s.src[(int64_t)tid * s.n / kTopkThreads];
@@ -173,9 +173,12 @@ __global__ __launch_bounds__(kTopkThreads) void topk_hist_kernel(const float *sc
     }
     for_each_score(s, tid, v, [&](float f, int) { atomicAdd(&s_hist[topk_bin(f, center, inv)], 1u); });
     __syncthreads();
-    for (int i = tid; i < kBins; i += kTopkThreads) {
-        const uint32_t c = s_hist[i];
-        if (c) atomicAdd(&s.state->hist[i], c);
+    // two neighbouring bins per 64-bit atomic (a count never carries out of its 32 bits)
+    const uint64_t *pairs = reinterpret_cast<const uint64_t *>(s_hist);
+    uint64_t *row_pairs = reinterpret_cast<uint64_t *>(s.state->hist);
+    for (int i = tid; i < kBins / 2; i += kTopkThreads) {
+        const uint64_t c = pairs[i];
+        if (c) __hip_atomic_fetch_add(&row_pairs[i], c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
