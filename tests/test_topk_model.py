@@ -18,6 +18,7 @@ import build_topk_model
 from oracle import tidal_oracle as O
 
 SLICE = 4096
+BINS = 2048      # kTopkBins of csrc/topk_math.h
 
 
 @pytest.fixture(scope="module")
@@ -60,14 +61,16 @@ def test_bin_map_is_monotone_and_respects_equal_keys(model):
     for center, inv in ((0.0, 1.0), (1.5, 64.0 / 7.0), (-40.0, 0.37), (0.0, 0.0), (3e37, 1e-37)):
         order = sorted(xs.tolist())
         bins = [model.topk_model_bin(x, center, inv) for x in order]
-        assert all(0 <= b < 2048 for b in bins)
+        assert all(0 <= b < BINS for b in bins)
         assert all(a <= b for a, b in zip(bins, bins[1:])), (center, inv)
-    assert model.topk_model_bin(0.0, 0.0, 1.0) == model.topk_model_bin(-0.0, 0.0, 1.0) == 1024
+    assert model.topk_model_bin(0.0, 0.0, 1.0) == model.topk_model_bin(-0.0, 0.0, 1.0) == BINS // 2
     assert model.topk_model_key(0.0) == model.topk_model_key(-0.0)
-    # 64 bins per octave on either side of zero
-    assert model.topk_model_bin(1.0, 0.0, 1.0) + 64 == model.topk_model_bin(2.0, 0.0, 1.0)
-    assert model.topk_model_bin(-1.0, 0.0, 1.0) - 64 == model.topk_model_bin(-2.0, 0.0, 1.0)
-    assert model.topk_model_bin(f32(1.0 + 1.0 / 64), 0.0, 1.0) == model.topk_model_bin(1.0, 0.0, 1.0) + 1
+    # the same number of bins per octave on either side of zero, 16 octaves each
+    per_octave = BINS // 32
+    assert model.topk_model_bin(1.0, 0.0, 1.0) + per_octave == model.topk_model_bin(2.0, 0.0, 1.0)
+    assert model.topk_model_bin(-1.0, 0.0, 1.0) - per_octave == model.topk_model_bin(-2.0, 0.0, 1.0)
+    assert model.topk_model_bin(f32(1.0 + 1.0 / per_octave), 0.0, 1.0) == model.topk_model_bin(1.0, 0.0, 1.0) + 1
+    assert model.topk_model_bin(3e38, 0.0, 1.0) == BINS - 1 and model.topk_model_bin(-3e38, 0.0, 1.0) == 0
     keys = [model.topk_model_key(x) for x in sorted(set(xs.tolist()))]
     assert all(a <= b for a, b in zip(keys, keys[1:]))
 
