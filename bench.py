@@ -304,13 +304,17 @@ def measure_budget(args, torch, tidal, W, dev, w, over, shape, lens, sets, all_n
         if r:
             per_kind[kname] = {"layers": sum(1 for x in w.schedule if x == kind),
                                "avg_us": round(r[0], 2), "median_us": round(r[1], 2)}
-    if "select" in per_kind and args.selection in ("sum", "max", "per_head"):
-        # argTopK alone on the scores that the last selection launch left (cache-resident, as in a layer)
-        rows = scores.view(w.batch * sel_rows, w.max_seq_len)
-        rho = sets[0][4][0].view(w.batch * sel_rows, w.k)
-        r = time_launches(lambda _: td.topk(rows, lens, sel_rows, w.k, rho), args.kernel_reps)
-        per_kind["select"]["topk_us"] = round(r[0], 2)
-        per_kind["select"]["attention_us"] = round(per_kind["select"]["avg_us"] - r[0], 2)
+    if "select" in per_kind:
+        # the selection layer's attention launch alone (fused score write and score histogram): the same calls
+        # with the library's timing switch that stops a selection call after its attention launch
+        tune = [int(x) for x in args.tune.split(",")] if args.tune else [0, 0, 0, 0, 0]
+        td.set_tuning(*(tune[:4] + [tune[4] | 32]))
+        td.reset()          # the switch marks the rows' state for clearing: do it here, not inside the timed graph
+        r = time_kind(W.SELECT, args.kernel_reps)
+        td.set_tuning(*tune)
+        td.reset()
+        per_kind["select"]["attention_us"] = round(r[0], 2)
+        per_kind["select"]["topk_us"] = round(per_kind["select"]["avg_us"] - r[0], 2)
     # algorithmic bytes per layer of each kind: K and V once; a selection layer also writes the fp32
     # scores and reads them back for the top-k, and writes rho; a sparse layer reads rho and its rows
     layer_bytes = {"full": kv_bytes, "select": kv_bytes + 2 * score_bytes + pos_bytes,
@@ -322,7 +326,7 @@ def measure_budget(args, torch, tidal, W, dev, w, over, shape, lens, sets, all_n
                   "share_of_step": round(d["layers"] * d["avg_us"] / us_per_step, 4)})
 
     # Roofline of the dominant kernel: the attention launch of the layer kind with the largest
-    # share of this run's step time (a selection layer's attention launch: its layer minus top-k).
+    # share of this run's step time (a selection layer's attention launch is timed with its top-k switched off).
     launch_us = {kname: d.get("attention_us", d["avg_us"]) for kname, d in per_kind.items()}
     dominant = max(per_kind, key=lambda n: per_kind[n]["layers"] * launch_us[n])
     launch_bytes = {"full": kv_bytes, "select": kv_bytes + score_bytes, "sparse": layer_bytes["sparse"]}[dominant]

@@ -262,8 +262,10 @@ td_status td_plan_launch(const td_ctx *ctx, const td_shape *shape, int32_t layer
  * the vector-ALU kernel with four / eight waves per workgroup in every launch;
  * 4 / 5: the same for the matrix-core kernel; plus 8: the chunk partials of
  * every split launch are folded by a second small launch, plus 16: by the
- * chunk that finishes last, instead of the choice per launch).  The workspace
- * size does not depend on them. */
+ * chunk that finishes last, instead of the choice per launch; plus 32, for
+ * timing only: selection calls stop after their attention launch - out and the
+ * scores are written, positions are not).  The workspace size does not depend
+ * on them. */
 td_status td_set_tuning(td_ctx *ctx, int32_t target_workgroups, int32_t min_chunk_dense,
                         int32_t min_chunk_sparse, int32_t max_splits, int32_t kernel_variant);
 

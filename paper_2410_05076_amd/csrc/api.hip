@@ -18,6 +18,7 @@ struct td_ctx {
     bool counters_dirty = false;     // a launch failed: the ticket counters are cleared before the next one
     int32_t target_workgroups = 0, min_chunk_dense = 0, min_chunk_sparse = 0, max_splits = 0, kernel_variant = 0;
     int32_t merge_mode = 0;          // 0: chosen per launch, 1: a second launch merges the partials, 2: the last chunk does
+    bool attention_only = false;     // measurement: selection calls stop after their attention launch
     char error[256] = {0};
 };
 
@@ -369,6 +370,7 @@ td_status select_tokens(td_ctx *ctx, const td_shape *s, const void *q, const voi
                     fused ? state : nullptr);
         if (st != TD_OK) return st;
     }
+    if (ctx->attention_only) return TD_OK;  // timing of the attention launch alone; the row histograms stay as they are
     hipError_t e = hipSuccess;
     if (!tp.fixed) e = launch_topk_reset(state, all_rows, stream);
     if (e == hipSuccess)
@@ -505,14 +507,19 @@ td_status td_set_tuning(td_ctx *ctx, int32_t target_workgroups, int32_t min_chun
                         int32_t min_chunk_sparse, int32_t max_splits, int32_t kernel_variant) {
     if (!ctx) return TD_ERR_INVALID_ARG;
     if (target_workgroups < 0 || min_chunk_dense < 0 || min_chunk_sparse < 0 || max_splits < 0 ||
-        kernel_variant < 0 || (kernel_variant & 7) > 5 || (kernel_variant >> 3) > 2)
+        kernel_variant < 0 || kernel_variant >= 64 || (kernel_variant & 7) > 5 || ((kernel_variant >> 3) & 3) > 2)
         return fail(ctx, TD_ERR_INVALID_ARG, "%s", "tuning values must be >= 0, kernel_variant one of those the header lists");
     ctx->target_workgroups = target_workgroups;
     ctx->min_chunk_dense = min_chunk_dense;
     ctx->min_chunk_sparse = min_chunk_sparse;
     ctx->max_splits = max_splits;
     ctx->kernel_variant = kernel_variant & 7;
-    ctx->merge_mode = kernel_variant >> 3;
+    ctx->merge_mode = (kernel_variant >> 3) & 3;
+    const bool attention_only = (kernel_variant & 32) != 0;
+    // selection calls that stopped after their attention launch have left their score histograms in the
+    // rows' state: it is cleared before the next launch, whichever way the switch goes
+    if (attention_only || ctx->attention_only) ctx->counters_dirty = true;
+    ctx->attention_only = attention_only;
     return TD_OK;
 }
 
