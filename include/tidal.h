@@ -193,7 +193,12 @@ td_status td_decode_step(td_ctx *ctx, const td_shape *shape, int32_t num_layers,
  * with Eq. 1, to the positions up to and including its own; a token that would sit before the
  * start of the cache (num_new > seq_lens[b]) yields zeros.  Supported: bf16, head_dim 128,
  * a contiguous cache or a paged one with pages of 16 tokens or more, kv_stride_tok <= 2^24
- * elements (TD_ERR_UNSUPPORTED otherwise).
+ * elements (TD_ERR_UNSUPPORTED otherwise).  Why not the rest: the kernel is built around the
+ * matrix core's 16x16x32 bf16 tile - 128 channels are eight of its channel groups, a 16-token
+ * half tile is fetched from one page - and has no vector-ALU twin; for fp32, head_dim 64 or
+ * smaller pages the same attention is td_full_attend over batch * num_new sequences that
+ * share the caches (kv_stride_batch 0 for one sequence) with lengths seq_lens[b] - num_new +
+ * j + 1, which reads the cache once per new token instead of once per call.
  * A prefill over few tokens is bound by the stream of the cache, as a decode step is: the tokens
  * are then cut into chunks whose partial states go through the context's workspace.
  * td_prefill_workspace_bytes is the size that allows every chunk the launch plan would like (0
