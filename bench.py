@@ -79,7 +79,8 @@ def main():
         sys.exit(2)
 
     import torch
-    from paper_2410_05076_amd import tidal, workloads as W
+    from paper_2410_05076_amd import tidal
+    import workloads as W
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     tidal.lib()                      # fail loudly if the HIP library is missing
@@ -483,7 +484,7 @@ def cpu_baseline(w, inputs, torch):
     Small caches: every layer of one decode step.  Large caches: every full and selection layer and
     the first four sparse layers, the sparse time scaled to the number of sparse layers (stated in `sample`)."""
     from oracle import tidal_oracle as O
-    from paper_2410_05076_amd import workloads as W
+    import workloads as W
     qs, Ks, Vs, _, _ = inputs
     layer_bytes = 2 * Ks[0].numel() * Ks[0].element_size()
     whole = layer_bytes * w.num_layers <= 6 * 2**30

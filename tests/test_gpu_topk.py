@@ -141,7 +141,6 @@ def test_repeated_calls_leave_the_row_state_clean(td):
 def test_selection_layer_with_tied_scores_matches_the_oracle_exactly():
     """The fused path (the attention launch bins the scores itself): keys drawn from five vectors give
     scores with five distinct values and thousands of exact ties, more than the candidate list holds."""
-    from paper_2410_05076_amd import workloads as W
     g = torch.Generator().manual_seed(21)
     B, Hq, Hkv, d, N, k = 2, 8, 2, 128, 9000, 3000
     q = torch.randn((B, Hq, d), generator=g).to(torch.bfloat16)

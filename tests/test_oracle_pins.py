@@ -15,7 +15,7 @@ import pytest
 import torch
 
 from oracle import tidal_oracle as O
-from paper_2410_05076_amd import workloads as W
+import workloads as W
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 

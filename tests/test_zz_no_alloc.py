@@ -8,7 +8,7 @@ import torch
 
 from oracle import tidal_oracle as O
 from paper_2410_05076_amd import tidal
-from paper_2410_05076_amd import workloads as W
+import workloads as W
 from parity_util import check_output, check_positions
 from test_gpu_parity import DEV, device_layers, host, say
 
