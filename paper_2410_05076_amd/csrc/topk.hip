@@ -263,9 +263,11 @@ struct EmitShared {
     uint32_t key[kCandMax];
     int32_t idx[kCandMax];
     uint32_t hist[256];
-    uint32_t tot[kTopkWaves];
-    uint32_t bin, remaining, kth, need;
+    uint32_t member[kTopkThreads];  // keys of the candidates in the bucket of the k-th key
+    uint32_t tot[kTopkWaves], lo[kTopkWaves], hi[kTopkWaves];
+    uint32_t bin, remaining, kth, need, members;
 };
+static_assert(sizeof(EmitShared) <= 32 * 1024, "five workgroups per compute unit");
 
 // Exact radix select (4 passes of 8 bits, most significant first) of the `remaining`-th
 // largest key among either the candidate list in LDS or, with FROM_ROW, all scores of the
@@ -312,6 +314,76 @@ __device__ __forceinline__ void radix_select(const Slice &s, EmitShared &sm, uin
     if (tid == 0) {
         sm.kth = prefix;
         sm.need = remaining;
+    }
+    __syncthreads();
+}
+
+// The `remaining`-th largest of the `count` keys in sm.key, and how many of its equals belong to the
+// selection: leaves the key in sm.kth and that number in sm.need.  Every slice of a row does this, so it
+// has to be cheap: the candidates of a row share a histogram bin, i.e. their keys lie in a narrow range, and
+// 256 buckets spread linearly over exactly that range leave one or two keys in the bucket of the k-th -
+// one pass of LDS atomics and one scan instead of a loop over all candidates in every thread (4.5 us for
+// 230 candidates with four workgroups per compute unit) or four passes of a radix select over key bits
+// that are mostly equal.  The bucket's few members are then ranked by counting.  A crowded bucket (many
+// equal keys) takes the radix select.
+__device__ __forceinline__ void select_among_candidates(const Slice &s, EmitShared &sm, uint32_t count, uint32_t remaining,
+                                                        int kth_bin, float center, float inv, int tid, int lane, int wave) {
+    uint32_t kmin = 0xffffffffu, kmax = 0u;
+    for (uint32_t i = tid; i < count; i += kTopkThreads) {
+        kmin = min(kmin, sm.key[i]);
+        kmax = max(kmax, sm.key[i]);
+    }
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o));
+        kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o));
+    }
+    if (lane == 0) {
+        sm.lo[wave] = kmin;
+        sm.hi[wave] = kmax;
+    }
+    sm.hist[tid] = 0;
+    if (tid == 0) sm.members = 0;
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < kTopkWaves; ++w) {
+        kmin = min(kmin, sm.lo[w]);
+        kmax = max(kmax, sm.hi[w]);
+    }
+    const uint32_t range = kmax - kmin;
+    const int shift = range < 256u ? 0 : 24 - __clz(range);  // (range >> shift) < 256
+    for (uint32_t i = tid; i < count; i += kTopkThreads) atomicAdd(&sm.hist[(sm.key[i] - kmin) >> shift], 1u);
+    __syncthreads();
+    const uint32_t cnt = sm.hist[255 - tid];  // thread t owns bucket 255 - t: the scan walks downwards
+    uint32_t total;
+    const uint32_t incl = block_inclusive_scan(cnt, lane, wave, sm.tot, &total);
+    if (incl - cnt < remaining && remaining <= incl) {
+        sm.bin = 255 - tid;
+        sm.remaining = remaining - (incl - cnt);  // rank of the k-th key inside its bucket
+    }
+    __syncthreads();
+    const uint32_t bucket = sm.bin, rank = sm.remaining, population = sm.hist[bucket];
+    if (population > (uint32_t)kTopkThreads) {
+        __syncthreads();  // everybody has read the bucket before the radix select reuses the histogram
+        radix_select<false>(s, sm, count, remaining, kth_bin, center, inv, tid, lane, wave);
+        return;
+    }
+    for (uint32_t i = tid; i < count; i += kTopkThreads) {
+        const uint32_t key = sm.key[i];
+        if (((key - kmin) >> shift) == bucket) sm.member[atomicAdd(&sm.members, 1u)] = key;
+    }
+    __syncthreads();
+    // one member per thread: its rank by counting; equal keys agree on the answer
+    const uint32_t mine = tid < (int)population ? sm.member[tid] : 0u;
+    uint32_t above = 0, same = 0;
+    for (uint32_t i = 0; i < population; ++i) {
+        const uint32_t other = sm.member[i];
+        above += other > mine ? 1u : 0u;
+        same += other == mine ? 1u : 0u;
+    }
+    if (tid < (int)population && above < rank && rank <= above + same) {
+        sm.kth = mine;
+        sm.need = rank - above;
     }
     __syncthreads();
 }
@@ -376,23 +448,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_emit_kernel(const float *sc
             sm.idx[i] = cand_idx[(int64_t)row * kCandMax + i];
         }
         __syncthreads();
-        if (ncand <= (uint32_t)kTopkThreads) {
-            // one candidate per thread: its rank by counting; equal keys agree on the answer
-            const uint32_t mine = tid < (int)ncand ? sm.key[tid] : 0u;
-            uint32_t above = 0, same = 0;
-            for (uint32_t i = 0; i < ncand; ++i) {
-                const uint32_t other = sm.key[i];
-                above += other > mine ? 1u : 0u;
-                same += other == mine ? 1u : 0u;
-            }
-            if (tid < (int)ncand && above < remaining && remaining <= above + same) {
-                sm.kth = mine;
-                sm.need = remaining - above;
-            }
-            __syncthreads();
-        } else {
-            radix_select<false>(s, sm, ncand, remaining, kth_bin, lo, inv, tid, lane, wave);
-        }
+        select_among_candidates(s, sm, ncand, remaining, kth_bin, lo, inv, tid, lane, wave);
         const uint32_t kth = sm.kth;
         for (uint32_t i = tid; i < ncand; i += kTopkThreads) {
             if (sm.idx[i] < slice_start) {

@@ -14,7 +14,7 @@
 namespace tidal {
 
 constexpr int kTopkBins = 2048;         // histogram bins per row
-constexpr int kTopkCandMax = 3840;      // scores of the k-th bin kept per row (with this the emit kernel needs under 32 KB of LDS: five workgroups per CU)
+constexpr int kTopkCandMax = 3584;      // scores of the k-th bin kept per row (with this the emit kernel needs under 32 KB of LDS: five workgroups per CU)
 constexpr int kTopkSliceScores = 4096;  // scores per top-k workgroup
 constexpr int kTopkThreads = 256;       // threads per top-k workgroup
 constexpr int kTopkPerThread = kTopkSliceScores / kTopkThreads;  // 16 consecutive scores per thread

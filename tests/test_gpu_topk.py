@@ -69,11 +69,11 @@ def test_ragged_rows_and_misaligned_stride(td):
 
 
 # ---- boundaries of the kernels' arithmetic: slice edges (4096 scores per workgroup), the candidate
-# list's capacity (3840 per row) and the switch between rank counting and radix select (256
+# list's capacity (3584 per row) and the switch between rank counting and radix select (256
 # candidates), misaligned row starts, many rows.  Seeded and bounded; integer work, bit-exact.
 
 LENGTHS = [255, 256, 257, 4093, 4094, 4095, 4096, 4097, 4099, 8191, 8192, 8193, 12287, 12289, 16385]
-BUDGETS = [1, 2, 255, 256, 257, 3839, 3840, 3841, 4095, 4096, 4097]
+BUDGETS = [1, 2, 255, 256, 257, 3583, 3584, 3585, 4095, 4096, 4097]
 
 
 @pytest.mark.parametrize("n", LENGTHS)
@@ -88,7 +88,7 @@ def test_lengths_and_budgets_around_slice_boundaries(td, n):
             assert torch.equal(run(td, scores, [n], 4, k), expect(scores, [n], 4, k)), (n, stride, k)
 
 
-@pytest.mark.parametrize("cands", [255, 256, 257, 3839, 3840, 3841, 5000])
+@pytest.mark.parametrize("cands", [255, 256, 257, 3583, 3584, 3585, 5000])
 def test_population_of_the_kth_bin_around_the_candidate_list_limits(td, cands):
     """Rows whose k-th bin holds exactly `cands` scores: rank counting up to 256, radix select over the
     list up to its capacity, exact select over the whole row beyond."""
