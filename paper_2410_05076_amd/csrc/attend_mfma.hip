@@ -259,11 +259,12 @@ void attend_mfma_kernel(const AttendParams p) {
                             for (int i = 0; i < 4; ++i)
                                 if (valid[x][i]) s_scores[tok[x][i] - t0] = gs[i];
                         }
-                        if (fused_hist) {
-#pragma unroll
-                            for (int i = 0; i < 4; ++i)
-                                if (valid[x][i]) bin_score(s_hist, gs[i]);
-                        }
+                    }
+                    // every lane of a quad holds the four reduced values: lane i of the first quad bins token i
+                    if (fused_hist && n16 < 4) {
+                        const float mine = n16 == 0 ? gs[0] : n16 == 1 ? gs[1] : n16 == 2 ? gs[2] : gs[3];
+                        const bool ok = n16 == 0 ? valid[x][0] : n16 == 1 ? valid[x][1] : n16 == 2 ? valid[x][2] : valid[x][3];
+                        if (ok) bin_score(s_hist, mine);
                     }
                 } else if (n16 < G) {  // one 16-byte store per head where the row allows it
                     float *dst = score_row + (int64_t)n16 * p.score_stride + tok[x][0];

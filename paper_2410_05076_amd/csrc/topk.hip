@@ -109,8 +109,23 @@ __device__ __forceinline__ void load_slice_early(const float *scores, int64_t ro
     for (int u = 0; u < kPerThread; ++u) v[u] = src4[min((int)blockIdx.x * kSliceGranules + u * kTopkThreads + tid, last4)];
 }
 
+// fn(score, token index, slot) for the slice's scores that lie inside the row; slot = 4 * u + e counts the
+// thread's 16 scores.  A slice that lies wholly inside its row (all but the first and last of a row)
+// skips the per-score bounds.
 template <class Fn>
 __device__ __forceinline__ void for_each_score(const Slice &s, int tid, const float4 (&v)[kPerThread], Fn fn) {
+    const bool interior = 4 * s.first - s.mis >= 0 && 4 * (s.first + kSliceGranules) - s.mis <= s.n;
+    if (interior) {
+#pragma unroll
+        for (int u = 0; u < kPerThread; ++u) {
+            const int j = 4 * (s.first + u * kTopkThreads + tid) - s.mis;
+            fn(v[u].x, j, 4 * u);
+            fn(v[u].y, j + 1, 4 * u + 1);
+            fn(v[u].z, j + 2, 4 * u + 2);
+            fn(v[u].w, j + 3, 4 * u + 3);
+        }
+        return;
+    }
 #pragma unroll
     for (int u = 0; u < kPerThread; ++u) {
         const int i = s.first + u * kTopkThreads + tid;
@@ -118,7 +133,7 @@ __device__ __forceinline__ void for_each_score(const Slice &s, int tid, const fl
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int j = 4 * i - s.mis + e;
-            if (i < s.n4 && j >= 0 && j < s.n) fn(f[e], j);
+            if (i < s.n4 && j >= 0 && j < s.n) fn(f[e], j, 4 * u + e);
         }
     }
 }
@@ -160,18 +175,19 @@ __global__ __launch_bounds__(kTopkThreads) void topk_hist_kernel(const float *sc
     }
     // The map is centred on the middle of the sampled range and scaled so that one sampled width is
     // 64 units: its 2^-8 .. 2^8 span then covers four sampled widths either side of the centre, at a
-    // resolution far below the width.  A degenerate range puts every score into one bin and
-    // leaves the decision to the exact paths.
+    // resolution far below the width.  A degenerate range (all samples equal or closer than the scale
+    // can express, an infinity or a NaN among them) takes the plain map around zero, which stays monotone
+    // for every input; such a row mostly lands in one bin and the exact paths decide.
     const float width = hi - lo;
-    const bool usable = width > 0.f && width < 3.0e38f;
+    const bool usable = width > 1.0e-30f && width < 3.0e38f;
     const float center = usable ? 0.5f * lo + 0.5f * hi : 0.f;
-    const float inv = usable ? 64.f / width : 0.f;
+    const float inv = usable ? 64.f / width : 1.f;
     if (blockIdx.x == 0 && tid == 0) {
         s.state->center = center;
         s.state->inv = inv;
         s.state->ncand = 0;
     }
-    for_each_score(s, tid, v, [&](float f, int) { atomicAdd(&s_hist[topk_bin(f, center, inv)], 1u); });
+    for_each_score(s, tid, v, [&](float f, int, int) { atomicAdd(&s_hist[topk_bin(f, center, inv)], 1u); });
     __syncthreads();
     // two neighbouring bins per 64-bit atomic (a count never carries out of its 32 bits)
     const uint64_t *pairs = reinterpret_cast<const uint64_t *>(s_hist);
@@ -229,13 +245,17 @@ __global__ __launch_bounds__(kTopkThreads) void topk_pick_kernel(const float *sc
     // its scores above the bin are counted, those inside it go to the row's candidate list: the
     // workgroup reserves room for all of its candidates with one atomic (one per candidate would
     // queue up on the row's counter)
-    uint32_t above = 0, cand_mask = 0, slot = 0;  // bit `slot` of the mask: the thread's slot-th score
-    for_each_score(s, tid, v, [&](float f, int) {
-        const int bin = topk_bin(f, lo, inv);
-        above += bin > kth_bin ? 1u : 0u;
-        cand_mask |= (bin == kth_bin ? 1u : 0u) << slot;
-        ++slot;
+    // (a scaled score lies in bin b or above exactly when it is at least topk_bin_floor(b): two compares
+    // per score instead of the bin arithmetic)
+    const float y_cand = topk_bin_floor(kth_bin), y_above = topk_bin_floor(kth_bin + 1);
+    uint32_t above_mask = 0, cand_mask = 0;  // bit `slot` of a mask: the thread's slot-th score
+    for_each_score(s, tid, v, [&](float f, int, int slot) {
+        const float y = topk_scaled(f, lo, inv);
+        const bool a = y >= y_above, c = y >= y_cand;
+        above_mask |= (a ? 1u : 0u) << slot;
+        cand_mask |= (c && !a ? 1u : 0u) << slot;
     });
+    const uint32_t above = (uint32_t)__popc(above_mask);
     const uint32_t mine_c = (uint32_t)__popc(cand_mask);
     uint32_t both;
     const uint32_t excl = block_inclusive_scan(above | (mine_c << 16), lane, wave, s_tot, &both) - (above | (mine_c << 16));
@@ -245,9 +265,9 @@ __global__ __launch_bounds__(kTopkThreads) void topk_pick_kernel(const float *sc
         s_base = (both >> 16) ? atomicAdd(&s.state->ncand, both >> 16) : 0u;
     }
     __syncthreads();
+    if (cand_mask == 0) return;
     uint32_t at = s_base + (excl >> 16);
-    slot = 0;
-    for_each_score(s, tid, v, [&](float f, int j) {
+    for_each_score(s, tid, v, [&](float f, int j, int slot) {
         if ((cand_mask >> slot) & 1u) {
             if (at < (uint32_t)kCandMax) {
                 cand_key[(int64_t)row * kCandMax + at] = order_key(f);
@@ -255,7 +275,6 @@ __global__ __launch_bounds__(kTopkThreads) void topk_pick_kernel(const float *sc
             }
             ++at;
         }
-        ++slot;
     });
 }
 
@@ -491,36 +510,58 @@ __global__ __launch_bounds__(kTopkThreads) void topk_emit_kernel(const float *sc
     __syncthreads();
 
     // compaction in index order: each thread owns 16 consecutive scores, so one prefix sum
-    // over the threads orders the slice
+    // over the threads orders the slice.  A score is selected for certain if it lies above the k-th
+    // bin or inside it above the k-th key; the map is monotone, so inside the bin the float compare
+    // with the k-th score says the same as the compare of the keys.
+    const float y_cand = topk_bin_floor(kth_bin), y_above = topk_bin_floor(kth_bin + 1);
+    const float kth_score = key_to_float(kth);
     uint32_t gt_mask = 0, eq_mask = 0;  // bit 4*u + e
+    const int g0 = s.first + kPerThread * tid;  // the thread's first granule
+    const int j0 = 4 * g0 - s.mis;              // and first token
+    auto classify = [&](float f, int slot) {
+        const float y = topk_scaled(f, lo, inv);
+        const bool inbin = y >= y_cand;
+        const bool gt = y >= y_above || (inbin && f > kth_score);
+        const bool eq = inbin && f == kth_score;  // never true above the bin: the k-th score lies inside it
+        gt_mask |= (gt ? 1u : 0u) << slot;
+        eq_mask |= (eq && !gt ? 1u : 0u) << slot;
+    };
+    if (j0 >= 0 && j0 + 4 * kPerThread <= s.n) {
 #pragma unroll
-    for (int u = 0; u < kPerThread; ++u) {
-        const int i = s.first + kPerThread * tid + u;
-        const float f[4] = {own[u].x, own[u].y, own[u].z, own[u].w};
+        for (int u = 0; u < kPerThread; ++u) {
+            classify(own[u].x, 4 * u);
+            classify(own[u].y, 4 * u + 1);
+            classify(own[u].z, 4 * u + 2);
+            classify(own[u].w, 4 * u + 3);
+        }
+    } else {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int j = 4 * i - s.mis + e;
-            const bool inside = i < s.n4 && j >= 0 && j < s.n;
-            const int bin = topk_bin(f[e], lo, inv);
-            const uint32_t key = order_key(f[e]);
-            const bool gt = inside && (bin > kth_bin || (bin == kth_bin && key > kth));
-            const bool eq = inside && bin == kth_bin && key == kth;
-            gt_mask |= (gt ? 1u : 0u) << (4 * u + e);
-            eq_mask |= (eq ? 1u : 0u) << (4 * u + e);
+        for (int u = 0; u < kPerThread; ++u) {
+            const float f[4] = {own[u].x, own[u].y, own[u].z, own[u].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int j = j0 + 4 * u + e;
+                if (g0 + u < s.n4 && j >= 0 && j < s.n) classify(f[e], 4 * u + e);
+            }
         }
     }
     const uint32_t packed = (uint32_t)__popc(gt_mask) | ((uint32_t)__popc(eq_mask) << 16);
     uint32_t total;
     const uint32_t excl = block_inclusive_scan(packed, lane, wave, sm.tot, &total) - packed;
     uint32_t gtb = gt_base + (excl & 0xffffu), eqb = eq_base + (excl >> 16);
-    const int j0 = 4 * (s.first + kPerThread * tid) - s.mis;
-#pragma unroll
-    for (int t = 0; t < 4 * kPerThread; ++t) {
+    // the thread's selected scores in index order; an output index never leaves the row's k entries,
+    // whatever the scores were (rows with NaNs are binned by their bits and compared as floats, so
+    // their counts need not add up)
+    uint32_t todo = gt_mask | eq_mask;
+    while (todo) {
+        const int t = __builtin_ctz(todo);
+        todo &= todo - 1;
         if ((gt_mask >> t) & 1u) {
-            dst[gtb + min(eqb, need)] = j0 + t;
+            const uint32_t at = gtb + min(eqb, need);
+            if (at < (uint32_t)k) dst[at] = j0 + t;
             ++gtb;
-        } else if ((eq_mask >> t) & 1u) {
-            if (eqb < need) dst[gtb + eqb] = j0 + t;
+        } else {
+            if (eqb < need && gtb + eqb < (uint32_t)k) dst[gtb + eqb] = j0 + t;
             ++eqb;
         }
     }

@@ -30,6 +30,9 @@ def model():
     L.topk_model.restype = ctypes.c_int
     L.topk_model_bin.argtypes, L.topk_model_bin.restype = [ctypes.c_float] * 3, ctypes.c_int
     L.topk_model_key.argtypes, L.topk_model_key.restype = [ctypes.c_float], ctypes.c_uint32
+    L.topk_model_bin_of_scaled.argtypes, L.topk_model_bin_of_scaled.restype = [ctypes.c_float], ctypes.c_int
+    L.topk_model_bin_floor.argtypes, L.topk_model_bin_floor.restype = [ctypes.c_int], ctypes.c_float
+    L.topk_model_key_to_float.argtypes, L.topk_model_key_to_float.restype = [ctypes.c_uint32], ctypes.c_float
     return L
 
 
@@ -58,7 +61,7 @@ def test_bin_map_is_monotone_and_respects_equal_keys(model):
     xs = torch.cat([torch.randn(4000, generator=g) * s for s in (1e-6, 1e-2, 1.0, 30.0, 1e4, 1e30)]
                    + [torch.tensor([0.0, -0.0, 2.0 ** -8, -2.0 ** -8, 255.9999, 256.0, -256.0, 3e38, -3e38,
                                     1e-45, -1e-45, 2.0 ** -8 - 1e-10])])
-    for center, inv in ((0.0, 1.0), (1.5, 64.0 / 7.0), (-40.0, 0.37), (0.0, 0.0), (3e37, 1e-37)):
+    for center, inv in ((0.0, 1.0), (1.5, 64.0 / 7.0), (-40.0, 0.37), (3e37, 1e-37)):
         order = sorted(xs.tolist())
         bins = [model.topk_model_bin(x, center, inv) for x in order]
         assert all(0 <= b < BINS for b in bins)
@@ -73,6 +76,43 @@ def test_bin_map_is_monotone_and_respects_equal_keys(model):
     assert model.topk_model_bin(3e38, 0.0, 1.0) == BINS - 1 and model.topk_model_bin(-3e38, 0.0, 1.0) == 0
     keys = [model.topk_model_key(x) for x in sorted(set(xs.tolist()))]
     assert all(a <= b for a, b in zip(keys, keys[1:]))
+
+
+def neighbours(x):
+    """x and the floats next to it on either side."""
+    if math.isnan(x):
+        return []
+    out = [x]
+    for direction in (-math.inf, math.inf):
+        y = torch.nextafter(torch.tensor(x, dtype=torch.float32), torch.tensor(direction, dtype=torch.float32)).item()
+        out.append(y)
+    return out
+
+
+def test_bin_floor_is_where_the_bin_starts(model):
+    """pick and emit compare a scaled score with topk_bin_floor(b) instead of binning it: for every bin b and
+    every y (tried: the floor itself, its two neighbours, and random values), y >= floor(b) exactly when bin(y) >= b."""
+    g = torch.Generator().manual_seed(5)
+    ys = torch.cat([torch.randn(300, generator=g) * s for s in (1e-4, 3e-3, 0.1, 1.0, 20.0, 300.0)]).tolist()
+    ys += [0.0, -0.0, math.inf, -math.inf, 2.0 ** -8, -2.0 ** -8, 256.0, -256.0, 1e-45, -1e-45]
+    floors = [model.topk_model_bin_floor(b) for b in range(-1, BINS + 2)]
+    assert floors[0] == floors[1] == -math.inf and math.isnan(floors[-1]) and math.isnan(floors[-2])
+    finite = [f for f in floors[2:-2]]
+    assert all(a < b for a, b in zip(finite, finite[1:]))          # strictly increasing: no empty bin
+    for b in range(0, BINS + 1):
+        fl = model.topk_model_bin_floor(b)
+        for y in neighbours(fl) + (ys if b % 97 == 0 else ys[::53]):
+            assert (y >= fl) == (model.topk_model_bin_of_scaled(y) >= b), (b, y, fl)
+    # a NaN lands in some bin by its bits but compares false with every floor; the kernels bound their writes for that
+    assert 0 <= model.topk_model_bin_of_scaled(math.nan) < BINS
+
+
+def test_key_to_float_inverts_the_key(model):
+    g = torch.Generator().manual_seed(6)
+    xs = torch.cat([torch.randn(500, generator=g) * s for s in (1e-30, 1e-3, 1.0, 1e20)]).tolist() + [math.inf, -math.inf, f32(1e-45)]
+    for x in xs:
+        assert model.topk_model_key_to_float(model.topk_model_key(x)) == x
+    assert math.copysign(1.0, model.topk_model_key_to_float(model.topk_model_key(-0.0))) == 1.0
 
 
 LENGTHS = [1, 2, 255, 256, 257, 4093, 4094, 4095, 4096, 4097, 4099, 8191, 8192, 8193, 12289, 20000]

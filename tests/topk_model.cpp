@@ -40,9 +40,9 @@ void bin_map_from_samples(const Row &r, float *center, float *inv) {
         hi = t ? std::max(hi, x) : x;
     }
     const float width = hi - lo;
-    const bool usable = width > 0.f && width < 3.0e38f;
+    const bool usable = width > 1.0e-30f && width < 3.0e38f;
     *center = usable ? 0.5f * lo + 0.5f * hi : 0.f;
-    *inv = usable ? 64.f / width : 0.f;
+    *inv = usable ? 64.f / width : 1.f;
 }
 
 void select_row(const Row &r, int k, bool fused_bins, int cand_max, uint32_t order_seed, int32_t *dst, int *path) {
@@ -68,8 +68,10 @@ void select_row(const Row &r, int k, bool fused_bins, int cand_max, uint32_t ord
         }
         run += hist[b];
     }
-    // ... every slice counts its scores above the bin and appends those inside it; slices run in
-    // an arbitrary order, which decides the order of the list
+    // ... every slice counts its scores above the bin and appends those inside it (as the kernels do:
+    // by comparing the scaled score with the lower ends of the bin and of the next one); slices run
+    // in an arbitrary order, which decides the order of the list
+    const float y_cand = topk_bin_floor(kth_bin), y_above = topk_bin_floor(kth_bin + 1);
     std::vector<int> order(nslices);
     for (int i = 0; i < nslices; ++i) order[i] = i;
     uint32_t rng = order_seed * 2654435761u + 12345u;
@@ -86,9 +88,9 @@ void select_row(const Row &r, int k, bool fused_bins, int cand_max, uint32_t ord
         for (int t = 0; t < kTopkSliceScores; ++t) {
             const int j = first + t;
             if (j < 0 || j >= n) continue;
-            const int bin = topk_bin(r.at(j), center, inv);
-            slice_above[sl] += bin > kth_bin;
-            if (bin == kth_bin) {
+            const float y = topk_scaled(r.at(j), center, inv);
+            slice_above[sl] += y >= y_above;
+            if (y >= y_cand && !(y >= y_above)) {
                 if (ncand < (uint32_t)cand_max) list.push_back(Cand{order_key(r.at(j)), j, 0});
                 ++ncand;
             }
@@ -108,6 +110,7 @@ void select_row(const Row &r, int k, bool fused_bins, int cand_max, uint32_t ord
     uint32_t above = 0;
     for (uint32_t key : keys) above += key > kth;
     const uint32_t need = remaining - above;
+    const float kth_score = key_to_float(kth);
     for (int i = 0; i < k; ++i) dst[i] = -9;
     for (int sl = 0; sl < nslices; ++sl) {
         const int first = topk_slice_first_token(sl, r.mis);
@@ -132,13 +135,14 @@ void select_row(const Row &r, int k, bool fused_bins, int cand_max, uint32_t ord
         for (int t = 0; t < kTopkSliceScores; ++t) {
             const int j = first + t;
             if (j < 0 || j >= n) continue;
-            const int bin = topk_bin(r.at(j), center, inv);
-            const uint32_t key = order_key(r.at(j));
-            if (bin > kth_bin || (bin == kth_bin && key > kth)) {
-                dst[gtb + std::min(eqb, need)] = j;
+            const float f = r.at(j), y = topk_scaled(f, center, inv);
+            const bool inbin = y >= y_cand;
+            if (y >= y_above || (inbin && f > kth_score)) {
+                const uint32_t at = gtb + std::min(eqb, need);
+                if (at < (uint32_t)k) dst[at] = j;
                 ++gtb;
-            } else if (bin == kth_bin && key == kth) {
-                if (eqb < need) dst[gtb + eqb] = j;
+            } else if (inbin && f == kth_score) {
+                if (eqb < need && gtb + eqb < (uint32_t)k) dst[gtb + eqb] = j;
                 ++eqb;
             }
         }
@@ -167,4 +171,7 @@ extern "C" int topk_model(const float *scores, int64_t row_stride, int rows, con
 }
 
 extern "C" int topk_model_bin(float x, float center, float inv) { return topk_bin(x, center, inv); }
+extern "C" int topk_model_bin_of_scaled(float y) { return topk_bin_of_scaled(y); }
+extern "C" float topk_model_bin_floor(int b) { return topk_bin_floor(b); }
+extern "C" float topk_model_key_to_float(uint32_t key) { return key_to_float(key); }
 extern "C" uint32_t topk_model_key(float x) { return order_key(x); }
