@@ -375,7 +375,7 @@ td_status select_tokens(td_ctx *ctx, const td_shape *s, const void *q, const voi
     if (!tp.fixed) e = launch_topk_reset(state, all_rows, stream);
     if (e == hipSuccess)
         e = launch_topk(scores, stride_for_topk, all_rows, s->seq_lens, rows, s->max_seq_len, k, positions, state,
-                        ctx->workspace + w.topk, fused, stream);
+                        ctx->workspace + w.topk, fused, ragged_batch(s), stream);
     if (e != hipSuccess) {
         ctx->counters_dirty = true;
         return fail(ctx, TD_ERR_HIP, "top-k launch failed: %s", hipGetErrorString(e));
@@ -635,7 +635,7 @@ td_status td_topk(td_ctx *ctx, const float *scores, int64_t row_stride, int32_t 
     if (e == hipSuccess && !tp.fixed) e = launch_topk_reset(state, rows, stream);
     if (e == hipSuccess)
         e = launch_topk(scores, row_stride, rows, row_lens, rows_per_len, max_len, k, positions, state,
-                        ctx->workspace + tp.scratch, false, stream);
+                        ctx->workspace + tp.scratch, false, false, stream);
     if (e != hipSuccess) {
         ctx->counters_dirty = true;
         return fail(ctx, TD_ERR_HIP, "top-k launch failed: %s", hipGetErrorString(e));

@@ -125,10 +125,13 @@ hipError_t launch_mean_prob(const float *head_logits, int64_t logit_stride, cons
 // argTopK over rows of fp32 scores.  state: TopkRow[rows], zero on entry and on exit; scratch:
 // topk_scratch_bytes(rows, max_len, k) bytes.  have_histogram: a selection attention launch has
 // already added every score to state[row].hist and set its bin map (one launch follows);
-// otherwise the histogram is built here (two launches).
+// otherwise the histogram is built here (two launches).  lengths_first: the rows' lengths differ
+// a lot (a ragged batch), so a workgroup reads its row's length before it requests any score, and
+// the many slices beyond a row's end cost no memory traffic; otherwise the scores are requested
+// first, which saves one wait for memory in every workgroup.
 hipError_t launch_topk(const float *scores, int64_t row_stride, int32_t rows, const int32_t *row_lens,
                        int32_t rows_per_len, int32_t max_len, int32_t k, int32_t *positions, TopkRow *state,
-                       void *scratch, bool have_histogram, hipStream_t stream);
+                       void *scratch, bool have_histogram, bool lengths_first, hipStream_t stream);
 // Zeroes TopkRow[rows] (state outside the fixed region, before a launch_topk without histogram).
 hipError_t launch_topk_reset(TopkRow *state, int32_t rows, hipStream_t stream);
 

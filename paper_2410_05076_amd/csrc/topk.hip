@@ -145,13 +145,15 @@ __global__ __launch_bounds__(kTopkThreads) void topk_reset_kernel(TopkRow *state
 
 __global__ __launch_bounds__(kTopkThreads) void topk_hist_kernel(const float *scores, int64_t row_stride,
                                                                 const int32_t *row_lens, int rows_per_len,
-                                                                int max_len, int k, TopkRow *states) {
+                                                                int max_len, int k, TopkRow *states,
+                                                                bool lengths_first) {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
     float4 v[kPerThread];
-    load_slice_early(scores, row_stride, max_len, tid, v);
+    if (!lengths_first) load_slice_early(scores, row_stride, max_len, tid, v);
     asm volatile("" ::: "memory");  // requested before the row's length is read
     const Slice s = open_slice(scores, row_stride, row_lens, rows_per_len, max_len, k, states);
     if (!s.active) return;
+    if (lengths_first) load_slice_early(scores, row_stride, max_len, tid, v);
     __shared__ __align__(8) uint32_t s_hist[kBins];
     __shared__ float s_lo[kTopkWaves], s_hi[kTopkWaves];
     // value range from 256 samples of the whole row: the same in every slice of the row
@@ -202,8 +204,13 @@ __global__ __launch_bounds__(kTopkThreads) void topk_pick_kernel(const float *sc
                                                                 const int32_t *row_lens, int rows_per_len,
                                                                 int max_len, int k, TopkRow *states, uint32_t *cand_key,
                                                                 int32_t *cand_idx, uint32_t *slice_above,
-                                                                int slices_per_row) {
+                                                                int slices_per_row, bool lengths_first) {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+    if (lengths_first) {  // a slice beyond its row's end leaves before it requests anything else
+        const int n = min(max(row_lens[blockIdx.y / rows_per_len], 0), max_len);
+        const int mis = (int)((reinterpret_cast<uintptr_t>(scores + (int64_t)blockIdx.y * row_stride) >> 2) & 3);
+        if (k >= n || (int)blockIdx.x * kSliceGranules >= topk_row_granules(mis, n)) return;
+    }
     // the slice's scores, the row histogram and the bin map are requested before the row's length is read
     float4 v[kPerThread];
     load_slice_early(scores, row_stride, max_len, tid, v);
@@ -412,10 +419,18 @@ __global__ __launch_bounds__(kTopkThreads) void topk_emit_kernel(const float *sc
                                                                 int max_len, int k, TopkRow *states,
                                                                 const uint32_t *cand_key, const int32_t *cand_idx,
                                                                 const uint32_t *slice_above, int slices_per_row,
-                                                                int32_t *positions) {
+                                                                int32_t *positions, bool lengths_first) {
     static_assert(kTopkThreads == 256, "one radix bin per thread");
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
     const int row = blockIdx.y;
+    if (lengths_first) {  // a slice beyond its row's end only zeroes its share of the histogram
+        const int n = min(max(row_lens[row / rows_per_len], 0), max_len);
+        const int mis = (int)((reinterpret_cast<uintptr_t>(scores + (int64_t)row * row_stride) >> 2) & 3);
+        if (k < n && (int)blockIdx.x * kSliceGranules >= topk_row_granules(mis, n)) {
+            for (int i = blockIdx.x * kTopkThreads + tid; i < kBins; i += gridDim.x * kTopkThreads) states[row].hist[i] = 0;
+            return;
+        }
+    }
     // Everything whose address follows from the launch arguments alone is requested before the
     // row's length is read, so that the kernel waits for memory once, not three times in a row:
     // the row's state, the first candidates (rarely more than a workgroup's worth), the counts
@@ -581,7 +596,7 @@ hipError_t launch_topk_reset(TopkRow *state, int32_t rows, hipStream_t stream) {
 
 hipError_t launch_topk(const float *scores, int64_t row_stride, int32_t rows, const int32_t *row_lens,
                        int32_t rows_per_len, int32_t max_len, int32_t k, int32_t *positions, TopkRow *state,
-                       void *scratch, bool have_histogram, hipStream_t stream) {
+                       void *scratch, bool have_histogram, bool lengths_first, hipStream_t stream) {
     const int slices = topk_slices(max_len);
     uint32_t *cand_key = static_cast<uint32_t *>(scratch);
     int32_t *cand_idx = reinterpret_cast<int32_t *>(cand_key + (size_t)rows * kCandMax);
@@ -589,11 +604,11 @@ hipError_t launch_topk(const float *scores, int64_t row_stride, int32_t rows, co
     const dim3 grid(slices, rows), block(kTopkThreads);
     if (!have_histogram)
         hipLaunchKernelGGL(topk_hist_kernel, grid, block, 0, stream, scores, row_stride, row_lens, rows_per_len, max_len,
-                           k, state);
+                           k, state, lengths_first);
     hipLaunchKernelGGL(topk_pick_kernel, grid, block, 0, stream, scores, row_stride, row_lens, rows_per_len, max_len,
-                       k, state, cand_key, cand_idx, slice_above, slices);
+                       k, state, cand_key, cand_idx, slice_above, slices, lengths_first);
     hipLaunchKernelGGL(topk_emit_kernel, grid, block, 0, stream, scores, row_stride, row_lens, rows_per_len, max_len,
-                       k, state, cand_key, cand_idx, slice_above, slices, positions);
+                       k, state, cand_key, cand_idx, slice_above, slices, positions, lengths_first);
     return hipGetLastError();
 }
 
