@@ -198,6 +198,12 @@ void plan_chunks(const td_ctx *ctx, const td_shape *s, int mode, int32_t waves, 
     int32_t c = std::max(ceil_div(tokens, want), floor_chunk);
     c = std::max(c, ceil_div(tokens, cap));
     c = (int32_t)align_up((size_t)c, kChunkGranule);
+    // Many chunks per workgroup slot (a ragged batch): chunks whose length is a power of two start
+    // at addresses that are the same modulo a few hundred KiB, and the workgroups that run side by
+    // side then press on the same memory channels (measured on a 16-sequence batch of 8K-64K tokens:
+    // full layer 490 us with chunks of 1024 tokens, 469 with 512, 420-430 with 896, 1152, 1280, 1536 or 1792).
+    // An odd number of 128-token granules keeps the starts apart.
+    if (!sparse && ragged_batch(s) && (c / kChunkGranule) % 2 == 0) c += kChunkGranule;
     if (sparse) c = std::min(c, kSparseChunkMax);
     if (!sparse && s->page_size > 0) c = (int32_t)std::min<int64_t>(c, paged_chunk_limit(s->page_size));
     if (mode == kSelect) c = std::min(c, waves * kScoreStagePerWave);  // the chunk's scores are staged in LDS
@@ -247,7 +253,11 @@ LaunchPlan plan_launch(const td_ctx *ctx, const td_shape *s, int mode, int32_t k
     if (!attend_supports_waves(plan.group, plan.waves)) plan.waves = 4;
     plan_chunks(ctx, s, mode, plan.waves, mode == kSparse ? k : s->max_seq_len, &plan.chunk, &plan.splits);
     const int32_t merge_mode = ctx ? ctx->merge_mode : 0;
-    plan.separate_merge = plan.splits > 1 && merge_mode == 1;
+    // The last chunk of a (sequence, KV head) folds the partials inside the launch - except on a ragged
+    // batch: there a workgroup slot serves several chunks one after the other, and the publish-and-ticket
+    // trips at the end of each of them, slow while the memory system is saturated, keep the slot from
+    // streaming (same batch as above: full layer 519 us, 490 with the fold in a launch of its own).
+    plan.separate_merge = plan.splits > 1 && (merge_mode == 1 || (merge_mode == 0 && mode != kSparse && ragged_batch(s)));
     return plan;
 }
 
