@@ -39,9 +39,11 @@ __device__ __forceinline__ void store_out(void *out, int64_t i, float v) {
 
 // Writes the n scores that the workgroup's waves have put into LDS to dst, 16 bytes per lane
 // where dst allows it.  Every thread of the workgroup calls it.  The stores are write-through
-// (device scope): left to the L2's write-back, 16 MiB of scores cost the launch 14 us at 4 x 128K
-// tokens, written through 4 us (non-temporal stores do the same for the matrix-core kernel and
-// cost the vector-ALU kernel 4 us more than either).
+// (device scope), so the scores do not wait in the L2 for the write-back at the end of the launch:
+// 16 MiB of scores at 4 x 128K tokens cost the launch 21 us that way and 11 us written through, in
+// launches timed back to back on their own (non-temporal stores: the same for the matrix-core kernel,
+// 4 us worse than either for the vector-ALU kernel); inside a whole decode step the difference is
+// within the run-to-run spread.
 template <int T>
 __device__ __forceinline__ void write_staged_scores(const float *staged, int n, float *dst) {
     __syncthreads();
