@@ -42,6 +42,23 @@ def test_ragged_hint_switches_to_many_small_chunks():
     assert ragged.chunk_tokens < even.chunk_tokens and ragged.workgroups > even.workgroups
 
 
+def test_ragged_batches_get_odd_chunk_granules_and_a_fold_launch_of_their_own():
+    """A slot serves several chunks there: chunk starts must not agree modulo a power of two, and no chunk waits for a ticket."""
+    for batch, n, frac in itertools.product((4, 16, 64), (8192, 65536, 131072, 100000), (0.3, 0.6, 0.85)):
+        s = shape(batch=batch, n=n, total=int(batch * n * frac))
+        for kind in (DENSE, SELECT):
+            p = tidal.plan_launch(s, kind, 2048)
+            assert p.waves_per_workgroup == 4
+            if p.chunks_per_row > 1:
+                assert p.merge_launch == 1
+                if p.chunk_tokens < 4 * SCORE_STAGE_PER_WAVE:        # the selection chunk's LDS limit wins over the rule
+                    assert (p.chunk_tokens // 128) % 2 == 1, (batch, n, frac, kind, p.chunk_tokens)
+            assert p.chunk_tokens * p.chunks_per_row >= n and p.chunks_per_row <= SPLITS_MAX
+        assert tidal.plan_launch(s, SPARSE, 2048).merge_launch == 0
+    even = shape(batch=16, n=65536, total=16 * 65536)
+    assert all(tidal.plan_launch(even, kind, 2048).merge_launch == 0 for kind in (DENSE, SELECT, SPARSE))
+
+
 def test_per_head_rule_gives_sparse_layers_one_grid_row_per_query_head():
     s = shape(selection=tidal.SELECT_PER_HEAD)
     assert tidal.plan_launch(s, SPARSE, 2048).grid_rows == 32
