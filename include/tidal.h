@@ -169,7 +169,8 @@ td_status td_sparse_attend(td_ctx *ctx, const td_shape *shape, const void *q, co
 /* argTopK of Alg. 1 on its own: for each of `rows` rows of fp32 scores (row r
  * at scores + r*row_stride, its length row_lens[r / rows_per_len], row_lens a
  * DEVICE int32 array) writes the ascending indices of the min(k, len) largest
- * scores to positions + r*k, -1 padded.  Scores must not be NaN. */
+ * scores to positions + r*k, -1 padded.  Scores must not be NaN: a row with a NaN gets
+ * an unspecified selection (nothing is written outside its k entries). */
 td_status td_topk(td_ctx *ctx, const float *scores, int64_t row_stride, int32_t rows,
                   const int32_t *row_lens, int32_t rows_per_len, int32_t max_len, int32_t k,
                   int32_t *positions, void *hip_stream);
@@ -267,7 +268,10 @@ td_status td_plan_launch(const td_ctx *ctx, const td_shape *shape, int32_t layer
  * the vector-ALU kernel with four / eight waves per workgroup in every launch;
  * 4 / 5: the same for the matrix-core kernel; plus 8: the chunk partials of
  * every split launch are folded by a second small launch, plus 16: by the
- * chunk that finishes last, instead of the choice per launch; plus 32, for
+ * chunk that finishes last, instead of the choice per launch (the last chunk,
+ * except in the full and selection layers of a ragged batch - see
+ * total_seq_len - where a workgroup slot serves several chunks in turn and a
+ * second launch is the faster way); plus 32, for
  * timing only: selection calls stop after their attention launch - out and the
  * scores are written, positions are not).  The workspace size does not depend
  * on them. */
