@@ -161,3 +161,31 @@ def test_selection_layer_with_tied_scores_matches_the_oracle_exactly():
         _, o_pos = O.select(q, K.contiguous(), V, lens, k)
         assert torch.equal(pos.cpu(), o_pos)
     t.close()
+
+
+def test_rows_with_nans_stay_inside_their_own_entries(td):
+    """The header leaves the selection of a row with NaN scores unspecified; what it promises is that nothing is
+    written outside that row's k entries and that the other rows of the call are selected as usual."""
+    g = torch.Generator().manual_seed(8)
+    n, k, rows = 20000, 512, 6
+    scores = torch.randn((rows, n), generator=g)
+    scores[1, ::97] = float("nan")                                        # a few
+    scores[2, :] = float("nan")                                           # all
+    scores[4, 5000:15000] = float("nan")                                  # half, one block
+    scores[4, ::3] = -scores[4, ::3]
+    s = scores.to(DEV)
+    guard = 64
+    buf = torch.full((rows * k + 2 * guard,), -7, dtype=torch.int32, device=DEV)
+    pos = buf[guard:guard + rows * k].view(rows, k)
+    td.topk(s, torch.tensor([n], dtype=torch.int32, device=DEV), rows, k, pos)
+    torch.cuda.synchronize()
+    assert bool((buf[:guard] == -7).all()) and bool((buf[guard + rows * k:] == -7).all())
+    got = pos.cpu()
+    want = expect(scores, [n], rows, k)
+    for r in (0, 3, 5):
+        assert torch.equal(got[r], want[r]), r
+    for r in (1, 2, 4):
+        assert bool(((got[r] >= -1) & (got[r] < n) | (got[r] == -7)).all()), r
+    # the context is as good as new afterwards (row histograms back at zero)
+    clean = torch.randn((rows, n), generator=g)
+    assert torch.equal(run(td, clean, [n], rows, k), expect(clean, [n], rows, k))
