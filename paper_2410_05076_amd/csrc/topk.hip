@@ -19,6 +19,10 @@
 //         uint32 image of the float), derives its output offset from the counts of the
 //         slices before it, and compacts its scores in index order (each thread owns 16
 //         consecutive scores, one prefix sum over the workgroup orders the slice).
+// pick and emit never bin a score: "in bin b or above" is "scaled score >= topk_bin_floor(b)", so a
+// score is classified by two compares with constants, and inside b* by a compare with the k-th
+// score itself (the same order as the keys').  A row's bounds are checked per score only in its
+// first and last slice.
 // If a row has more candidates than the list holds (many equal scores), emit falls back to
 // an exact radix select over the row's scores inside b*: slow, but never wrong.
 // The row histogram is zero when a launch sequence starts and emit leaves it zero again (state
@@ -297,7 +301,7 @@ static_assert(sizeof(EmitShared) <= 32 * 1024, "five workgroups per compute unit
 
 // Exact radix select (4 passes of 8 bits, most significant first) of the `remaining`-th
 // largest key among either the candidate list in LDS or, with FROM_ROW, all scores of the
-// row whose linear bin is kth_bin.  Leaves the key in sm.kth and the tie count in sm.need.
+// row whose bin is kth_bin.  Leaves the key in sm.kth and the tie count in sm.need.
 template <bool FROM_ROW>
 __device__ __forceinline__ void radix_select(const Slice &s, EmitShared &sm, uint32_t count, uint32_t remaining,
                                              int kth_bin, float lo, float inv, int tid, int lane, int wave) {
