@@ -1,4 +1,4 @@
-"""Host-side launch planning (td_plan_launch), no GPU: the decisions the design doc describes, and the
+"""Host-side launch planning (td_plan_launch), no GPU: the documented decisions, and the
 bounds the kernels rely on (chunks per row within the workspace, staged positions / scores /
 block-table entries within their LDS buffers) over a sweep of shapes."""
 import ctypes
