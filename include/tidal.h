@@ -192,19 +192,24 @@ td_status td_decode_step(td_ctx *ctx, const td_shape *shape, int32_t num_layers,
  * sparsely.  q, out: [batch][num_new][num_q_heads][head_dim]; token j of sequence b sits at
  * position seq_lens[b] - num_new + j (its key and value are already in the cache) and attends,
  * with Eq. 1, to the positions up to and including its own; a token that would sit before the
- * start of the cache (num_new > seq_lens[b]) yields zeros.  Supported: bf16, head_dim 128,
- * a contiguous cache or a paged one with pages of 16 tokens or more, kv_stride_tok <= 2^24
- * elements (TD_ERR_UNSUPPORTED otherwise).  Why not the rest: the kernel is built around the
- * matrix core's 16x16x32 bf16 tile - 128 channels are eight of its channel groups, a 16-token
- * half tile is fetched from one page - and has no vector-ALU twin; for fp32, head_dim 64 or
- * smaller pages the same attention is td_full_attend over batch * num_new sequences that
- * share the caches (kv_stride_batch 0 for one sequence) with lengths seq_lens[b] - num_new +
- * j + 1, which reads the cache once per new token instead of once per call.
- * A prefill over few tokens is bound by the stream of the cache, as a decode step is: the tokens
- * are then cut into chunks whose partial states go through the context's workspace.
- * td_prefill_workspace_bytes is the size that allows every chunk the launch plan would like (0
- * when it wants none); with a smaller workspace the call uses fewer chunks, down to one (correct,
- * slower when num_new * num_q_heads / num_kv_heads rows are too few to fill the GPU). */
+ * start of the cache (num_new > seq_lens[b]) yields zeros.
+ * Two paths.  bf16 with head_dim 128, a contiguous cache or a paged one with pages of 16 tokens
+ * or more, kv_stride_tok <= 2^24 elements: a kernel on the matrix cores that reads the cache
+ * once per call.  A prefill over few tokens is bound by the stream of the cache, as a decode step
+ * is: the tokens are then cut into chunks whose partial states go through the context's workspace.
+ * Every other shape the decode calls accept (fp32, head_dim 64, smaller pages, longer token
+ * strides): the plain path - the matrix-core kernel is built around the 16x16x32 bf16 tile (128
+ * channels are eight of its channel groups, a 16-token half tile comes from one page) and has no
+ * vector-ALU twin, so these shapes run the full-attention kernel of the decode step with one grid
+ * row block per new token, each attending to the positions up to its own.  That reads the cache
+ * once per new token instead of once per call: right for the short corrections the step is meant
+ * for, slow for long ones.
+ * td_prefill_workspace_bytes is the size that allows every chunk the launch plan would like
+ * (matrix-core path; 0 when it wants none) or all new tokens of all sequences in one launch
+ * (plain path).  With a smaller workspace the call uses fewer chunks, down to one (correct, slower
+ * when num_new * num_q_heads / num_kv_heads rows are too few to fill the GPU), or runs of as many
+ * new tokens of one sequence per launch as fit; TD_ERR_WORKSPACE if the plain path has no room
+ * for a single token (td_workspace_bytes(shape, 0) is always enough). */
 size_t td_prefill_workspace_bytes(const td_shape *shape, int32_t num_new);
 td_status td_prefill_attend(td_ctx *ctx, const td_shape *shape, int32_t num_new, const void *q,
                             const void *K, const void *V, void *out, void *hip_stream);

@@ -147,7 +147,9 @@ hipError_t clear_counters(char *workspace, size_t counters, size_t topk_rows, hi
     return hipGetLastError();
 }
 
-Workspace workspace_layout(const td_shape *s, int32_t k) {
+// splits: chunks per (sequence, KV head) that the partials have to hold; every decode call reserves kSplitsMax,
+// so that the layout does not depend on the launch plan.
+Workspace workspace_layout(const td_shape *s, int32_t k, int32_t splits = kSplitsMax) {
     Workspace w;
     const size_t heads = (size_t)s->batch * s->num_q_heads;
     const int32_t rows = s->batch * selection_rows(s);
@@ -158,8 +160,8 @@ Workspace workspace_layout(const td_shape *s, int32_t k) {
     w.topk_state = tp.state;
     w.topk = k > 0 ? tp.scratch : kFixedBytes;
     w.part_acc = align_up(w.topk + (k > 0 ? topk_scratch_bytes(rows, s->max_seq_len, k) : 0), 256);
-    w.part_ml = align_up(w.part_acc + heads * kSplitsMax * s->head_dim * sizeof(float), 256);
-    w.scores = align_up(w.part_ml + heads * kSplitsMax * 2 * sizeof(float), 256);
+    w.part_ml = align_up(w.part_acc + heads * splits * s->head_dim * sizeof(float), 256);
+    w.scores = align_up(w.part_ml + heads * splits * 2 * sizeof(float), 256);
     const size_t score_bytes = k > 0 ? (size_t)rows * w.score_stride * sizeof(float) : 0;
     // the mean-of-probabilities rule also keeps every head's logits and final softmax statistics
     const bool two_pass = k > 0 && s->selection == TD_SELECT_GROUP_MEAN_PROB;
@@ -261,13 +263,27 @@ LaunchPlan plan_launch(const td_ctx *ctx, const td_shape *s, int mode, int32_t k
     return plan;
 }
 
+// Rows of a prefill served by the decode kernel (AttendParams): s->batch is then the number of row blocks.
+struct PrefillRows {
+    int32_t new_per_seq, new_first, num_new, cache_first;
+};
+
 td_status attend(td_ctx *ctx, const td_shape *s, int mode, const void *q, const void *K, const void *V,
                  const int32_t *positions, int32_t k, float *scores, int64_t score_stride, void *out,
                  hipStream_t stream, const void *k_new = nullptr, const void *v_new = nullptr,
-                 int32_t score_rule = -1, float *ml_out = nullptr, TopkRow *fused_rows = nullptr) {
-    const Workspace w = workspace_layout(s, mode == kDense ? 0 : k);
+                 int32_t score_rule = -1, float *ml_out = nullptr, TopkRow *fused_rows = nullptr,
+                 const PrefillRows *prefill = nullptr) {
+    const LaunchPlan plan = plan_launch(ctx, s, mode, k);
+    // a prefill through this kernel may have many more rows than a decode step: its partials take what the plan needs
+    const Workspace w = workspace_layout(s, mode == kDense ? 0 : k, prefill ? plan.splits : kSplitsMax);
     AttendParams p;
     memset(&p, 0, sizeof p);
+    if (prefill) {
+        p.new_per_seq = prefill->new_per_seq;
+        p.new_first = prefill->new_first;
+        p.num_new = prefill->num_new;
+        p.cache_first = prefill->cache_first;
+    }
     p.q = q; p.K = K; p.V = V; p.out = out;
     p.k_new = k_new; p.v_new = v_new;
     p.seq_lens = s->seq_lens;
@@ -296,7 +312,6 @@ td_status attend(td_ctx *ctx, const td_shape *s, int mode, const void *q, const 
     p.max_seq_len = s->max_seq_len;
     p.k = k;
     p.scale = s->sm_scale > 0.f ? s->sm_scale : 1.0f / sqrtf((float)s->head_dim);
-    const LaunchPlan plan = plan_launch(ctx, s, mode, k);
     if (plan.grid_rows_per_seq != s->num_kv_heads) {
         // one grid row per query head, each gathering its own rho from KV head (row / group)
         p.kv_div = s->num_q_heads / s->num_kv_heads;
@@ -306,7 +321,7 @@ td_status attend(td_ctx *ctx, const td_shape *s, int mode, const void *q, const 
     p.num_splits = plan.splits;
     p.separate_merge = plan.separate_merge ? 1 : 0;
     const int group = plan.group, waves = plan.waves;
-    const bool mfma = plan.matrix_core;
+    const bool mfma = plan.matrix_core && !prefill;  // only the vector-ALU kernel knows prefill rows
     if (ctx->counters_dirty) {  // an earlier launch on this context failed: start from zeroed tickets
         const hipError_t ce = clear_counters(ctx->workspace, kCountersMax, kTopkFusedRows, stream);
         if (ce != hipSuccess) return fail(ctx, TD_ERR_HIP, "clearing the ticket counters failed: %s", hipGetErrorString(ce));
@@ -562,11 +577,84 @@ size_t prefill_ml_bytes(const PrefillPlan &pl, const td_shape *s) {
     const size_t slots = (size_t)pl.row_blocks * s->batch * s->num_kv_heads * pl.chunks * pl.rows_per_wg;
     return align_up(slots * 2 * sizeof(float), 256);
 }
+
+// The matrix-core prefill kernel takes bf16 with head_dim 128, contiguous or in pages of 16 tokens and more,
+// with token strides its 32-bit lane offsets can express.
+bool prefill_kernel_takes(const td_shape *s) {
+    return s->dtype == TD_BF16 && s->head_dim == 128 && (s->page_size == 0 || s->page_size >= 16) &&
+           s->kv_stride_tok <= (int64_t)1 << 24;
+}
+
+// Every other shape goes through the vector-ALU decode kernel in full mode: one row block of the grid per new
+// token, each attending to the positions up to its own (AttendParams::new_per_seq).  The cache is then read
+// once per new token - it is the plain path, for shapes outside the matrix-core kernel's reach.
+// A launch takes as many row blocks as the grid, the ticket counters and the workspace allow: all
+// batch * num_new at once if they fit, else runs of new tokens of one sequence at a time.
+struct PlainPrefill {
+    int32_t rows;        // row blocks per launch
+    bool whole;          // one launch covers every sequence
+    size_t workspace;    // bytes such a launch needs
+};
+size_t plain_prefill_bytes(const td_ctx *ctx, const td_shape *s, int32_t rows) {
+    td_shape rs = *s;
+    rs.batch = rows;
+    rs.total_seq_len = 0;
+    return workspace_layout(&rs, 0, plan_launch(ctx, &rs, kDense, 0).splits).total;
+}
+PlainPrefill plan_plain_prefill(const td_ctx *ctx, const td_shape *s, int32_t num_new, size_t avail) {
+    const int64_t most = std::min<int64_t>(65535, kCountersMax / s->num_kv_heads);  // grid.z, one ticket counter per (row block, KV head)
+    PlainPrefill pp;
+    const int64_t all = (int64_t)s->batch * num_new;
+    if (all <= most && plain_prefill_bytes(ctx, s, (int32_t)all) <= avail) {
+        pp.rows = (int32_t)all;
+        pp.whole = true;
+        pp.workspace = plain_prefill_bytes(ctx, s, pp.rows);
+        return pp;
+    }
+    pp.whole = false;
+    pp.rows = (int32_t)std::min<int64_t>(num_new, most);
+    while (pp.rows > 1 && plain_prefill_bytes(ctx, s, pp.rows) > avail) pp.rows = (pp.rows + 1) / 2;
+    pp.workspace = plain_prefill_bytes(ctx, s, pp.rows);
+    return pp;
+}
+
+td_status plain_prefill(td_ctx *ctx, const td_shape *s, int32_t num_new, const void *q, const void *K, const void *V,
+                        void *out, hipStream_t stream) {
+    const PlainPrefill pp = plan_plain_prefill(ctx, s, num_new, ctx->workspace_bytes);
+    if (pp.workspace > ctx->workspace_bytes)
+        return fail(ctx, TD_ERR_WORKSPACE, "%s", "workspace is smaller than td_workspace_bytes(shape, 0): not even one new token fits");
+    td_shape rs = *s;
+    rs.batch = pp.rows;
+    rs.total_seq_len = 0;
+    PrefillRows pr;
+    pr.num_new = num_new;
+    if (pp.whole) {
+        pr.new_per_seq = num_new;
+        pr.new_first = 0;
+        pr.cache_first = 0;
+        return attend(ctx, &rs, kDense, q, K, V, nullptr, 0, nullptr, 0, out, stream, nullptr, nullptr, -1, nullptr, nullptr, &pr);
+    }
+    const size_t row_bytes = (size_t)s->num_q_heads * s->head_dim * (s->dtype == TD_BF16 ? 2 : 4);
+    for (int32_t b = 0; b < s->batch; ++b) {
+        for (int32_t first = 0; first < num_new; first += pp.rows) {
+            rs.batch = std::min(pp.rows, num_new - first);
+            pr.new_per_seq = rs.batch;
+            pr.new_first = first;
+            pr.cache_first = b;
+            const size_t at = ((size_t)b * num_new + first) * row_bytes;
+            const td_status st = attend(ctx, &rs, kDense, static_cast<const char *>(q) + at, K, V, nullptr, 0, nullptr, 0,
+                                        static_cast<char *>(out) + at, stream, nullptr, nullptr, -1, nullptr, nullptr, &pr);
+            if (st != TD_OK) return st;
+        }
+    }
+    return TD_OK;
+}
 }  // namespace
 
 size_t td_prefill_workspace_bytes(const td_shape *shape, int32_t num_new) {
     td_status code;
     if (shape_problem(shape, 0, &code) || num_new < 1 || num_new > shape->max_seq_len) return 0;
+    if (!prefill_kernel_takes(shape)) return plan_plain_prefill(nullptr, shape, num_new, ~(size_t)0).workspace;
     const PrefillPlan pl = prefill_plan_for(shape, num_new, ~(size_t)0);
     return pl.chunks > 1 ? align_up(kFixedBytes + 256 + pl.part_bytes, 256) : 0;
 }
@@ -577,10 +665,7 @@ td_status td_prefill_attend(td_ctx *ctx, const td_shape *shape, int32_t num_new,
     if (st != TD_OK) return st;
     if (num_new < 1 || num_new > shape->max_seq_len)
         return fail(ctx, TD_ERR_INVALID_ARG, "%s", "num_new outside [1, max_seq_len]");
-    if (shape->dtype != TD_BF16 || shape->head_dim != 128 || (shape->page_size != 0 && shape->page_size < 16))
-        return fail(ctx, TD_ERR_UNSUPPORTED, "%s", "prefill attention needs bf16, head_dim 128 and, if paged, pages of 16 tokens or more");
-    if (shape->kv_stride_tok > (int64_t)1 << 24)  // the kernel adds lane offsets of up to 16 rows in 32 bits
-        return fail(ctx, TD_ERR_UNSUPPORTED, "%s", "prefill attention needs kv_stride_tok <= 2^24 elements");
+    if (!prefill_kernel_takes(shape)) return plain_prefill(ctx, shape, num_new, q, K, V, out, static_cast<hipStream_t>(hip_stream));
     PrefillParams p;
     memset(&p, 0, sizeof p);
     p.q = q; p.K = K; p.V = V; p.out = out;

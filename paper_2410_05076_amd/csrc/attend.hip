@@ -98,6 +98,9 @@ void attend_split_kernel(const AttendParams p) {
     const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
     const int r = lane / LPR, c = lane % LPR;
+    // the sequence whose cache row block b reads: b itself, except when the rows are the new tokens of a prefill
+    const bool prefill = MODE == kDense && p.new_per_seq > 0;
+    const int bc = prefill ? p.cache_first + b / p.new_per_seq : b;
 
     // A workgroup owns p.chunk consecutive tokens (a multiple of the 128-token granule): a
     // contiguous stream per workgroup keeps TLB and DRAM-page locality.
@@ -131,7 +134,7 @@ void attend_split_kernel(const AttendParams p) {
     int tstage[kTablePerThread];
     const int first_page = PAGED ? t0 >> p.page_shift : 0;
     if constexpr (kStageTable) {
-        const int32_t *table = p.block_table + (int64_t)b * p.bt_stride + first_page;
+        const int32_t *table = p.block_table + (int64_t)bc * p.bt_stride + first_page;
         const int pages = ((min(p.max_seq_len, t0 + p.chunk) - 1) >> p.page_shift) - first_page + 1;
 #pragma unroll
         for (int i = 0; i < kTablePerThread; ++i) {
@@ -141,7 +144,16 @@ void attend_split_kernel(const AttendParams p) {
     }
     asm volatile("" ::: "memory");  // the loads above stay above the branch on the sequence length
 
-    const int N = min(max(p.seq_lens[b], 0), p.max_seq_len);
+    int N = min(max(p.seq_lens[bc], 0), p.max_seq_len);
+    if (prefill) {
+        // the new token's own position + 1; a token before the start of the cache yields zeros
+        N = N - p.num_new + p.new_first + b % p.new_per_seq + 1;
+        if (N <= 0) {
+            if (split == 0)
+                for (int i = threadIdx.x; i < G * D; i += T) store_out<DT>(p.out, ((int64_t)b * p.num_q_heads + g * G) * D + i, 0.f);
+            return;
+        }
+    }
     const int n_tok = MODE == kSparse ? (N > 0 ? p.k : 0) : N;
     if (t0 >= n_tok) return;
     const int t1 = min(n_tok, t0 + p.chunk);
@@ -157,7 +169,7 @@ void attend_split_kernel(const AttendParams p) {
                 s_pos[j] = pstage[i];
                 if constexpr (PAGED) {  // the page of the row that the gather will read (row 0 if masked)
                     const int pj = pstage[i] >= 0 && pstage[i] < N ? pstage[i] : 0;
-                    s_page[j] = p.block_table[(int64_t)b * p.bt_stride + (pj >> p.page_shift)];
+                    s_page[j] = p.block_table[(int64_t)bc * p.bt_stride + (pj >> p.page_shift)];
                 }
             }
         }
@@ -177,7 +189,7 @@ void attend_split_kernel(const AttendParams p) {
 
     const int64_t row_bytes = p.stride_tok * E::kBytes;
     const int64_t head_off =
-        ((PAGED ? 0 : (int64_t)b * p.stride_batch) + (int64_t)(g / p.kv_div) * p.stride_head) * E::kBytes + c * 16;
+        ((PAGED ? 0 : (int64_t)bc * p.stride_batch) + (int64_t)(g / p.kv_div) * p.stride_head) * E::kBytes + c * 16;
     const int64_t page_bytes = p.stride_batch * E::kBytes;  // paged only
     const int slot_mask = PAGED ? (1 << p.page_shift) - 1 : 0;
     const char *Kb = (const char *)p.K + head_off;

@@ -66,6 +66,10 @@ struct AttendParams {
     int32_t chunk;       // tokens per workgroup
     int32_t num_splits;  // grid.x
     int32_t separate_merge;  // 1: the chunks only leave their partials and launch_merge folds them
+    // Prefill through the decode kernel (vector-ALU kernel, full mode only): grid row block b is not a
+    // sequence but new token new_first + b % new_per_seq of sequence cache_first + b / new_per_seq, which
+    // attends to the positions up to its own, seq_lens[sequence] - num_new + token.  0: a decode step.
+    int32_t new_per_seq, new_first, num_new, cache_first;
     float scale;
 };
 

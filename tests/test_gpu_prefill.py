@@ -108,16 +108,82 @@ def test_chunked_prefill_of_a_ragged_batch_with_a_sequence_shorter_than_the_new_
     td.close()
 
 
-def test_prefill_rejects_unsupported_shapes():
-    w = W.workload("c1", context=100, k=8)               # fp32, head_dim 64
+def run_plain_prefill(w, num_new, page_size=0, workspace="whole", seed=9):
+    """Shapes outside the matrix-core kernel (fp32, head_dim 64, pages under 16 tokens) take the library's plain
+    path; workspace: "whole" = td_prefill_workspace_bytes (one launch for all new tokens), "some" = room for about
+    a quarter of them (runs of new tokens, one sequence at a time), or a byte count.  Sequences shorter than num_new are compared
+    token by token: zeros before the start of the cache, the oracle on the rest."""
+    (_, K, V), = device_layers(w, [0])
+    g = torch.Generator(device=DEV).manual_seed(seed)
+    q = torch.randn((w.batch, num_new, w.num_q_heads, w.head_dim), generator=g, device=DEV).to(w.torch_dtype)
+    lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=DEV)
+    Kd, Vd = K, V
+    if page_size:
+        table, num_pages = W.page_table(w, page_size, device=DEV)
+        _, Kd = W.paginate(K, table, num_pages, page_size)
+        _, Vd = W.paginate(V, table, num_pages, page_size)
+        shape = tidal.make_paged_shape(q[:, 0].contiguous(), Kd, table, lens, w.max_seq_len)
+    else:
+        shape = tidal.make_shape(q[:, 0].contiguous(), K, lens)
+    if workspace == "whole":
+        assert tidal.lib().td_prefill_workspace_bytes(shape, num_new) > 0
+        td = tidal.Tidal(shape, 0, prefill_new=num_new)
+    elif workspace == "some":
+        whole = tidal.lib().td_prefill_workspace_bytes(shape, num_new)
+        base = tidal.lib().td_prefill_workspace_bytes(shape, 1)
+        td = tidal.Tidal(shape, 0, workspace_bytes=base + (whole - base) // 4)
+    else:
+        td = tidal.Tidal(shape, 0, workspace_bytes=workspace)
+    out = torch.full_like(q, float("nan"))
+    say("plain prefill %s %s d%d P=%d page %d workspace %s" % (w.name, w.dtype, w.head_dim, num_new, page_size, workspace))
+    td.prefill_attend(shape, q, Kd, Vd, out)
+    torch.cuda.synchronize()
+    for b, n in enumerate(w.seq_lens):
+        missing = max(0, num_new - n)
+        assert (out[b, :missing] == 0).all(), "tokens before the start of sequence %d" % b
+        ref = O.prefill(host(q[b:b + 1, missing:]).contiguous(), host(K[b:b + 1]), host(V[b:b + 1]), [n])
+        check_output(out[b:b + 1, missing:], ref, "plain prefill, sequence %d" % b)
+    # the ticket counters are back at zero: the context serves a decode call as before (where its workspace
+    # has room for one), and the same prefill again gives the same bits
+    if workspace == "whole":
+        out1 = torch.full_like(q[:, 0], float("nan"))
+        td.full_attend(shape, q[:, 0].contiguous(), Kd, Vd, out1)
+        torch.cuda.synchronize()
+        check_output(out1, O.full(host(q[:, 0]).contiguous(), host(K), host(V), w.seq_lens), "decode call afterwards")
+    again = torch.full_like(q, float("nan"))
+    td.prefill_attend(shape, q, Kd, Vd, again)
+    torch.cuda.synchronize()
+    assert torch.equal(again, out)
+    td.close()
+
+
+@pytest.mark.parametrize("name,over,num_new,page_size", [
+    ("c1", dict(context=300, k=8), 1, 0),                                          # fp32, head_dim 64: one token
+    ("c1", dict(context=300, k=8), 40, 0),
+    ("c1", dict(seq_lens=(300, 5, 120), k=8), 16, 0),                              # a sequence shorter than the new tokens
+    ("c1", dict(context=700, k=8, dtype="bf16"), 33, 0),                           # bf16, head_dim 64
+    ("c2", dict(context=600, k=8, dtype="f32"), 21, 0),                            # fp32, head_dim 128
+    ("c3", dict(context=500, k=8, head_dim=64), 9, 0),                             # G = 1
+    ("c2", dict(context=500, k=16), 33, 8),                                        # bf16, head_dim 128, pages of 8 tokens
+    ("c2", dict(seq_lens=(500, 90), k=16), 12, 4),                                 # pages of 4, two sequences
+    ("c1", dict(seq_lens=(3000, 2100), k=8), 24, 1),                               # pages of 1: every token its own page
+    ("c1", dict(context=9000, k=8), 3, 0),                                         # few rows: the tokens are cut into chunks
+])
+@pytest.mark.parametrize("workspace", ["whole", "some"])
+def test_plain_prefill_for_shapes_outside_the_matrix_core_kernel(name, over, num_new, page_size, workspace):
+    run_plain_prefill(W.workload(name, **over), num_new, page_size=page_size, workspace=workspace)
+
+
+def test_plain_prefill_with_a_workspace_too_small_for_one_token():
+    w = W.workload("c1", context=100, k=8)
     (q1, K, V), = device_layers(w, [0])
     lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=DEV)
     shape = tidal.make_shape(q1, K, lens)
-    td = tidal.Tidal(shape, 0)
+    td = tidal.Tidal(shape, 0, workspace_bytes=4096)
     q = q1[:, None].contiguous()
     with pytest.raises(tidal.TidalError) as e:
         td.prefill_attend(shape, q, K, V, torch.empty_like(q))
-    assert e.value.status == tidal.ERR_UNSUPPORTED
+    assert e.value.status == tidal.ERR_WORKSPACE
     td.close()
 
 
@@ -245,21 +311,6 @@ def test_prefill_over_a_paged_cache(name, over, num_new, page_size, layout):
     Kl = O.gather_pages(host(Kv), t, w.seq_lens, w.max_seq_len)
     Vl = O.gather_pages(host(Vv), t, w.seq_lens, w.max_seq_len)
     check_output(out, O.prefill(host(q), Kl, Vl, w.seq_lens), "paged prefill")
-    td.close()
-
-
-def test_prefill_rejects_pages_shorter_than_sixteen_tokens():
-    w = W.workload("c2", context=500, k=16)
-    (q1, K, V), = device_layers(w, [0])
-    table, num_pages = W.page_table(w, 8, device=DEV)
-    Kp, Kv = W.paginate(K, table, num_pages, 8)
-    lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=DEV)
-    shape = tidal.make_paged_shape(q1, Kv, table, lens, w.max_seq_len)
-    td = tidal.Tidal(shape, 0)
-    q = q1[:, None].contiguous()
-    with pytest.raises(tidal.TidalError) as e:
-        td.prefill_attend(shape, q, Kv, Kv, torch.empty_like(q))
-    assert e.value.status == tidal.ERR_UNSUPPORTED
     td.close()
 
 
