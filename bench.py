@@ -432,8 +432,16 @@ def prefill_bench(args, torch, tidal, W, dev):
     esize = 2 if w.dtype == "bf16" else 4
     kv_bytes = 2.0 * w.num_kv_heads * w.head_dim * esize * sum(w.seq_lens)
     td.close()
+    # shapes outside the matrix-core kernel take the library's plain path: the vector-ALU full-attention kernel,
+    # one grid row block per new token, which streams the cache once per new token
+    plain = w.dtype != "bf16" or w.head_dim != 128 or (args.page_size and args.page_size < 16)
+    if plain:
+        rate = kv_bytes / (us * 1e-6) / 1e9
+        roof = {"kernel": "attend_split_kernel (plain path: the cache is read once per new token, %d times here)" % P,
+                "bound": "hbm", "achieved": round(rate, 1), "peak": 8000.0, "unit": "GB/s", "frac": round(rate / 8000.0, 4),
+                "traffic": None, "bytes_per_launch": kv_bytes, "flop_per_launch": flop}
     # whichever of the two floors is higher for this P names the bound
-    if kv_bytes / 8.0e12 > flop / 2.5e15:
+    elif kv_bytes / 8.0e12 > flop / 2.5e15:
         rate = kv_bytes / (us * 1e-6) / 1e9
         roof = {"kernel": "prefill_mfma_kernel + prefill_merge_kernel", "bound": "hbm", "achieved": round(rate, 1),
                 "peak": 8000.0, "unit": "GB/s", "frac": round(rate / 8000.0, 4), "traffic": None,
