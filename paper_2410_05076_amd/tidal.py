@@ -185,7 +185,8 @@ class Tidal:
             raise TidalError(st, "td_create failed")
 
     def close(self):
-        if getattr(self, "_ctx", None):
+        # (at interpreter shutdown the module's globals may already be gone: then the process's exit frees the context)
+        if getattr(self, "_ctx", None) and lib is not None:
             lib().td_destroy(self._ctx)
             self._ctx = None
 
