@@ -250,6 +250,11 @@ LaunchPlan plan_launch(const td_ctx *ctx, const td_shape *s, int mode, int32_t k
     // 11.5 us; groups of four lose, 9.9 vs 9.6 us.)
     plan.waves = mode != kSparse && !ragged_batch(s) ? 8 : 4;
     if (mode == kSparse && plan.matrix_core && plan.group == 8) plan.waves = 8;
+    // Larger gathers also do better with eight waves (half as many partials, one tile per wave and iteration):
+    // measured four / eight waves, us per sparse layer - 32 rows: k 1024 10.5 / 11.0, k 2048 14.9 / 13.5,
+    // k 4096 20.5 / 19.1, k 16384 54.2 / 51.8; 8 rows: k 2048 9.8 / 10.1, k 4096 12.9 / 12.2, k 8192 20.0 / 14.5;
+    // 128 ragged rows, k 2048: 30.4 / 29.7; 32 rows of one head each (vector-ALU kernel), k 4096: 18.1 / 17.75.
+    if (mode == kSparse && (k >= 4096 || (int64_t)s->batch * plan.grid_rows_per_seq * k >= 65536)) plan.waves = 8;
     if (kv == 2 || kv == 4) plan.waves = 4;
     if (kv == 3 || kv == 5) plan.waves = 8;
     if (!attend_supports_waves(plan.group, plan.waves)) plan.waves = 4;

@@ -29,6 +29,10 @@ def test_benchmark_shapes_get_the_documented_plans():
     p = tidal.plan_launch(c3, SELECT, 4096)
     assert (p.matrix_core, p.waves_per_workgroup) == (0, 8)
     assert tidal.plan_launch(c3, SPARSE, 4096).matrix_core == 0
+    assert tidal.plan_launch(c3, SPARSE, 4096).waves_per_workgroup == 8                 # large gathers: eight waves
+    c5 = shape(batch=4, n=131072)
+    assert [tidal.plan_launch(c5, SPARSE, k).waves_per_workgroup for k in (256, 1024, 2048, 4096, 16384)] == [4, 4, 8, 8, 8]
+    assert tidal.plan_launch(c2, SPARSE, 4096).waves_per_workgroup == 8
     c6 = shape(hq=64, hkv=8)
     assert all(tidal.plan_launch(c6, kind, 2048).matrix_core == 1 for kind in (DENSE, SELECT, SPARSE))
     f32 = shape(dtype=tidal.F32)
